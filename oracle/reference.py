@@ -1,0 +1,215 @@
+"""Python face of the CPU oracle (ctypes over oracle/adahop_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this module.  It
+never touches the GPU library and the GPU library never touches it.
+
+Operands are passed as the 2-D uint16 array of bf16 bit patterns *as stored* plus a flag:
+k_contig=True means the array is [outer, K]; k_contig=False means it is [K, outer] (paper Eq. 1-3:
+the forward product has both operands K-contiguous, dgrad has a K-strided B, wgrad has both K-strided).
+
+The whole-path function `adahop_gemm` strings the steps together in the order of the paper's
+pipeline (App. F: FOID -> IHT + quantise on the residual -> MXFP4 product + BF16 outlier product ->
+sum), for the five strategies none / IHT / IHT+OE-row (Eq. 7) / IHT+OE-col (Eq. 8) / IHT+OE-K.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+NONE, IHT, IHT_OE_ROW, IHT_OE_COL, IHT_OE_K = range(5)
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build())
+        _lib.orc_e8m0_from_amax.restype = C.c_uint8
+        _lib.orc_e8m0_from_amax.argtypes = [C.c_float]
+        _lib.orc_e2m1_encode.restype = C.c_uint8
+        _lib.orc_e2m1_encode.argtypes = [C.c_float]
+        _lib.orc_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _i64(x):
+    return C.c_int64(int(x))
+
+
+def _operand(bits, k_contig):
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    assert bits.ndim == 2
+    outer, K = (bits.shape if k_contig else bits.shape[::-1])
+    return bits, outer, K, bits.shape[1]
+
+
+def _mask(m, n):
+    if m is None:
+        return None
+    m = np.ascontiguousarray(m, dtype=np.uint8)
+    assert m.shape == (n,)
+    return m
+
+
+def _sel(s):
+    return None if s is None else np.ascontiguousarray(s, dtype=np.int32)
+
+
+def num_threads():
+    return int(lib().orc_num_threads())
+
+
+def fwht(v, b):
+    """(1/sqrt(b)) H_b v on a length-b fp32 vector (Eq. 5, one block)."""
+    v = np.array(v, dtype=np.float32, copy=True)
+    assert v.shape == (b,)
+    lib().orc_fwht(_p(v), C.c_int(b))
+    return v
+
+
+def e8m0_from_amax(amax):
+    return int(lib().orc_e8m0_from_amax(C.c_float(float(amax))))
+
+
+def e2m1_encode(q):
+    return int(lib().orc_e2m1_encode(C.c_float(float(q))))
+
+
+def foid_scores(bits, k_contig, axis):
+    bits, outer, K, ld = _operand(bits, k_contig)
+    out = np.empty(outer if axis == 0 else K, dtype=np.float32)
+    lib().orc_foid_scores(_p(bits), _i64(outer), _i64(K), _i64(ld), C.c_int(int(k_contig)), C.c_int(axis), _p(out))
+    return out
+
+
+def topk(scores, k):
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    idx = np.empty(k, dtype=np.int32)
+    mask = np.empty(scores.shape[0], dtype=np.uint8)
+    lib().orc_topk(_p(scores), _i64(scores.shape[0]), _i64(k), _p(idx), _p(mask))
+    return idx, mask
+
+
+def foid_topk(bits, k_contig, axis, k):
+    return topk(foid_scores(bits, k_contig, axis), k)
+
+
+def transform(bits, k_contig, iht_block, zero_outer=None, zero_k=None):
+    """fp32 values that enter the quantiser: residual masking, then the block transform."""
+    bits, outer, K, ld = _operand(bits, k_contig)
+    zo, zk = _mask(zero_outer, outer), _mask(zero_k, K)
+    out = np.empty((outer, K), dtype=np.float32)
+    lib().orc_transform(_p(bits), _i64(outer), _i64(K), _i64(ld), C.c_int(int(k_contig)), C.c_int(iht_block),
+                        _p(zo), _p(zk), _p(out))
+    return out
+
+
+def iht_quantize(bits, k_contig, iht_block, zero_outer=None, zero_k=None):
+    bits, outer, K, ld = _operand(bits, k_contig)
+    assert K % 32 == 0 and (iht_block == 0 or K % iht_block == 0)
+    zo, zk = _mask(zero_outer, outer), _mask(zero_k, K)
+    codes = np.empty((outer, K // 2), dtype=np.uint8)
+    scales = np.empty((outer, K // 32), dtype=np.uint8)
+    lib().orc_iht_quantize(_p(bits), _i64(outer), _i64(K), _i64(ld), C.c_int(int(k_contig)), C.c_int(iht_block),
+                           _p(zo), _p(zk), _p(codes), _p(scales))
+    return codes, scales
+
+
+def quantize_mx(bits, k_contig):
+    return iht_quantize(bits, k_contig, 0)
+
+
+def mx_gemm(a_codes, a_scales, b_codes, b_scales, rows=None, cols=None):
+    """Emulated MXFP4 product in double: out[r, c] = <dequant A[rows[r]], dequant B[cols[c]]>."""
+    a_codes = np.ascontiguousarray(a_codes, dtype=np.uint8)
+    b_codes = np.ascontiguousarray(b_codes, dtype=np.uint8)
+    a_scales = np.ascontiguousarray(a_scales, dtype=np.uint8)
+    b_scales = np.ascontiguousarray(b_scales, dtype=np.uint8)
+    K = a_codes.shape[1] * 2
+    assert b_codes.shape[1] * 2 == K
+    rows, cols = _sel(rows), _sel(cols)
+    nr = a_codes.shape[0] if rows is None else rows.shape[0]
+    nc = b_codes.shape[0] if cols is None else cols.shape[0]
+    out = np.empty((nr, nc), dtype=np.float64)
+    lib().orc_mx_gemm(_i64(K), _p(a_codes), _p(a_scales), _p(b_codes), _p(b_scales), _p(rows), _i64(nr),
+                      _p(cols), _i64(nc), _p(out))
+    return out
+
+
+def bf16_gemm(a_bits, a_k_contig, b_bits, b_k_contig, a_zero_outer=None, b_zero_outer=None, zero_k=None,
+              ksel=None, rows=None, cols=None):
+    """Double-precision product on the bf16 values themselves (see orc_bf16_gemm)."""
+    a_bits, M, K, a_ld = _operand(a_bits, a_k_contig)
+    b_bits, N, Kb, b_ld = _operand(b_bits, b_k_contig)
+    assert K == Kb
+    azo, bzo, zk = _mask(a_zero_outer, M), _mask(b_zero_outer, N), _mask(zero_k, K)
+    ksel, rows, cols = _sel(ksel), _sel(rows), _sel(cols)
+    nr = M if rows is None else rows.shape[0]
+    nc = N if cols is None else cols.shape[0]
+    nk = 0 if ksel is None else ksel.shape[0]
+    out = np.empty((nr, nc), dtype=np.float64)
+    lib().orc_bf16_gemm(_p(a_bits), _i64(a_ld), C.c_int(int(a_k_contig)), _p(b_bits), _i64(b_ld),
+                        C.c_int(int(b_k_contig)), _i64(K), _p(azo), _p(bzo), _p(zk), _p(ksel), _i64(nk),
+                        _p(rows), _i64(nr), _p(cols), _i64(nc), _p(out))
+    return out
+
+
+def exact_gemm(a_bits, a_k_contig, b_bits, b_k_contig, rows=None, cols=None):
+    """A*B in double on the bf16 inputs: the quality reference (left-hand side of Eq. 4)."""
+    return bf16_gemm(a_bits, a_k_contig, b_bits, b_k_contig, rows=rows, cols=cols)
+
+
+def adahop_gemm(a_bits, a_k_contig, b_bits, b_k_contig, strategy, iht_block, k=0, idx=None, rows=None, cols=None):
+    """The whole per-GEMM path.  A is logical [M, K], B is logical [N, K] (i.e. B^T), C is [M, N].
+
+    rows / cols: optional index samples; C is returned on rows x cols only.
+    idx: optional externally chosen extraction indices (else FOID picks them).
+    Returns dict(C, a_codes, a_scales, b_codes, b_scales, idx).
+    """
+    a_bits, M, K, _ = _operand(a_bits, a_k_contig)
+    b_bits, N, _, _ = _operand(b_bits, b_k_contig)
+    rows_a = np.arange(M, dtype=np.int32) if rows is None else _sel(rows)
+    cols_a = np.arange(N, dtype=np.int32) if cols is None else _sel(cols)
+    b_iht = 0 if strategy == NONE else iht_block
+    a_zo = b_zo = zk = None
+    sel = np.zeros(0, dtype=np.int32)
+    if strategy in (IHT_OE_ROW, IHT_OE_COL, IHT_OE_K) and k > 0:
+        dim = {IHT_OE_ROW: M, IHT_OE_COL: N, IHT_OE_K: K}[strategy]
+        if idx is not None:
+            sel = np.sort(_sel(idx))
+            mask = np.zeros(dim, dtype=np.uint8)
+            mask[sel] = 1
+        elif strategy == IHT_OE_ROW:      # rows of A, scored over their first 64 K-elements
+            sel, mask = foid_topk(a_bits, a_k_contig, 0, k)
+        elif strategy == IHT_OE_COL:      # columns of B, scored over their first 64 K-elements
+            sel, mask = foid_topk(b_bits, b_k_contig, 0, k)
+        else:                             # K-channels, scored on A over its first 64 rows
+            sel, mask = foid_topk(a_bits, a_k_contig, 1, k)
+        if strategy == IHT_OE_ROW:
+            a_zo = mask
+        elif strategy == IHT_OE_COL:
+            b_zo = mask
+        else:
+            zk = mask
+    a_codes, a_scales = iht_quantize(a_bits, a_k_contig, b_iht, a_zo, zk)
+    b_codes, b_scales = iht_quantize(b_bits, b_k_contig, b_iht, b_zo, zk)
+    Cm = mx_gemm(a_codes, a_scales, b_codes, b_scales, rows_a, cols_a)
+    if sel.size:
+        if strategy == IHT_OE_ROW:        # C[S, :] += A[S, :] B   (Eq. 7)
+            pos = np.nonzero(np.isin(rows_a, sel))[0]
+            if pos.size:
+                Cm[pos, :] += bf16_gemm(a_bits, a_k_contig, b_bits, b_k_contig, rows=rows_a[pos], cols=cols_a)
+        elif strategy == IHT_OE_COL:      # C[:, S] += A B[:, S]   (Eq. 8)
+            pos = np.nonzero(np.isin(cols_a, sel))[0]
+            if pos.size:
+                Cm[:, pos] += bf16_gemm(a_bits, a_k_contig, b_bits, b_k_contig, rows=rows_a, cols=cols_a[pos])
+        else:                             # C += A[:, S] B[S, :]
+            Cm += bf16_gemm(a_bits, a_k_contig, b_bits, b_k_contig, ksel=sel, rows=rows_a, cols=cols_a)
+    return dict(C=Cm, a_codes=a_codes, a_scales=a_scales, b_codes=b_codes, b_scales=b_scales, idx=sel)

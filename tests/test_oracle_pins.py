@@ -1,0 +1,463 @@
+"""Pins for the CPU oracle: every check here is against something other than the oracle itself --
+the definition of the Sylvester matrix, exact algebraic identities, the OCP MX value table, brute
+force, numpy's float64 routines, or closed forms.  No GPU.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import reference as orc
+from paper_2604_02525_amd import inputs
+
+
+# ----------------------------------------------------------------------------- helpers (test-side)
+
+def bf16_bits(x):
+    """fp32 array -> bf16 bit patterns (RNE), done with integer arithmetic on the fp32 bits."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    return r
+
+
+def bits_to_f64(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def sylvester(n):
+    """H_1 = [1];  H_2n = [[H, H], [H, -H]]  (integer entries)."""
+    H = np.array([[1]], dtype=np.int64)
+    while H.shape[0] < n:
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
+def load_table(path):
+    rows = []
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            rows.append(line.split())
+    return rows
+
+
+def e2m1_table(golden_dir):
+    t = {int(c): float(v) for c, v in load_table(os.path.join(golden_dir, "e2m1_values.txt"))}
+    assert len(t) == 16
+    return t
+
+
+def unpack_codes(codes):
+    lo = codes & 15
+    hi = codes >> 4
+    return np.stack([lo, hi], axis=-1).reshape(codes.shape[0], -1)
+
+
+def dequant(codes, scales, table):
+    """Independent dequantiser: value table from the golden file, scale 2^(s-127)."""
+    c = unpack_codes(codes)
+    vals = np.vectorize(table.get)(c).astype(np.float64)
+    s = np.repeat(scales.astype(np.int64), 32, axis=1)
+    return vals * np.exp2((s - 127).astype(np.float64))
+
+
+# ----------------------------------------------------------------------------- Hadamard
+
+@pytest.mark.parametrize("b", [2, 4, 8, 16, 32, 64, 128, 256])
+def test_sylvester_is_hadamard_and_fwht_matches_its_columns(b):
+    H = sylvester(b)
+    assert np.array_equal(H @ H.T, b * np.eye(b, dtype=np.int64))
+    assert np.array_equal(H, H.T)
+    c = np.float32(1.0 / np.sqrt(float(b)))
+    for i in range(b):
+        e = np.zeros(b, dtype=np.float32)
+        e[i] = 1.0
+        got = orc.fwht(e, b)
+        assert np.array_equal(got, (H[:, i].astype(np.float32) * c)), (b, i)
+
+
+@pytest.mark.parametrize("b", [32, 64, 128, 256])
+def test_fwht_close_to_explicit_matrix_product(b):
+    rng = np.random.default_rng(b)
+    H = sylvester(b).astype(np.float64)
+    for _ in range(8):
+        x = rng.standard_normal(b).astype(np.float32)
+        ref = H @ x.astype(np.float64) / np.sqrt(float(b))
+        got = orc.fwht(x, b).astype(np.float64)
+        assert np.max(np.abs(got - ref)) <= 16 * np.log2(b) * np.finfo(np.float32).eps * np.max(np.abs(ref))
+
+
+def test_fwht_exact_on_integers_block_256():
+    rng = np.random.default_rng(7)
+    x = rng.integers(-64, 65, size=256).astype(np.float32)
+    ref = sylvester(256) @ x.astype(np.int64)          # |ref| <= 256*64 = 2^14: exact in fp32
+    got = orc.fwht(x, 256)
+    assert np.array_equal(got.astype(np.float64), ref / 16.0)
+
+
+def test_fwht_stage_order_is_ascending_stride():
+    """With a value that rounds differently under the two textbook stage orders the result must be
+    the ascending-stride one: ((x0+x1)+(x2+x3)), not ((x0+x2)+(x1+x3))."""
+    x = np.array([1.0, 2.0 ** -24, 0.0, 2.0 ** -24], dtype=np.float32)
+    f = np.float32
+    asc0 = f(f(x[0] + x[1]) + f(x[2] + x[3]))      # h=1 first, then h=2
+    desc0 = f(f(x[0] + x[2]) + f(x[1] + x[3]))     # h=2 first, then h=1
+    assert asc0 != desc0                            # the probe does discriminate
+    got = orc.fwht(x, 4)
+    assert got[0] == f(asc0 * f(0.5))
+
+
+@pytest.mark.parametrize("b", [32, 128, 256])
+def test_iht_identity_without_quantisation(b):
+    """(A H)(H^T B) = A B  (Eq. 5's remark), with the oracle's fp32 transform and no quantiser."""
+    rng = np.random.default_rng(11 + b)
+    M, N, K = 24, 40, 2 * b
+    A = bf16_bits(rng.standard_normal((M, K)))
+    Bt = bf16_bits(rng.standard_normal((N, K)) * 0.02)
+    # B stored K-strided, as in dgrad: array [K, N]
+    B_store = np.ascontiguousarray(Bt.T)
+    Ah = orc.transform(A, True, b).astype(np.float64)
+    Bh = orc.transform(B_store, False, b).astype(np.float64)
+    exact = bits_to_f64(A) @ bits_to_f64(Bt).T
+    got = Ah @ Bh.T
+    assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 2e-6
+    # and the oracle's exact product agrees with numpy's float64 matmul
+    assert np.allclose(orc.exact_gemm(A, True, B_store, False), exact, rtol=1e-12, atol=1e-12)
+
+
+def test_transform_is_per_block_and_respects_layout():
+    """Block-diagonal I (x) H_b: each K-block only sees its own elements, in both layouts."""
+    rng = np.random.default_rng(5)
+    b, K, O = 32, 96, 3
+    x = rng.standard_normal((O, K)).astype(np.float32)
+    bits = bf16_bits(x)
+    ref = np.empty((O, K))
+    H = sylvester(b) / np.sqrt(float(b))
+    xv = bits_to_f64(bits)
+    for o in range(O):
+        for k0 in range(0, K, b):
+            ref[o, k0:k0 + b] = H @ xv[o, k0:k0 + b]
+    for kc, store in ((True, bits), (False, np.ascontiguousarray(bits.T))):
+        got = orc.transform(store, kc, b)
+        assert np.allclose(got, ref, rtol=0, atol=1e-5)
+
+
+# ----------------------------------------------------------------------------- E2M1 / E8M0
+
+def test_e2m1_encode_brute_force_all_bf16(golden_dir):
+    """Every finite bf16 bit pattern, at every power-of-two scaling that keeps it within the format's
+    range, against an argmin over the 16 representable values with ties to the even code."""
+    table = e2m1_table(golden_dir)
+    mags = np.array([table[c] for c in range(8)])
+    allbits = np.arange(65536, dtype=np.uint32)
+    vals = (allbits << 16).astype(np.uint32).view(np.float32)
+    finite = np.isfinite(vals)
+    vals = vals[finite]
+    checked = 0
+    for v in vals:
+        a = abs(float(v))
+        if a == 0.0:
+            scalings = [1.0]
+        else:
+            e = int(np.floor(np.log2(a)))
+            if e < -120:
+                continue
+            # bring |v| into each binade from 2^-3 up to just below 8
+            scalings = [2.0 ** (t - e) for t in (-3, -2, -1, 0, 1, 2)]
+        for sc in scalings:
+            q = np.float32(v) * np.float32(sc)
+            aq = abs(float(q))
+            if aq >= 8.0:
+                continue
+            d = np.abs(mags - aq)
+            best = np.flatnonzero(d == d.min())
+            m = int(best[0]) if len(best) == 1 else int([c for c in best if c % 2 == 0][0])
+            if aq > 6.0:
+                m = 7
+            want = m | (8 if np.signbit(q) else 0)
+            assert orc.e2m1_encode(q) == want, (float(q), want)
+            checked += 1
+    assert checked > 150000
+
+
+def test_e2m1_ties_and_saturation(golden_dir):
+    table = e2m1_table(golden_dir)
+    for mid, want in load_table(os.path.join(golden_dir, "e2m1_ties.txt")):
+        for sign in (1.0, -1.0):
+            code = orc.e2m1_encode(sign * float(mid))
+            assert abs(table[code]) == float(want)
+            assert (code >> 3) == (1 if sign < 0 else 0)
+    for big in (6.0, 6.5, 7.0, 7.999):
+        assert table[orc.e2m1_encode(big)] == 6.0
+        assert table[orc.e2m1_encode(-big)] == -6.0
+    assert orc.e2m1_encode(-0.0) == 8 and orc.e2m1_encode(-0.1) == 8 and orc.e2m1_encode(0.1) == 0
+
+
+def test_e8m0_rule(golden_dir):
+    for amax, want in load_table(os.path.join(golden_dir, "e8m0_cases.txt")):
+        assert orc.e8m0_from_amax(float.fromhex(amax)) == int(want), amax
+    assert orc.e8m0_from_amax(0.0) == 0
+    # closed form over many exponents and mantissas: amax = m 2^e, m in [1,2)  ->  e + 125
+    for e in range(-100, 101, 7):
+        for m in (1.0, 1.25, 1.999):
+            assert orc.e8m0_from_amax(np.float32(m * 2.0 ** e)) == e + 125
+
+
+def test_nibble_order_and_scale_layout(golden_dir):
+    """Element 2t in the low nibble of byte t; one scale byte per 32 K-elements, K-contiguous."""
+    K = 64
+    x = np.zeros((2, K), dtype=np.float32)
+    x[0, 0] = 6.0      # block 0: amax 6 -> scale 127, element 0 -> code 7
+    x[0, 1] = -1.0     # element 1 -> code 10, high nibble of byte 0
+    x[0, 33] = 3.0     # block 1: amax 3 -> scale 126 (X = 0.5), 3/0.5 = 6 -> code 7, high nibble of byte 16
+    x[1, 62] = 0.5     # row 1 block 1: amax .5 -> X = 2^-3, .5/X = 4 -> code 6, low nibble of byte 31
+    codes, scales = orc.quantize_mx(bf16_bits(x), True)
+    assert codes.shape == (2, 32) and scales.shape == (2, 2)
+    assert codes[0, 0] == (7 | (10 << 4))
+    assert codes[0, 16] == (7 << 4)
+    assert codes[1, 31] == 6
+    assert scales.tolist() == [[127, 126], [0, 124]]
+    expect_zero = np.ones_like(codes, dtype=bool)
+    expect_zero[0, 0] = expect_zero[0, 16] = expect_zero[1, 31] = False
+    assert np.all(codes[expect_zero] == 0)
+
+
+def test_quantiser_round_trip_and_none_gemm_is_exact(golden_dir):
+    """Blocks made of E2M1 values times a common power of two (with a 4 or 6 present) quantise to
+    themselves, so strategy `none` must reproduce the exact product (numpy float64 matmul)."""
+    table = e2m1_table(golden_dir)
+    rng = np.random.default_rng(3)
+    M, N, K = 16, 24, 128
+
+    def make(rows):
+        codes = rng.integers(0, 16, size=(rows, K))
+        exps = rng.integers(-6, 7, size=(rows, K // 32))
+        codes[:, ::32] = rng.choice([6, 7, 14, 15], size=(rows, K // 32))   # a 4 or a 6 per block
+        vals = np.vectorize(table.get)(codes) * np.exp2(np.repeat(exps, 32, axis=1).astype(np.float64))
+        return codes, exps, vals
+
+    ca, ea, va = make(M)
+    cb, eb, vb = make(N)
+    A, Bt = bf16_bits(va), bf16_bits(vb)
+    assert np.array_equal(bits_to_f64(A), va)            # all values are bf16-exact
+    a_codes, a_scales = orc.quantize_mx(A, True)
+    assert np.array_equal(unpack_codes(a_codes) & 7, ca & 7)
+    nz = (ca & 7) != 0
+    assert np.array_equal((unpack_codes(a_codes) >> 3)[nz], (ca >> 3)[nz])
+    assert np.array_equal(a_scales.astype(np.int64), ea + 127)
+    assert np.array_equal(dequant(a_codes, a_scales, table), va)
+    # K-strided storage of B gives the same codes
+    b_codes, b_scales = orc.quantize_mx(np.ascontiguousarray(Bt.T), False)
+    b_codes2, b_scales2 = orc.quantize_mx(Bt, True)
+    assert np.array_equal(b_codes, b_codes2) and np.array_equal(b_scales, b_scales2)
+    res = orc.adahop_gemm(A, True, np.ascontiguousarray(Bt.T), False, orc.NONE, 0)
+    assert np.allclose(res["C"], va @ vb.T, rtol=1e-13, atol=0)
+
+
+@pytest.mark.parametrize("b", [32, 64, 128, 256])
+def test_fused_closed_form_hadamard_rows(b, golden_dir):
+    """A K-block equal to c * (row i of the +-1 Sylvester matrix) transforms to b*c*e_i exactly
+    (integer butterflies), i.e. fl(fl(b c) * c_b) at position i and 0 elsewhere: one nonzero nibble
+    per transform block, and the E8M0 code from the closed form."""
+    table = e2m1_table(golden_dir)
+    H = sylvester(b)
+    cvals = [1.0, 0.75, 3.0, 0.0078125, 5.0]
+    nblk = len(cvals)
+    picks = [1, b - 1, b // 2, 3, 17 % b]
+    x = np.concatenate([c * H[i] for c, i in zip(cvals, picks)]).astype(np.float32)[None, :]
+    codes, scales = orc.iht_quantize(bf16_bits(x), True, b)
+    dq = dequant(codes, scales, table)[0]
+    cb = np.float32(1.0 / np.sqrt(float(b)))
+    for t, (c, i) in enumerate(zip(cvals, picks)):
+        blk = dq[t * b:(t + 1) * b]
+        peak = float(np.float32(np.float32(b * c) * cb))
+        nzpos = np.flatnonzero(blk)
+        assert nzpos.tolist() == [i]
+        e = int(np.floor(np.log2(peak)))
+        s = scales[0, (t * b + i) // 32]
+        assert s == e - 2 + 127
+        # the value stored is the nearest E2M1 magnitude to peak / 2^(e-2) (6 when that exceeds 6)
+        q = peak / 2.0 ** (e - 2)
+        mags = np.array([table[c] for c in range(8)])
+        d = np.abs(mags - q)
+        best = [int(c) for c in np.flatnonzero(d == d.min())]
+        pick = best[0] if len(best) == 1 else [c for c in best if c % 2 == 0][0]   # tie -> even code
+        assert blk[i] == mags[pick] * 2.0 ** (e - 2)
+        other = np.delete(scales[0, t * b // 32:(t + 1) * b // 32], i // 32)
+        assert np.all(other == 0)
+    assert nblk * b == x.shape[1]
+
+
+# ----------------------------------------------------------------------------- emulated GEMM
+
+def test_mx_gemm_matches_numpy_on_independent_dequant(golden_dir):
+    table = e2m1_table(golden_dir)
+    rng = np.random.default_rng(9)
+    M, N, K = 20, 12, 96
+    a_codes = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    b_codes = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    a_scales = rng.integers(110, 140, size=(M, K // 32), dtype=np.uint8)
+    b_scales = rng.integers(110, 140, size=(N, K // 32), dtype=np.uint8)
+    ref = dequant(a_codes, a_scales, table) @ dequant(b_codes, b_scales, table).T
+    got = orc.mx_gemm(a_codes, a_scales, b_codes, b_scales)
+    assert np.allclose(got, ref, rtol=1e-13, atol=1e-300)
+    rows = np.array([3, 19, 0], dtype=np.int32)
+    cols = np.array([11, 2], dtype=np.int32)
+    assert np.allclose(orc.mx_gemm(a_codes, a_scales, b_codes, b_scales, rows, cols), ref[np.ix_(rows, cols)],
+                       rtol=1e-13)
+
+
+def test_mx_gemm_hand_case():
+    """M=N=1, K=32: a = [6, -0.5, 0...] scale 2^1, b = [1.5, 4, 0...] scale 2^-2:
+    (6*2)(1.5/4) + (-0.5*2)(4/4) = 4.5 - 1 = 3.5."""
+    a = np.zeros((1, 16), dtype=np.uint8)
+    b = np.zeros((1, 16), dtype=np.uint8)
+    a[0, 0] = 7 | (9 << 4)
+    b[0, 0] = 3 | (6 << 4)
+    got = orc.mx_gemm(a, np.array([[128]], dtype=np.uint8), b, np.array([[125]], dtype=np.uint8))
+    assert got.shape == (1, 1) and got[0, 0] == 3.5
+
+
+# ----------------------------------------------------------------------------- OE
+
+@pytest.mark.parametrize("kind", ["row", "col", "k"])
+@pytest.mark.parametrize("layouts", [(True, True), (True, False), (False, False)])
+def test_oe_split_identity_without_quantisation(kind, layouts):
+    """A B = A_res B_res' + extracted part, exactly in double (App. E), for all three OE kinds."""
+    rng = np.random.default_rng(21)
+    M, N, K = 18, 22, 64
+    A = bf16_bits(rng.standard_normal((M, K)))
+    Bt = bf16_bits(rng.standard_normal((N, K)))
+    a_store = A if layouts[0] else np.ascontiguousarray(A.T)
+    b_store = Bt if layouts[1] else np.ascontiguousarray(Bt.T)
+    exact = bits_to_f64(A) @ bits_to_f64(Bt).T
+    assert np.allclose(orc.exact_gemm(a_store, layouts[0], b_store, layouts[1]), exact, rtol=1e-13)
+    dim = {"row": M, "col": N, "k": K}[kind]
+    sel = np.sort(rng.permutation(dim)[:5]).astype(np.int32)
+    mask = np.zeros(dim, dtype=np.uint8)
+    mask[sel] = 1
+    kw = {"row": dict(a_zero_outer=mask), "col": dict(b_zero_outer=mask), "k": dict(zero_k=mask)}[kind]
+    res = orc.bf16_gemm(a_store, layouts[0], b_store, layouts[1], **kw)
+    if kind == "row":
+        assert np.all(res[sel, :] == 0)
+        out = np.zeros_like(res)
+        out[sel, :] = orc.bf16_gemm(a_store, layouts[0], b_store, layouts[1], rows=sel)
+        assert np.allclose(out[sel], exact[sel], rtol=1e-13)
+    elif kind == "col":
+        assert np.all(res[:, sel] == 0)
+        out = np.zeros_like(res)
+        out[:, sel] = orc.bf16_gemm(a_store, layouts[0], b_store, layouts[1], cols=sel)
+    else:
+        out = orc.bf16_gemm(a_store, layouts[0], b_store, layouts[1], ksel=sel)
+        ref_part = bits_to_f64(A)[:, sel] @ bits_to_f64(Bt)[:, sel].T
+        assert np.allclose(out, ref_part, rtol=1e-12, atol=1e-12)
+    assert np.allclose(res + out, exact, rtol=1e-12, atol=1e-12)
+
+
+def test_oe_row_residual_rows_have_zero_codes():
+    g = inputs.Gemm("t", inputs.Operand(inputs.matrix(64, 128, 1.0, 77, row_outliers=(3, 100.0, 100.0)), True),
+                    inputs.Operand(inputs.matrix(48, 128, 0.02, 78), True), orc.IHT_OE_ROW, 32, 3)
+    res = orc.adahop_gemm(g.A.bits, True, g.B.bits, True, g.strategy, g.iht_block, g.k)
+    S = res["idx"]
+    assert len(S) == 3
+    assert np.all(res["a_codes"][S] == 0) and np.all(res["a_scales"][S] == 0)
+    # with the residual rows zero the MXFP4 part contributes nothing there: C[S] is the bf16 product
+    exact = orc.exact_gemm(g.A.bits, True, g.B.bits, True)
+    assert np.allclose(res["C"][S], exact[S], rtol=1e-12, atol=1e-14)
+
+
+def test_whole_path_matches_step_by_step_numpy(golden_dir):
+    """adahop_gemm (OE-K, K-strided B) against the same pipeline assembled in the test from numpy
+    pieces: Sylvester matrix product for the transform is replaced by the oracle's own codes (pinned
+    above), everything downstream -- dequantise, product, outlier part, sum -- is numpy."""
+    table = e2m1_table(golden_dir)
+    A = inputs.matrix(40, 128, 1.0, 5, col_outliers=(4, 50.0, 50.0))
+    Bt = inputs.matrix(24, 128, 0.02, 6)
+    b_store = np.ascontiguousarray(Bt.T)
+    res = orc.adahop_gemm(A, True, b_store, False, orc.IHT_OE_K, 64, 4)
+    S = res["idx"]
+    a64, b64 = bits_to_f64(A), bits_to_f64(Bt)
+    ref = dequant(res["a_codes"], res["a_scales"], table) @ dequant(res["b_codes"], res["b_scales"], table).T
+    ref += a64[:, S] @ b64[:, S].T
+    assert np.allclose(res["C"], ref, rtol=1e-12, atol=1e-12)
+    # the codes are those of the masked operand
+    mask = np.zeros(128, dtype=np.uint8)
+    mask[S] = 1
+    A_res = A.copy()
+    A_res[:, S] = 0
+    c2, s2 = orc.iht_quantize(A_res, True, 64)
+    assert np.array_equal(c2, res["a_codes"]) and np.array_equal(s2, res["a_scales"])
+
+
+# ----------------------------------------------------------------------------- FOID
+
+def test_foid_recall_of_planted_outliers_and_double_precision_ranking():
+    rng = np.random.default_rng(31)
+    rows, cols = 512, 256
+    g = np.random.default_rng(1)
+    x = g.standard_normal((rows, cols)).astype(np.float32)
+    planted = np.sort(rng.permutation(rows)[:9])
+    x[planted] *= 20.0                      # variance ratio 400
+    bits = bf16_bits(x)
+    for kc, store in ((True, bits), (False, np.ascontiguousarray(bits.T))):
+        idx, mask = orc.foid_topk(store, kc, 0, 9)
+        assert idx.tolist() == planted.tolist()
+        assert mask.sum() == 9 and np.all(mask[planted] == 1)
+        idx12, _ = orc.foid_topk(store, kc, 0, 12)
+        assert set(planted.tolist()) <= set(idx12.tolist()) and np.all(np.diff(idx12) > 0)
+        # double-precision variance over the first 64 elements ranks the same way
+        scores = orc.foid_scores(store, kc, 0)
+        v = bits_to_f64(bits)[:, :64]
+        ref = ((v - v.mean(axis=1, keepdims=True)) ** 2).sum(axis=1)
+        assert np.allclose(scores, ref, rtol=2e-5)
+        order = np.argsort(-ref, kind="stable")
+        gap_ok = ref[order[11]] * (1 - 1e-4) > ref[order[12]]
+        if gap_ok:
+            assert set(order[:12].tolist()) == set(idx12.tolist())
+    # axis = 1: score K indices over the first 64 outer elements
+    idxk, _ = orc.foid_topk(np.ascontiguousarray(bits.T), True, 1, 9)     # array [outer=cols, K=rows]
+    assert idxk.tolist() == planted.tolist()
+
+
+def test_topk_tie_break_is_lowest_index():
+    scores = np.array([1.0, 5.0, 5.0, 0.5, 5.0, 7.0, 1.0], dtype=np.float32)
+    idx, mask = orc.topk(scores, 3)
+    assert idx.tolist() == [1, 2, 5] and mask.tolist() == [0, 1, 1, 0, 0, 1, 0]
+    idx, _ = orc.topk(scores, 5)
+    assert idx.tolist() == [0, 1, 2, 4, 5]
+    idx, mask = orc.topk(scores, 0)
+    assert idx.size == 0 and mask.sum() == 0
+
+
+def test_foid_uses_only_first_64_samples():
+    x = np.zeros((4, 256), dtype=np.float32)
+    x[1, 100:] = 1000.0 * np.arange(156)          # huge, but outside the sampled window
+    x[2, :64] = np.arange(64)
+    s = orc.foid_scores(bf16_bits(x), True, 0)
+    assert s[1] == 0.0 and s[2] > 0 and s[0] == 0.0
+
+
+# ----------------------------------------------------------------------------- qualitative (paper)
+
+def test_iht_helps_column_outlier_activations_config0():
+    """Sec. 3.2 / Fig. 2: for a CN pair IHT lowers the product error relative to plain MXFP4."""
+    g = inputs.config0()[0]
+    exact = orc.exact_gemm(g.A.bits, True, g.B.bits, True)
+    e = {}
+    for s in (orc.NONE, orc.IHT):
+        C = orc.adahop_gemm(g.A.bits, True, g.B.bits, True, s, 32)["C"]
+        e[s] = np.mean((C - exact) ** 2)
+    assert e[orc.IHT] < e[orc.NONE]
+
+
+def test_oe_row_error_non_increasing_in_rank():
+    """App. G: error falls with the extraction rank and flattens once the planted rows are out."""
+    A = inputs.matrix(256, 256, 1.0, 41, row_outliers=(6, 100.0, 100.0))
+    Bt = inputs.matrix(128, 256, 0.02, 42)
+    exact = orc.exact_gemm(A, True, Bt, True)
+    errs = []
+    for k in (0, 2, 6, 12):
+        C = orc.adahop_gemm(A, True, Bt, True, orc.IHT_OE_ROW, 32, k)["C"]
+        errs.append(np.linalg.norm(C - exact))
+    assert errs[0] > errs[1] > errs[2] >= errs[3] * 0.999
+    assert errs[2] < 0.2 * errs[0]
