@@ -1,0 +1,161 @@
+/*
+ * adahop.h -- C ABI of the MI355X (gfx950) AdaHOP per-GEMM hot path.
+ *
+ * One GEMM of a linear layer, C[M,N] = A[M,K] * B[K,N] (paper Eq. 1-4), computed as
+ *
+ *     C = Q(A_res H) * Q(H^T B_res)            MXFP4, block-scaled FP4 matrix cores
+ *       + (extracted rows / columns / K-channels of the original operands)   BF16 matrix cores
+ *
+ * with H the block-diagonal normalised Sylvester Hadamard matrix along K (paper Eq. 5), Q the OCP
+ * MX quantiser (E2M1 elements, one E8M0 scale per 32 consecutive K-elements), and the extracted
+ * part chosen by a 64-sample variance score (paper Eq. 7-8, App. F).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; the library allocates nothing,
+ *     keeps no state between calls and never synchronises: work is queued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns.
+ *   - Outputs are fully overwritten.  Inputs are not modified.
+ *   - Return value: ADAHOP_OK, or a negative adahop_status_t.  Arguments are validated before any
+ *     HIP call, so ADAHOP_E_INVALID_ARG / ADAHOP_E_WORKSPACE can be exercised without a GPU.
+ *     After ADAHOP_E_HIP, adahop_last_hip_error() returns the hipError_t of the failed call.
+ *   - B is always described as its transpose: a logical [N, K] matrix, so that both operands are
+ *     "outer x K" and K is the contraction axis.
+ */
+#ifndef ADAHOP_H
+#define ADAHOP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ADAHOP_OK = 0,
+    ADAHOP_E_INVALID_ARG = -1, /* null pointer, bad enum, K % 32 != 0, K % iht_block != 0, bad k, ld too small, misaligned */
+    ADAHOP_E_WORKSPACE = -2,   /* workspace pointer null / misaligned / too small */
+    ADAHOP_E_HIP = -3          /* a HIP launch or API call failed */
+} adahop_status_t;
+
+/* Per-GEMM strategy (paper Sec. 4.2; the caller supplies what the paper's calibration would). */
+typedef enum {
+    ADAHOP_NONE = 0,       /* C = Q(A) Q(B)                                   (Eq. 4)            */
+    ADAHOP_IHT = 1,        /* C = Q(A H) Q(H^T B)                             (Eq. 5)            */
+    ADAHOP_IHT_OE_ROW = 2, /* OE-Left : top-k rows of A in BF16              (Eq. 7)            */
+    ADAHOP_IHT_OE_COL = 3, /* OE-Right: top-k columns of B in BF16           (Eq. 8)            */
+    ADAHOP_IHT_OE_K = 4    /* top-k K-channels (of A) in BF16, removed from both residuals       */
+} adahop_strategy_t;
+
+/* A bf16 matrix operand, logical shape [outer, K].
+ *   k_contig = 1: element (o, kk) is data[o * ld + kk]   (ld >= K)
+ *   k_contig = 0: element (o, kk) is data[kk * ld + o]   (ld >= outer)
+ * The three products of a linear layer (Eq. 1-3) use: forward  A = X (k_contig), B = W (k_contig);
+ * dgrad  A = G_Y (k_contig), B = W stored [K, N] (k_contig = 0);  wgrad  A = G_Y stored [K, M] and
+ * B = X stored [K, N] (both k_contig = 0).
+ * Alignment: data must be 16-byte aligned and ld a multiple of 8 elements. */
+typedef struct {
+    const void *data; /* device pointer to bf16 */
+    int64_t outer;
+    int64_t K;
+    int64_t ld;       /* leading dimension in elements */
+    int k_contig;
+} adahop_operand_t;
+
+/* ---------------------------------------------------------------------------------------------
+ * Quantisers.  Canonical packed layout, K-contiguous whatever the input layout:
+ *   codes  uint8 [outer, K/2]   byte t of a row = code(kk = 2t) | code(kk = 2t+1) << 4
+ *   scales uint8 [outer, K/32]  E8M0, biased by 127
+ * E2M1 code: bit 3 = sign, bits 0..2 index {0, .5, 1, 1.5, 2, 3, 4, 6}; round to nearest even,
+ * saturating at 6.  Scale = 127 + floor(log2(amax)) - 2, clamped to [0, 254]; 0 for an all-zero
+ * block (OCP Microscaling v1.0; the paper names the format in Sec. 1 and App. F item 2).
+ * Requires K % 32 == 0.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Plain MX quantisation along K (the operand side of Eq. 4). */
+int adahop_quantize_mx(const adahop_operand_t *x, uint8_t *codes, uint8_t *scales, void *stream);
+
+/* Fused residual masking -> block Hadamard transform -> MX quantisation (Eq. 5 applied to one
+ * operand; App. F items 1-2).  iht_block in {0, 32, 64, 128, 256}; 0 = no transform; K % iht_block
+ * must be 0.  The transform is fp32: butterflies in ascending stride, then one multiply by
+ * (float)(1/sqrt(iht_block)).
+ * zero_outer (length outer) / zero_k (length K): optional device byte masks; a nonzero byte means
+ * that whole row / that K index is treated as 0 (the Outlier Extraction residual).  NULL = none.
+ * zero_k must be 8-byte aligned. */
+int adahop_iht_quantize(const adahop_operand_t *x, int iht_block, const uint8_t *zero_outer,
+                        const uint8_t *zero_k, uint8_t *codes, uint8_t *scales, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * FOID (App. F item 1): score = sum of squared deviations from the mean over the first
+ * min(64, len) elements (fp32: sequential sum, mean = sum * (1/len), sequential fused
+ * multiply-add), then the exact top-k by (score descending, index ascending).
+ *   axis = 0: score every outer index over its first 64 K-elements        (dim = outer)
+ *   axis = 1: score every K index over its first 64 outer elements        (dim = K)
+ * idx_out  int32 [k]    selected indices, ascending
+ * mask_out uint8 [dim]  1 where selected, else 0 (8-byte aligned; usable as zero_outer / zero_k)
+ * scores_ws float [dim] scratch for the scores (left filled on return)
+ * 0 <= k <= dim, dim <= 2^24.
+ * ------------------------------------------------------------------------------------------- */
+int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_out, uint8_t *mask_out,
+                     float *scores_ws, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Block-scaled FP4 product on packed operands (the MXFP4 term of Eq. 4 / 5 / 7 / 8):
+ *   C[m, n] = sum_blk 2^(sa[m,blk]-127) 2^(sb[n,blk]-127) sum_{i<32} a[m, 32 blk + i] b[n, 32 blk + i]
+ * fp32 accumulation and output, C row-major with leading dimension ldc >= N.
+ * codes / scales in the canonical layout above; codes 16-byte aligned, K % 32 == 0.
+ * ------------------------------------------------------------------------------------------- */
+int adahop_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * The whole path (App. F: FOID -> IHT + quantise -> MXFP4 product + BF16 outlier product -> sum).
+ * A is [M, K], B is [N, K] (operand sense), C is fp32 [M, N] with leading dimension ldc.
+ *   strategy NONE: iht_block is ignored.  OE strategies with k == 0 behave as ADAHOP_IHT.
+ *   k counts extracted rows of A (OE_ROW, k <= M), columns of B (OE_COL, k <= N) or K-channels
+ *   (OE_K, k <= K; scored on A over its first 64 rows and removed from both operands).
+ *   idx_inout int32 [k]: if use_given_idx != 0 the k distinct indices are read from it (any order),
+ *   else FOID fills it (ascending).  May be NULL when k == 0.
+ * The BF16 part uses the original bf16 values with fp32 accumulation and is added in fp32.
+ * The workspace holds, at the offsets reported by adahop_gemm_workspace_layout(), the canonical
+ * codes and scales of both operands, the extraction mask and the FOID scores, all left in place on
+ * return so that a caller can inspect or reuse them.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    size_t a_codes, a_scales, b_codes, b_scales; /* byte offsets into the workspace */
+    size_t mask;                                 /* uint8 [extracted dim]           */
+    size_t scores;                               /* float [extracted dim]           */
+    size_t gather_a, gather_b;                   /* bf16 staging for the BF16 part  */
+    size_t total;                                /* bytes required                  */
+} adahop_ws_layout_t;
+
+int adahop_gemm_workspace_layout(int64_t M, int64_t N, int64_t K, adahop_strategy_t strategy, int k,
+                                 adahop_ws_layout_t *out);
+size_t adahop_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, adahop_strategy_t strategy, int k);
+
+int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, int64_t ldc,
+                adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/* The BF16 outlier product alone (second term of Eq. 7 / Eq. 8 / the K-channel form), for callers
+ * that keep quantised operands across products and for tests.
+ *   kind OE_ROW: C[idx[t], :]  = A[idx[t], :] * B          (overwrites those rows)
+ *   kind OE_COL: C[:, idx[t]]  = A * B[:, idx[t]]          (overwrites those columns)
+ *   kind OE_K  : C            += A[:, idx] * B[idx, :]     (accumulates)
+ * idx int32 [k] device, distinct, in range.  gather_ws: device scratch of at least
+ * adahop_oe_gather_bytes(M, N, K, kind, k) bytes, 256-byte aligned. */
+size_t adahop_oe_gather_bytes(int64_t M, int64_t N, int64_t K, adahop_strategy_t kind, int k);
+int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, adahop_strategy_t kind,
+                        const int32_t *idx, int k, float *C, int64_t ldc, void *gather_ws,
+                        size_t gather_bytes, void *stream);
+
+/* hipError_t (as int) of the most recent failed HIP call on this thread, 0 if none. */
+int adahop_last_hip_error(void);
+const char *adahop_status_string(int status);
+/* ABI version: bumped on any incompatible change. */
+int adahop_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAHOP_H */

@@ -1,0 +1,201 @@
+"""Thin ctypes binding over libadahop.so (the C ABI of include/adahop.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels behind the ABI.  PyTorch is
+used for device memory (outputs and workspaces are torch tensors) and for the current stream.  There
+is no CPU fallback: if the library is missing, loading fails loudly.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libadahop.so")
+
+ADAHOP_NONE, ADAHOP_IHT, ADAHOP_IHT_OE_ROW, ADAHOP_IHT_OE_COL, ADAHOP_IHT_OE_K = range(5)
+ADAHOP_OK, ADAHOP_E_INVALID_ARG, ADAHOP_E_WORKSPACE, ADAHOP_E_HIP = 0, -1, -2, -3
+
+EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_gemm_mx",
+           "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
+           "adahop_oe_gemm_bf16", "adahop_last_hip_error", "adahop_status_string", "adahop_abi_version"]
+
+
+class AdahopError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().adahop_status_string(status).decode()
+        if status == ADAHOP_E_HIP:
+            msg += f" [hipError {lib().adahop_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+class adahop_operand_t(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("outer", C.c_int64), ("K", C.c_int64), ("ld", C.c_int64), ("k_contig", C.c_int)]
+
+
+class adahop_ws_layout_t(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("a_codes", "a_scales", "b_codes", "b_scales", "mask", "scores",
+                                          "gather_a", "gather_b", "total")]
+
+
+_lib = None
+
+
+def lib():
+    """Load libadahop.so (built in-tree by paper_2604_02525_amd/build.py); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        P, I64, I, SZ = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+        OP = C.POINTER(adahop_operand_t)
+        L.adahop_quantize_mx.argtypes = [OP, P, P, P]
+        L.adahop_iht_quantize.argtypes = [OP, I, P, P, P, P, P]
+        L.adahop_foid_topk.argtypes = [OP, I, I, P, P, P, P]
+        L.adahop_gemm_mx.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P]
+        L.adahop_gemm_workspace_layout.argtypes = [I64, I64, I64, I, I, C.POINTER(adahop_ws_layout_t)]
+        L.adahop_gemm_workspace_bytes.argtypes = [I64, I64, I64, I, I]
+        L.adahop_gemm_workspace_bytes.restype = SZ
+        L.adahop_gemm.argtypes = [OP, OP, P, I64, I, I, I, P, I, P, SZ, P]
+        L.adahop_oe_gather_bytes.argtypes = [I64, I64, I64, I, I]
+        L.adahop_oe_gather_bytes.restype = SZ
+        L.adahop_oe_gemm_bf16.argtypes = [OP, OP, I, P, I, P, I64, P, SZ, P]
+        L.adahop_status_string.restype = C.c_char_p
+        L.adahop_status_string.argtypes = [I]
+        for name in EXPORTS:
+            getattr(L, name)          # AttributeError here means the library is stale: rebuild it
+        _lib = L
+    return _lib
+
+
+def _check(status, where):
+    if status != ADAHOP_OK:
+        raise AdahopError(status, where)
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+class Operand:
+    """A bf16 device matrix as stored plus the flag saying which of its axes is K.
+
+    tensor: 2-D torch tensor on the GPU (bfloat16, or int16/uint16 bit patterns), row stride = ld,
+    unit column stride.  k_contig=True: tensor is [outer, K]; False: tensor is [K, outer].
+    """
+
+    def __init__(self, tensor, k_contig):
+        assert tensor.dim() == 2 and tensor.stride(1) == 1 and tensor.element_size() == 2
+        self.tensor = tensor
+        self.k_contig = bool(k_contig)
+        self.outer, self.K = (tensor.shape if k_contig else tensor.shape[::-1])
+        self.ld = tensor.stride(0)
+
+    @classmethod
+    def from_bits(cls, bits, k_contig, device="cuda"):
+        """Upload a numpy uint16 array of bf16 bit patterns."""
+        t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
+        return cls(t, k_contig)
+
+    def c(self):
+        return adahop_operand_t(self.tensor.data_ptr(), self.outer, self.K, self.ld, int(self.k_contig))
+
+
+def _u8(shape, device):
+    return torch.empty(shape, dtype=torch.uint8, device=device)
+
+
+def adahop_iht_quantize(x, iht_block, zero_outer=None, zero_k=None, codes=None, scales=None, stream=None):
+    dev = x.tensor.device
+    codes = _u8((x.outer, x.K // 2), dev) if codes is None else codes
+    scales = _u8((x.outer, x.K // 32), dev) if scales is None else scales
+    _check(lib().adahop_iht_quantize(C.byref(x.c()), iht_block, _ptr(zero_outer), _ptr(zero_k), _ptr(codes),
+                                     _ptr(scales), _stream(stream)), "adahop_iht_quantize")
+    return codes, scales
+
+
+def adahop_quantize_mx(x, codes=None, scales=None, stream=None):
+    dev = x.tensor.device
+    codes = _u8((x.outer, x.K // 2), dev) if codes is None else codes
+    scales = _u8((x.outer, x.K // 32), dev) if scales is None else scales
+    _check(lib().adahop_quantize_mx(C.byref(x.c()), _ptr(codes), _ptr(scales), _stream(stream)), "adahop_quantize_mx")
+    return codes, scales
+
+
+def adahop_foid_topk(x, axis, k, stream=None):
+    dev = x.tensor.device
+    dim = x.outer if axis == 0 else x.K
+    idx = torch.empty(max(k, 1), dtype=torch.int32, device=dev)
+    mask = _u8((dim,), dev)
+    scores = torch.empty(dim, dtype=torch.float32, device=dev)
+    _check(lib().adahop_foid_topk(C.byref(x.c()), axis, k, _ptr(idx), _ptr(mask), _ptr(scores), _stream(stream)),
+           "adahop_foid_topk")
+    return idx[:k], mask, scores
+
+
+def adahop_gemm_mx(a_codes, a_scales, b_codes, b_scales, Cout=None, stream=None):
+    M, N, K = a_codes.shape[0], b_codes.shape[0], a_codes.shape[1] * 2
+    assert b_codes.shape[1] * 2 == K
+    if Cout is None:
+        Cout = torch.empty((M, N), dtype=torch.float32, device=a_codes.device)
+    _check(lib().adahop_gemm_mx(M, N, K, _ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), _ptr(Cout),
+                                Cout.stride(0), _stream(stream)), "adahop_gemm_mx")
+    return Cout
+
+
+def adahop_gemm_workspace_layout(M, N, K, strategy, k):
+    L = adahop_ws_layout_t()
+    _check(lib().adahop_gemm_workspace_layout(M, N, K, strategy, k, C.byref(L)), "adahop_gemm_workspace_layout")
+    return L
+
+
+def adahop_gemm_workspace_bytes(M, N, K, strategy, k):
+    return int(lib().adahop_gemm_workspace_bytes(M, N, K, strategy, k))
+
+
+def adahop_gemm(A, B, strategy, iht_block, k=0, idx=None, Cout=None, workspace=None, stream=None):
+    """Whole path.  Returns dict(C, idx, workspace, layout, a_codes, a_scales, b_codes, b_scales, mask)
+    where the codes / scales / mask entries are views into the workspace."""
+    dev = A.tensor.device
+    M, N, K = A.outer, B.outer, A.K
+    L = adahop_gemm_workspace_layout(M, N, K, strategy, k)
+    if workspace is None:
+        workspace = _u8((L.total,), dev)
+    if Cout is None:
+        Cout = torch.empty((M, N), dtype=torch.float32, device=dev)
+    use_given = idx is not None
+    if idx is None:
+        idx = torch.empty(max(k, 1), dtype=torch.int32, device=dev)
+    _check(lib().adahop_gemm(C.byref(A.c()), C.byref(B.c()), _ptr(Cout), Cout.stride(0), strategy, iht_block, k,
+                             _ptr(idx), int(use_given), _ptr(workspace), workspace.numel(), _stream(stream)),
+           "adahop_gemm")
+    dim = {ADAHOP_IHT_OE_ROW: M, ADAHOP_IHT_OE_COL: N, ADAHOP_IHT_OE_K: K}.get(strategy, 0)
+    view = lambda off, n, shape: workspace[off:off + n].view(shape)
+    return dict(C=Cout, idx=idx[:k], workspace=workspace, layout=L,
+                a_codes=view(L.a_codes, M * K // 2, (M, K // 2)), a_scales=view(L.a_scales, M * K // 32, (M, K // 32)),
+                b_codes=view(L.b_codes, N * K // 2, (N, K // 2)), b_scales=view(L.b_scales, N * K // 32, (N, K // 32)),
+                mask=view(L.mask, dim, (dim,)))
+
+
+def adahop_oe_gather_bytes(M, N, K, kind, k):
+    return int(lib().adahop_oe_gather_bytes(M, N, K, kind, k))
+
+
+def adahop_oe_gemm_bf16(A, B, kind, idx, Cout, gather_ws=None, stream=None):
+    k = int(idx.numel())
+    need = adahop_oe_gather_bytes(A.outer, B.outer, A.K, kind, k)
+    if gather_ws is None and need:
+        gather_ws = _u8((need,), A.tensor.device)
+    _check(lib().adahop_oe_gemm_bf16(C.byref(A.c()), C.byref(B.c()), kind, _ptr(idx), k, _ptr(Cout), Cout.stride(0),
+                                     _ptr(gather_ws), 0 if gather_ws is None else gather_ws.numel(), _stream(stream)),
+           "adahop_oe_gemm_bf16")
+    return Cout

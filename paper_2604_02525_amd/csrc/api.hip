@@ -1,0 +1,241 @@
+// extern "C" entry points of the AdaHOP library: argument validation (before any HIP call),
+// workspace layout, and the per-GEMM pipeline of paper App. F (FOID -> IHT + quantise -> MXFP4
+// product + BF16 outlier product -> sum) queued on one stream.
+#include "common.h"
+
+namespace adahop {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(int e) { g_last_hip_error = e; }
+
+static const int64_t MAX_OUTER = (int64_t)1 << 22; // keeps every grid dimension legal
+static const int64_t MAX_K = (int64_t)1 << 24;
+
+bool valid_iht_block(int b) { return b == 0 || b == 32 || b == 64 || b == 128 || b == 256; }
+
+int validate_operand(const adahop_operand_t *x)
+{
+    if (!x || !x->data) return ADAHOP_E_INVALID_ARG;
+    if (x->outer < 1 || x->K < 32 || x->outer > MAX_OUTER || x->K > MAX_K) return ADAHOP_E_INVALID_ARG;
+    if (x->K % 32 != 0) return ADAHOP_E_INVALID_ARG;
+    if (x->k_contig != 0 && x->k_contig != 1) return ADAHOP_E_INVALID_ARG;
+    if (x->ld < (x->k_contig ? x->K : x->outer) || x->ld % 8 != 0) return ADAHOP_E_INVALID_ARG;
+    if (!aligned(x->data, 16)) return ADAHOP_E_INVALID_ARG;
+    if (x->outer * (x->K / 8) >= ((int64_t)1 << 32)) return ADAHOP_E_INVALID_ARG;
+    return ADAHOP_OK;
+}
+
+static int kpad_of(int k) { return (k + 15) / 16 * 16; }
+
+static int extracted_dim(adahop_strategy_t s, int64_t M, int64_t N, int64_t K, int64_t *dim)
+{
+    switch (s) {
+    case ADAHOP_NONE:
+    case ADAHOP_IHT: *dim = 0; return ADAHOP_OK;
+    case ADAHOP_IHT_OE_ROW: *dim = M; return ADAHOP_OK;
+    case ADAHOP_IHT_OE_COL: *dim = N; return ADAHOP_OK;
+    case ADAHOP_IHT_OE_K: *dim = K; return ADAHOP_OK;
+    }
+    return ADAHOP_E_INVALID_ARG;
+}
+
+} // namespace adahop
+
+using namespace adahop;
+
+extern "C" {
+
+int adahop_abi_version(void) { return 1; }
+
+int adahop_last_hip_error(void) { return g_last_hip_error; }
+
+const char *adahop_status_string(int status)
+{
+    switch (status) {
+    case ADAHOP_OK: return "ok";
+    case ADAHOP_E_INVALID_ARG: return "invalid argument";
+    case ADAHOP_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ADAHOP_E_HIP: return "HIP call failed (see adahop_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+int adahop_iht_quantize(const adahop_operand_t *x, int iht_block, const uint8_t *zero_outer, const uint8_t *zero_k,
+                        uint8_t *codes, uint8_t *scales, void *stream)
+{
+    int rc = validate_operand(x);
+    if (rc != ADAHOP_OK) return rc;
+    if (!codes || !scales || !valid_iht_block(iht_block)) return ADAHOP_E_INVALID_ARG;
+    if (iht_block > 0 && x->K % iht_block != 0) return ADAHOP_E_INVALID_ARG;
+    if (!aligned(codes, 16) || (zero_k && !aligned(zero_k, 8))) return ADAHOP_E_INVALID_ARG;
+    return launch_iht_quantize(*x, iht_block, zero_outer, zero_k, codes, scales, static_cast<hipStream_t>(stream));
+}
+
+int adahop_quantize_mx(const adahop_operand_t *x, uint8_t *codes, uint8_t *scales, void *stream)
+{
+    return adahop_iht_quantize(x, 0, nullptr, nullptr, codes, scales, stream);
+}
+
+int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_out, uint8_t *mask_out, float *scores_ws,
+                     void *stream)
+{
+    int rc = validate_operand(x);
+    if (rc != ADAHOP_OK) return rc;
+    if (axis != 0 && axis != 1) return ADAHOP_E_INVALID_ARG;
+    const int64_t dim = axis == 0 ? x->outer : x->K;
+    if (k < 0 || k > dim || !mask_out || !scores_ws || (k > 0 && !idx_out)) return ADAHOP_E_INVALID_ARG;
+    if (!aligned(mask_out, 8) || !aligned(scores_ws, 4)) return ADAHOP_E_INVALID_ARG;
+    return launch_foid_topk(*x, axis, k, idx_out, mask_out, scores_ws, static_cast<hipStream_t>(stream));
+}
+
+int adahop_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *stream)
+{
+    if (M < 1 || N < 1 || K < 32 || K % 32 != 0 || M > MAX_OUTER || N > MAX_OUTER || K > MAX_K)
+        return ADAHOP_E_INVALID_ARG;
+    if (!a_codes || !a_scales || !b_codes || !b_scales || !C || ldc < N) return ADAHOP_E_INVALID_ARG;
+    if (!aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(C, 4)) return ADAHOP_E_INVALID_ARG;
+    return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0,
+                          static_cast<hipStream_t>(stream));
+}
+
+int adahop_gemm_workspace_layout(int64_t M, int64_t N, int64_t K, adahop_strategy_t strategy, int k,
+                                 adahop_ws_layout_t *out)
+{
+    if (!out || M < 1 || N < 1 || K < 32 || K % 32 != 0 || M > MAX_OUTER || N > MAX_OUTER || K > MAX_K)
+        return ADAHOP_E_INVALID_ARG;
+    int64_t dim = 0;
+    if (extracted_dim(strategy, M, N, K, &dim) != ADAHOP_OK) return ADAHOP_E_INVALID_ARG;
+    if (k < 0 || (dim > 0 && k > dim)) return ADAHOP_E_INVALID_ARG;
+    size_t off = 0;
+    auto take = [&off](size_t bytes) {
+        size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    out->a_codes = take((size_t)M * (K / 2));
+    out->a_scales = take((size_t)M * (K / 32));
+    out->b_codes = take((size_t)N * (K / 2));
+    out->b_scales = take((size_t)N * (K / 32));
+    out->mask = take((size_t)dim);
+    out->scores = take((size_t)dim * sizeof(float));
+    const bool oek = strategy == ADAHOP_IHT_OE_K && k > 0;
+    out->gather_a = take(oek ? (size_t)M * kpad_of(k) * 2 : 0);
+    out->gather_b = take(oek ? (size_t)N * kpad_of(k) * 2 : 0);
+    out->total = off;
+    return ADAHOP_OK;
+}
+
+size_t adahop_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, adahop_strategy_t strategy, int k)
+{
+    adahop_ws_layout_t l;
+    if (adahop_gemm_workspace_layout(M, N, K, strategy, k, &l) != ADAHOP_OK) return 0;
+    return l.total;
+}
+
+size_t adahop_oe_gather_bytes(int64_t M, int64_t N, int64_t K, adahop_strategy_t kind, int k)
+{
+    (void)K;
+    if (kind != ADAHOP_IHT_OE_K || k <= 0 || M < 1 || N < 1) return 0;
+    return align_up((size_t)M * kpad_of(k) * 2, 256) + align_up((size_t)N * kpad_of(k) * 2, 256);
+}
+
+static int validate_pair(const adahop_operand_t *A, const adahop_operand_t *B, const float *C, int64_t ldc)
+{
+    int rc = validate_operand(A);
+    if (rc != ADAHOP_OK) return rc;
+    rc = validate_operand(B);
+    if (rc != ADAHOP_OK) return rc;
+    if (A->K != B->K || !C || ldc < B->outer || !aligned(C, 4)) return ADAHOP_E_INVALID_ARG;
+    return ADAHOP_OK;
+}
+
+int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, adahop_strategy_t kind,
+                        const int32_t *idx, int k, float *C, int64_t ldc, void *gather_ws, size_t gather_bytes,
+                        void *stream)
+{
+    int rc = validate_pair(A, B, C, ldc);
+    if (rc != ADAHOP_OK) return rc;
+    int64_t dim = 0;
+    if (extracted_dim(kind, A->outer, B->outer, A->K, &dim) != ADAHOP_OK || dim == 0) return ADAHOP_E_INVALID_ARG;
+    if (k < 0 || k > dim || (k > 0 && !idx)) return ADAHOP_E_INVALID_ARG;
+    if (k == 0) return ADAHOP_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (kind != ADAHOP_IHT_OE_K) return launch_oe_rowcol(*A, *B, kind, idx, k, C, ldc, st);
+    const size_t need = adahop_oe_gather_bytes(A->outer, B->outer, A->K, kind, k);
+    if (!gather_ws || !aligned(gather_ws, 256) || gather_bytes < need) return ADAHOP_E_WORKSPACE;
+    const int kpad = kpad_of(k);
+    uint16_t *Ag = static_cast<uint16_t *>(gather_ws);
+    uint16_t *Bg = reinterpret_cast<uint16_t *>(static_cast<char *>(gather_ws) + align_up((size_t)A->outer * kpad * 2, 256));
+    rc = launch_gather_k(*A, idx, k, kpad, Ag, st);
+    if (rc != ADAHOP_OK) return rc;
+    rc = launch_gather_k(*B, idx, k, kpad, Bg, st);
+    if (rc != ADAHOP_OK) return rc;
+    return launch_oe_k_accumulate(A->outer, B->outer, Ag, Bg, kpad, C, ldc, st);
+}
+
+int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, int64_t ldc,
+                adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
+                void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = validate_pair(A, B, C, ldc);
+    if (rc != ADAHOP_OK) return rc;
+    const int64_t M = A->outer, N = B->outer, K = A->K;
+    int64_t dim = 0;
+    if (extracted_dim(strategy, M, N, K, &dim) != ADAHOP_OK) return ADAHOP_E_INVALID_ARG;
+    const int b = strategy == ADAHOP_NONE ? 0 : iht_block;
+    if (!valid_iht_block(b) || (b > 0 && K % b != 0)) return ADAHOP_E_INVALID_ARG;
+    if (strategy != ADAHOP_NONE && b == 0) return ADAHOP_E_INVALID_ARG;
+    if (k < 0 || (dim > 0 && k > dim)) return ADAHOP_E_INVALID_ARG;
+    const bool oe = dim > 0 && k > 0;
+    if (oe && !idx_inout) return ADAHOP_E_INVALID_ARG;
+    adahop_ws_layout_t L;
+    rc = adahop_gemm_workspace_layout(M, N, K, strategy, k, &L);
+    if (rc != ADAHOP_OK) return rc;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return ADAHOP_E_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    uint8_t *a_codes = reinterpret_cast<uint8_t *>(ws + L.a_codes), *a_scales = reinterpret_cast<uint8_t *>(ws + L.a_scales);
+    uint8_t *b_codes = reinterpret_cast<uint8_t *>(ws + L.b_codes), *b_scales = reinterpret_cast<uint8_t *>(ws + L.b_scales);
+    uint8_t *mask = reinterpret_cast<uint8_t *>(ws + L.mask);
+    float *scores = reinterpret_cast<float *>(ws + L.scores);
+
+    // 1. which rows / columns / K-channels leave the MXFP4 path (App. F item 1)
+    if (oe) {
+        if (use_given_idx) {
+            rc = launch_mask_from_idx(idx_inout, k, mask, dim, st);
+        } else if (strategy == ADAHOP_IHT_OE_ROW) {
+            rc = launch_foid_topk(*A, 0, k, idx_inout, mask, scores, st);
+        } else if (strategy == ADAHOP_IHT_OE_COL) {
+            rc = launch_foid_topk(*B, 0, k, idx_inout, mask, scores, st);
+        } else {
+            rc = launch_foid_topk(*A, 1, k, idx_inout, mask, scores, st);
+        }
+        if (rc != ADAHOP_OK) return rc;
+    }
+    // 2. residual -> transform -> MXFP4 (App. F item 2)
+    const uint8_t *a_zo = (oe && strategy == ADAHOP_IHT_OE_ROW) ? mask : nullptr;
+    const uint8_t *b_zo = (oe && strategy == ADAHOP_IHT_OE_COL) ? mask : nullptr;
+    const uint8_t *zk = (oe && strategy == ADAHOP_IHT_OE_K) ? mask : nullptr;
+    rc = launch_iht_quantize(*A, b, a_zo, zk, a_codes, a_scales, st);
+    if (rc != ADAHOP_OK) return rc;
+    rc = launch_iht_quantize(*B, b, b_zo, zk, b_codes, b_scales, st);
+    if (rc != ADAHOP_OK) return rc;
+    // 3. MXFP4 product, with the K-channel BF16 product fused in front; 4. row / column BF16 product
+    if (oe && strategy == ADAHOP_IHT_OE_K) {
+        const int kpad = kpad_of(k);
+        uint16_t *Ag = reinterpret_cast<uint16_t *>(ws + L.gather_a), *Bg = reinterpret_cast<uint16_t *>(ws + L.gather_b);
+        rc = launch_gather_k(*A, idx_inout, k, kpad, Ag, st);
+        if (rc != ADAHOP_OK) return rc;
+        rc = launch_gather_k(*B, idx_inout, k, kpad, Bg, st);
+        if (rc != ADAHOP_OK) return rc;
+        return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, Ag, Bg, kpad, st);
+    }
+    rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0, st);
+    if (rc != ADAHOP_OK) return rc;
+    if (oe) rc = launch_oe_rowcol(*A, *B, strategy, idx_inout, k, C, ldc, st);
+    return rc;
+}
+
+} // extern "C"

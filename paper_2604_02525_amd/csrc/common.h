@@ -1,0 +1,53 @@
+// Shared host/device helpers of the AdaHOP HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/adahop.h"
+
+namespace adahop {
+
+// Records the hipError_t of a failed call for adahop_last_hip_error().
+void set_last_hip_error(int e);
+
+inline int check_hip(hipError_t e)
+{
+    if (e == hipSuccess) return ADAHOP_OK;
+    set_last_hip_error((int)e);
+    return ADAHOP_E_HIP;
+}
+
+inline int check_launch() { return check_hip(hipGetLastError()); }
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Argument checks shared by the entry points; all run before any HIP call.
+int validate_operand(const adahop_operand_t *x);
+bool valid_iht_block(int b);
+
+// Launchers (one per kernel family); each validates nothing and returns a status.
+int launch_iht_quantize(const adahop_operand_t &x, int iht_block, const uint8_t *zero_outer,
+                        const uint8_t *zero_k, uint8_t *codes, uint8_t *scales, hipStream_t st);
+int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, uint8_t *mask, float *scores,
+                     hipStream_t st);
+int launch_mask_from_idx(const int32_t *idx, int k, uint8_t *mask, int64_t dim, hipStream_t st);
+// OE-K operands for the fused prologue: Ag [M, kpad], Bg [N, kpad] bf16, K-contiguous, zero padded.
+int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc,
+                   const uint16_t *Ag, const uint16_t *Bg, int kpad, hipStream_t st);
+int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kpad, uint16_t *out, hipStream_t st);
+int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int kind, const int32_t *idx, int k,
+                     float *C, int64_t ldc, hipStream_t st);
+int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint16_t *Bg, int kpad, float *C,
+                           int64_t ldc, hipStream_t st);
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+#if defined(__HIPCC__)
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ float bf16_one(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+#endif
+
+} // namespace adahop

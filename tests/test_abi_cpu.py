@@ -1,0 +1,119 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function that
+include/adahop.h declares, and rejects bad arguments before touching HIP."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_02525_amd import binding as ah
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "adahop.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adahop_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 10
+    L = ah.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(ah.EXPORTS) == names
+    assert L.adahop_abi_version() == 1
+
+
+FAKE = 0x10000  # non-null, 16-byte aligned, never dereferenced on these paths
+
+
+def op(outer=64, K=128, ld=None, kc=1, data=FAKE):
+    return ah.adahop_operand_t(data, outer, K, K if ld is None and kc else (outer if ld is None else ld), kc)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(K=100), dict(K=0), dict(outer=0), dict(data=0), dict(data=FAKE + 2), dict(ld=120), dict(ld=132), dict(kc=2),
+])
+def test_quantize_rejects_bad_operands(bad):
+    L = ah.lib()
+    x = op(**bad)
+    assert L.adahop_quantize_mx(C.byref(x), FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_iht_quantize(C.byref(x), 32, None, None, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+
+
+def test_iht_quantize_rejects_bad_blocks_and_pointers():
+    L = ah.lib()
+    x = op(K=192)
+    for b in (16, 48, 512, -32):
+        assert L.adahop_iht_quantize(C.byref(x), b, None, None, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_iht_quantize(C.byref(x), 128, None, None, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG  # 192 % 128
+    assert L.adahop_iht_quantize(C.byref(x), 64, None, None, None, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_iht_quantize(C.byref(x), 64, None, FAKE + 4, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG  # mask align
+    assert L.adahop_iht_quantize(None, 64, None, None, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+
+
+def test_foid_rejects_bad_arguments():
+    L = ah.lib()
+    x = op()
+    assert L.adahop_foid_topk(C.byref(x), 2, 1, FAKE, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_foid_topk(C.byref(x), 0, 65, FAKE, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_foid_topk(C.byref(x), 1, 129, FAKE, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_foid_topk(C.byref(x), 0, -1, FAKE, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_foid_topk(C.byref(x), 0, 4, None, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+
+
+def test_gemm_mx_rejects_bad_arguments():
+    L = ah.lib()
+    ok = [64, 64, 128, FAKE, FAKE, FAKE, FAKE, FAKE, 64, None]
+    for pos, val in ((0, 0), (2, 48), (2, 0), (3, None), (7, None), (8, 63), (3, FAKE + 8)):
+        a = list(ok)
+        a[pos] = val
+        assert L.adahop_gemm_mx(*a) == ah.ADAHOP_E_INVALID_ARG, (pos, val)
+
+
+def test_gemm_argument_and_workspace_checks():
+    L = ah.lib()
+    A, B = op(64, 256), op(32, 256)
+    need = L.adahop_gemm_workspace_bytes(64, 32, 256, ah.ADAHOP_IHT_OE_K, 8)
+    lay = ah.adahop_gemm_workspace_layout(64, 32, 256, ah.ADAHOP_IHT_OE_K, 8)
+    assert need == lay.total and need % 256 == 0
+    offs = [lay.a_codes, lay.a_scales, lay.b_codes, lay.b_scales, lay.mask, lay.scores, lay.gather_a, lay.gather_b]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert lay.a_scales - lay.a_codes >= 64 * 128 and lay.gather_b - lay.gather_a >= 64 * 16 * 2
+    call = lambda **kw: L.adahop_gemm(C.byref(kw.get("A", A)), C.byref(kw.get("B", B)), kw.get("C", FAKE),
+                                      kw.get("ldc", 32), kw.get("s", ah.ADAHOP_IHT), kw.get("b", 64), kw.get("k", 0),
+                                      kw.get("idx", FAKE), 0, kw.get("ws", FAKE), kw.get("wsb", need), None)
+    assert call(B=op(32, 128)) == ah.ADAHOP_E_INVALID_ARG          # K mismatch
+    assert call(ldc=31) == ah.ADAHOP_E_INVALID_ARG
+    assert call(s=7) == ah.ADAHOP_E_INVALID_ARG
+    assert call(b=48) == ah.ADAHOP_E_INVALID_ARG
+    assert call(b=0) == ah.ADAHOP_E_INVALID_ARG                    # IHT strategies need a block
+    assert call(s=ah.ADAHOP_IHT_OE_ROW, k=65) == ah.ADAHOP_E_INVALID_ARG
+    assert call(s=ah.ADAHOP_IHT_OE_COL, k=33) == ah.ADAHOP_E_INVALID_ARG
+    assert call(s=ah.ADAHOP_IHT_OE_K, k=8, idx=None) == ah.ADAHOP_E_INVALID_ARG
+    assert call(ws=None) == ah.ADAHOP_E_WORKSPACE
+    assert call(ws=FAKE + 16) == ah.ADAHOP_E_WORKSPACE
+    assert call(s=ah.ADAHOP_IHT_OE_K, k=8, wsb=need - 1) == ah.ADAHOP_E_WORKSPACE
+    assert L.adahop_gemm_workspace_bytes(64, 32, 100, ah.ADAHOP_IHT, 0) == 0
+
+
+def test_oe_gemm_argument_checks():
+    L = ah.lib()
+    A, B = op(64, 256), op(32, 256)
+    f = lambda kind, idx, k, ws, wsb: L.adahop_oe_gemm_bf16(C.byref(A), C.byref(B), kind, idx, k, FAKE, 32, ws, wsb, None)
+    assert f(ah.ADAHOP_IHT, FAKE, 4, None, 0) == ah.ADAHOP_E_INVALID_ARG
+    assert f(ah.ADAHOP_IHT_OE_ROW, None, 4, None, 0) == ah.ADAHOP_E_INVALID_ARG
+    assert f(ah.ADAHOP_IHT_OE_ROW, FAKE, 65, None, 0) == ah.ADAHOP_E_INVALID_ARG
+    assert f(ah.ADAHOP_IHT_OE_K, FAKE, 4, None, 0) == ah.ADAHOP_E_WORKSPACE
+    assert f(ah.ADAHOP_IHT_OE_K, FAKE, 0, None, 0) == ah.ADAHOP_OK      # nothing to do
+    assert L.adahop_oe_gather_bytes(64, 32, 256, ah.ADAHOP_IHT_OE_K, 4) == 64 * 16 * 2 + 32 * 16 * 2
+
+
+def test_status_strings():
+    L = ah.lib()
+    assert L.adahop_status_string(0) == b"ok"
+    for s in (-1, -2, -3, -99):
+        assert len(L.adahop_status_string(s)) > 3

@@ -1,0 +1,296 @@
+"""GPU-vs-oracle parity through the C ABI (run with -m gpu on an MI355X).
+
+Bars: packed E2M1 codes, E8M0 scales, FOID indices and masks bit-exact; GEMM outputs within 1e-3
+relative Frobenius error of the oracle's emulated-MXFP4 result (the arithmetic only differs in fp32
+accumulation order, so the observed error is ~1e-6).
+"""
+import numpy as np
+import pytest
+
+from oracle import reference as orc
+from paper_2604_02525_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def ah():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2604_02525_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev_op(ah, op):
+    return ah.Operand.from_bits(op.bits, op.k_contig)
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def rel_fro(got, ref):
+    return float(np.linalg.norm(got.astype(np.float64) - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def rand_bits(rng, shape, scale=1.0):
+    x = torch.from_numpy((rng.standard_normal(shape) * scale).astype(np.float32))
+    return x.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def stored(bits_ok, k_contig, pad=0):
+    """bits_ok is logical [outer, K]; return the array as stored (optionally with ld > width)."""
+    a = bits_ok if k_contig else np.ascontiguousarray(bits_ok.T)
+    pad += (-(a.shape[1] + pad)) % 8          # the ABI wants ld to be a multiple of 8 elements
+    if pad:
+        wide = np.zeros((a.shape[0], a.shape[1] + pad), dtype=a.dtype)
+        wide[:, :a.shape[1]] = a
+        return wide, a.shape[1]
+    return a, a.shape[1]
+
+
+# ----------------------------------------------------------------------------- quantisers
+
+@pytest.mark.parametrize("k_contig", [True, False])
+@pytest.mark.parametrize("b", [0, 32, 64, 128, 256])
+def test_iht_quantize_bit_exact(ah, b, k_contig):
+    rng = np.random.default_rng(100 + b + int(k_contig))
+    for outer, K, pad, masks in ((77, 3 * max(b, 32), 0, False), (300, 4 * max(b, 32), 8, True),
+                                 (130, 1280 if b != 256 else 1280, 0, True), (1, max(b, 32), 0, False)):
+        if b and K % b:
+            K = (K // b + 1) * b
+        say("iht_quantize", dict(b=b, k_contig=k_contig, outer=outer, K=K, pad=pad, masks=masks))
+        logical = rand_bits(rng, (outer, K))
+        logical[rng.integers(0, outer), :] = 0                      # an all-zero row
+        logical[:, 5] = rand_bits(rng, (outer,), 60.0)              # an outlier channel
+        arr, width = stored(logical, k_contig, pad)
+        t = torch.from_numpy(arr.view(np.int16)).cuda()
+        x = ah.Operand(t[:, :width], k_contig)
+        zo = zk = zo_d = zk_d = None
+        if masks:
+            zo = (rng.random(outer) < 0.1).astype(np.uint8)
+            zk = (rng.random(K) < 0.05).astype(np.uint8)
+            zo_d, zk_d = torch.from_numpy(zo).cuda(), torch.from_numpy(zk).cuda()
+        codes, scales = ah.adahop_iht_quantize(x, b, zo_d, zk_d)
+        torch.cuda.synchronize()
+        rc, rs = orc.iht_quantize(arr[:, :width], k_contig, b, zo, zk)
+        assert np.array_equal(host(scales), rs)
+        assert np.array_equal(host(codes), rc)
+
+
+def test_quantize_mx_every_bf16_pattern_bit_exact(ah):
+    """Every finite bf16 value, placed so that it lands in each E2M1 binade (and in the saturating
+    range) relative to the block scale set by an anchor element."""
+    allbits = np.arange(65536, dtype=np.uint32)
+    vals = (allbits << 16).view(np.float32)
+    keep = np.isfinite(vals) & (np.abs(vals) > 2.0 ** -100) & (np.abs(vals) < 2.0 ** 100)
+    pats = allbits[keep].astype(np.uint16)
+    v = vals[keep]
+    e = np.floor(np.log2(np.abs(v))).astype(np.int64)
+    blocks = []
+    for shift in (-4, -3, -2, -1, 0, 1, 2):      # anchor = 2^(e - shift + 2): value/X falls in binade `shift`
+        anchor = np.exp2((e - shift + 2).astype(np.float64)).astype(np.float32)
+        anchor_bits = (anchor.view(np.uint32) >> 16).astype(np.uint16)
+        blk = np.zeros((len(pats), 32), dtype=np.uint16)
+        blk[:, 0] = anchor_bits
+        blk[:, 7] = pats
+        blk[:, 30] = pats ^ 0x8000
+        blocks.append(blk)
+    # value itself is the block maximum (exercises saturation: value / X in [4, 8))
+    blk = np.zeros((len(pats), 32), dtype=np.uint16)
+    blk[:, 3] = pats
+    blocks.append(blk)
+    logical = np.concatenate(blocks, axis=0)
+    say("quantize_mx all bf16 patterns", logical.shape)
+    for k_contig in (True, False):
+        arr, width = stored(logical, k_contig)
+        x = ah.Operand(torch.from_numpy(arr.view(np.int16)).cuda()[:, :width], k_contig)
+        codes, scales = ah.adahop_quantize_mx(x)
+        torch.cuda.synchronize()
+        rc, rs = orc.quantize_mx(arr[:, :width], k_contig)
+        assert np.array_equal(host(scales), rs)
+        assert np.array_equal(host(codes), rc)
+
+
+# ----------------------------------------------------------------------------- FOID
+
+@pytest.mark.parametrize("k_contig", [True, False])
+@pytest.mark.parametrize("axis", [0, 1])
+def test_foid_topk_bit_exact(ah, axis, k_contig):
+    rng = np.random.default_rng(7 + axis * 2 + int(k_contig))
+    for outer, K, ks in ((200, 96, (0, 1, 7, 96)), (4100, 160, (41, 160)), (40, 2080, (13,)), (28672, 64, (574, 72))):
+        logical = rand_bits(rng, (outer, K))
+        dim = outer if axis == 0 else K
+        hot = rng.permutation(dim)[:5]
+        if axis == 0:
+            logical[hot, :] = rand_bits(rng, (5, K), 30.0)
+        else:
+            logical[:, hot] = rand_bits(rng, (outer, 5), 30.0)
+        dup = rng.permutation(dim)[:6]              # exact score ties: identical sample windows
+        if axis == 0:
+            logical[dup[1::2], :64] = logical[dup[0::2], :64]
+        else:
+            logical[:64, dup[1::2]] = logical[:64, dup[0::2]]
+        arr, width = stored(logical, k_contig)
+        x = ah.Operand(torch.from_numpy(arr.view(np.int16)).cuda()[:, :width], k_contig)
+        ref_scores = orc.foid_scores(arr[:, :width], k_contig, axis)
+        for k in ks:
+            k = min(k, dim)
+            say("foid_topk", dict(axis=axis, k_contig=k_contig, outer=outer, K=K, k=k))
+            idx, mask, scores = ah.adahop_foid_topk(x, axis, k)
+            torch.cuda.synchronize()
+            assert np.array_equal(host(scores).view(np.uint32), ref_scores.view(np.uint32))
+            ridx, rmask = orc.topk(ref_scores, k)
+            assert np.array_equal(host(idx), ridx)
+            assert np.array_equal(host(mask), rmask)
+
+
+# ----------------------------------------------------------------------------- MXFP4 product
+
+@pytest.mark.parametrize("shape", [(32, 32, 64), (128, 128, 256), (200, 136, 96), (257, 129, 32), (64, 384, 1056),
+                                   (512, 512, 512)])
+def test_gemm_mx_matches_emulation(ah, shape):
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + K)
+    a_codes = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    b_codes = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    a_scales = rng.integers(117, 137, size=(M, K // 32), dtype=np.uint8)
+    b_scales = rng.integers(100, 120, size=(N, K // 32), dtype=np.uint8)
+    say("gemm_mx", shape)
+    C = ah.adahop_gemm_mx(*(torch.from_numpy(t).cuda() for t in (a_codes, a_scales, b_codes, b_scales)))
+    torch.cuda.synchronize()
+    ref = orc.mx_gemm(a_codes, a_scales, b_codes, b_scales)
+    err = rel_fro(host(C), ref)
+    say("  rel_fro", err)
+    assert err < 1e-3
+    assert err < 1e-5        # what the arithmetic predicts; a layout mistake gives O(1)
+
+
+def test_gemm_mx_single_nonzero_probes_operand_layout(ah):
+    """One nonzero code per operand at a time: the product must land in exactly one output element
+    with exactly the right value, for positions covering every lane group, nibble and scale slot."""
+    M = N = 64
+    K = 128
+    for (m, ka, code_a, sa), (n, code_b, sb) in [((0, 0, 7, 127), (0, 2, 127)), ((33, 37, 3, 130), (5, 6, 120)),
+                                                 ((63, 127, 15, 125), (63, 9, 129)), ((17, 64, 5, 127), (40, 12, 127)),
+                                                 ((8, 95, 1, 127), (31, 1, 126))]:
+        a_codes = np.zeros((M, K // 2), np.uint8)
+        b_codes = np.zeros((N, K // 2), np.uint8)
+        a_scales = np.full((M, K // 32), 127, np.uint8)
+        b_scales = np.full((N, K // 32), 127, np.uint8)
+        a_codes[m, ka // 2] = code_a << (4 * (ka & 1))
+        b_codes[n, ka // 2] = code_b << (4 * (ka & 1))
+        a_scales[m, ka // 32] = sa
+        b_scales[n, ka // 32] = sb
+        say("gemm_mx probe", (m, n, ka))
+        C = host(ah.adahop_gemm_mx(*(torch.from_numpy(t).cuda() for t in (a_codes, a_scales, b_codes, b_scales))))
+        ref = orc.mx_gemm(a_codes, a_scales, b_codes, b_scales)
+        assert np.count_nonzero(ref) == 1
+        assert np.array_equal(C.astype(np.float64), ref)
+
+
+# ----------------------------------------------------------------------------- whole path
+
+def run_whole(ah, g, rows=None, cols=None, given_idx=None, tol=1e-3):
+    A, B = dev_op(ah, g.A), dev_op(ah, g.B)
+    idx_d = None if given_idx is None else torch.from_numpy(np.asarray(given_idx, dtype=np.int32)).cuda()
+    out = ah.adahop_gemm(A, B, g.strategy, g.iht_block, g.k, idx=idx_d)
+    torch.cuda.synchronize()
+    ref = orc.adahop_gemm(g.A.bits, g.A.k_contig, g.B.bits, g.B.k_contig, g.strategy, g.iht_block, g.k,
+                          idx=given_idx, rows=rows, cols=cols)
+    if g.strategy >= inputs.IHT_OE_ROW and g.k > 0:
+        got_idx = np.sort(host(out["idx"]))
+        assert np.array_equal(got_idx, ref["idx"]), "extraction indices differ"
+        mask = np.zeros(out["mask"].numel(), np.uint8)
+        mask[ref["idx"]] = 1
+        assert np.array_equal(host(out["mask"]), mask)
+    for name in ("a_scales", "b_scales", "a_codes", "b_codes"):
+        assert np.array_equal(host(out[name]), ref[name]), name
+    C = out["C"]
+    if rows is not None:
+        C = C[torch.from_numpy(np.asarray(rows, dtype=np.int64)).cuda()]
+    if cols is not None:
+        C = C[:, torch.from_numpy(np.asarray(cols, dtype=np.int64)).cuda()]
+    got = host(C)
+    err = rel_fro(got, ref["C"])
+    exact = orc.exact_gemm(g.A.bits, g.A.k_contig, g.B.bits, g.B.k_contig, rows=rows, cols=cols)
+    q = rel_fro(got, exact)
+    say(f"  {g.name} {inputs.STRATEGY_NAMES[g.strategy]} b={g.iht_block} k={g.k} shape={g.shape}: "
+        f"vs oracle {err:.3e}, vs exact product {q:.3e}")
+    assert err < tol
+    return err, q
+
+
+def test_config0_iht_and_none(ah):
+    g = inputs.config0()[0]
+    say("config0 IHT")
+    _, q_iht = run_whole(ah, g)
+    g.strategy = inputs.NONE
+    say("config0 none")
+    _, q_none = run_whole(ah, g)
+    assert q_iht < q_none                      # CN pair: the transform must help (paper Sec. 3.2)
+
+
+LAYOUTS = {"fwd": (True, True), "dgrad": (True, False), "wgrad": (False, False)}
+
+
+@pytest.mark.parametrize("kind", ["fwd", "dgrad", "wgrad"])
+@pytest.mark.parametrize("strategy", [inputs.IHT, inputs.IHT_OE_ROW, inputs.IHT_OE_COL, inputs.IHT_OE_K])
+def test_whole_path_small_all_layouts(ah, strategy, kind):
+    """Ragged M and N spanning several workgroup tiles; K spans several transform blocks."""
+    M, N, K, b = 328, 200, 512, 128
+    a_kc, b_kc = LAYOUTS[kind]
+    A_log = inputs.matrix(M, K, 1.0, 50, row_outliers=(5, 100.0, 100.0), col_outliers=(6, 50.0, 50.0))
+    B_log = inputs.matrix(N, K, 0.02, 51, row_outliers=(4, 30.0, 30.0))
+    A = inputs.Operand(A_log if a_kc else np.ascontiguousarray(A_log.T), a_kc)
+    B = inputs.Operand(B_log if b_kc else np.ascontiguousarray(B_log.T), b_kc)
+    k = {inputs.IHT: 0, inputs.IHT_OE_ROW: 9, inputs.IHT_OE_COL: 7, inputs.IHT_OE_K: 21}[strategy]
+    g = inputs.Gemm(f"small.{kind}", A, B, strategy, b, k)
+    say("whole path", kind, inputs.STRATEGY_NAMES[strategy])
+    run_whole(ah, g)
+    if k:
+        given = np.random.default_rng(5).permutation({inputs.IHT_OE_ROW: M, inputs.IHT_OE_COL: N,
+                                                      inputs.IHT_OE_K: K}[strategy])[:k].astype(np.int32)
+        say("whole path, caller-chosen indices", kind, inputs.STRATEGY_NAMES[strategy])
+        run_whole(ah, g, given_idx=given)
+
+
+def test_oe_k_zero_equals_iht(ah):
+    g = inputs.config0()[0]
+    A, B = dev_op(ah, g.A), dev_op(ah, g.B)
+    say("k=0 equals IHT")
+    c_iht = host(ah.adahop_gemm(A, B, inputs.IHT, 32)["C"])
+    for s in (inputs.IHT_OE_ROW, inputs.IHT_OE_COL, inputs.IHT_OE_K):
+        assert np.array_equal(host(ah.adahop_gemm(A, B, s, 32, 0)["C"]), c_iht)
+
+
+def test_oe_gemm_bf16_standalone(ah):
+    rng = np.random.default_rng(3)
+    M, N, K = 152, 88, 160
+    for a_kc, b_kc in LAYOUTS.values():
+        A_log, B_log = rand_bits(rng, (M, K)), rand_bits(rng, (N, K), 0.05)
+        A = inputs.Operand(A_log if a_kc else np.ascontiguousarray(A_log.T), a_kc)
+        B = inputs.Operand(B_log if b_kc else np.ascontiguousarray(B_log.T), b_kc)
+        dA, dB = dev_op(ah, A), dev_op(ah, B)
+        for kind, dim, k in ((inputs.IHT_OE_ROW, M, 37), (inputs.IHT_OE_COL, N, 5), (inputs.IHT_OE_K, K, 19)):
+            sel = np.sort(rng.permutation(dim)[:k]).astype(np.int32)
+            base = rng.standard_normal((M, N)).astype(np.float32)
+            C = torch.from_numpy(base.copy()).cuda()
+            say("oe_gemm_bf16", dict(a_kc=a_kc, b_kc=b_kc, kind=kind, k=k))
+            ah.adahop_oe_gemm_bf16(dA, dB, kind, torch.from_numpy(sel).cuda(), C)
+            torch.cuda.synchronize()
+            want = base.astype(np.float64)
+            if kind == inputs.IHT_OE_ROW:
+                want[sel, :] = orc.bf16_gemm(A.bits, a_kc, B.bits, b_kc, rows=sel)
+            elif kind == inputs.IHT_OE_COL:
+                want[:, sel] = orc.bf16_gemm(A.bits, a_kc, B.bits, b_kc, cols=sel)
+            else:
+                want += orc.bf16_gemm(A.bits, a_kc, B.bits, b_kc, ksel=sel)
+            assert rel_fro(host(C), want) < 1e-5
