@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdaHOP per-GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg4-up|cfg1|cfg0]
+
+A step is one pass of the whole path (FOID -> residual masking -> IHT -> MX quantise -> MXFP4 GEMM
+-> BF16 outlier GEMM -> sum) over every GEMM of the workload, operands resident in HBM.  Prints one
+JSON line: the effective TFLOP/s of the step (sum of 2MNK over the GEMMs / time), the roofline of
+the dominant kernel (the block-scaled FP4 GEMM) measured with HIP events on the launch stream, and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+MXFP4_PEAK_TFLOPS = 10066.0   # MI355X dense FP4 matrix-core peak: 256 CU x 16384 flop/clk x 2.4 GHz
+BF16_PEAK_TFLOPS = 2516.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=10)
+    p.add_argument("--warmup", type=int, default=3)
+    p.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg4-up", "cfg1", "cfg0"])
+    p.add_argument("--k-pct", type=float, default=1.0, help="extraction count as %% of the extracted dim (cfg4)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-extras", action="store_true", help="skip the k-sweep / BF16 / per-stage extras")
+    return p.parse_args()
+
+
+def build_workload(name, k_pct):
+    from paper_2604_02525_amd import inputs
+    I = inputs
+    if name == "cfg0":
+        return "configs[0]: M=N=K=256, IHT block 32", I.config0()
+    if name == "cfg1":
+        return "configs[1]: fwd X[8192,2048] W[8192,2048], IHT block 128", I.config1()
+    which = ("up",) if name == "cfg4-up" else ("up", "down")
+    # fwd: activation channel outliers are K-channels of A; dgrad: gradient token rows are rows of A;
+    # wgrad: gradient token rows are K-channels of A = G_Y^T.
+    strategies = (I.IHT_OE_K, I.IHT_OE_ROW, I.IHT_OE_K) if k_pct > 0 else (I.IHT, I.IHT, I.IHT)
+    desc = (f"configs[4]: T=16384, {'+'.join(which)} 8192<->28672, fwd+dgrad+wgrad, IHT block 256, "
+            f"fwd/wgrad OE-K, dgrad OE-row, k={k_pct}% of the extracted dim")
+    return desc, I.config4(which=which, strategies=strategies, k_pct=k_pct)
+
+
+class Prepared:
+    """Device operands, output and workspace of one GEMM, allocated once outside the timed region."""
+
+    def __init__(self, ah, torch, g, cache):
+        def dev(op):
+            key = id(op.bits)
+            if key not in cache:
+                cache[key] = torch.from_numpy(op.bits.view(np.int16)).cuda()
+            return ah.Operand(cache[key], op.k_contig)
+        self.g = g
+        self.A, self.B = dev(g.A), dev(g.B)
+        self.M, self.N, self.K = g.shape
+        self.flops = 2.0 * self.M * self.N * self.K
+        self.C = torch.empty((self.M, self.N), dtype=torch.float32, device="cuda")
+        self.idx = torch.zeros(max(g.k, 1), dtype=torch.int32, device="cuda")
+
+    def workspace(self, ah, torch, pool):
+        need = ah.adahop_gemm_workspace_bytes(self.M, self.N, self.K, self.g.strategy, self.g.k)
+        if pool.get("ws") is None or pool["ws"].numel() < need:
+            pool["ws"] = torch.empty(need, dtype=torch.uint8, device="cuda")
+        return pool["ws"]
+
+
+def run_gemm(ah, p, ws, strategy=None, k=None):
+    import ctypes as C
+    s = p.g.strategy if strategy is None else strategy
+    kk = p.g.k if k is None else k
+    rc = ah.lib().adahop_gemm(C.byref(p.A.c()), C.byref(p.B.c()), p.C.data_ptr(), p.C.stride(0), s, p.g.iht_block, kk,
+                              p.idx.data_ptr(), 0, ws.data_ptr(), ws.numel(), ah._stream(None))
+    if rc != 0:
+        raise ah.AdahopError(rc, "adahop_gemm")
+
+
+def time_ms(torch, fn, iters, warmup=1):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def cpu_baseline(workload_gemms):
+    """The oracle, as it stands, on a bounded slab of the first GEMM of the workload."""
+    from oracle import reference as orc
+    g = workload_gemms[0]
+    M, N, K = g.shape
+    ms, ns = min(M, 1024), min(N, 2048)
+    a = g.A.bits[:ms] if g.A.k_contig else g.A.bits[:, :ms]
+    b = g.B.bits[:ns] if g.B.k_contig else g.B.bits[:, :ns]
+    k = min(g.k, {2: ms, 3: ns, 4: K}.get(g.strategy, 0))
+    t0 = time.perf_counter()
+    orc.adahop_gemm(a, g.A.k_contig, b, g.B.k_contig, g.strategy, g.iht_block, k)
+    dt = time.perf_counter() - t0
+    return {"value": 2.0 * ms * ns * K / dt / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"whole path of {g.name} cropped to M={ms}, N={ns}, K={K} ({dt:.1f} s)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported", file=sys.stderr)
+        return 2
+    import torch
+    from paper_2604_02525_amd import binding as ah, inputs
+    ah.lib()
+    torch.cuda.set_device(0)
+
+    desc, gemms = build_workload(args.workload, args.k_pct)
+    cache, pool = {}, {}
+    prepared = [Prepared(ah, torch, g, cache) for g in gemms]
+    for p in prepared:
+        p.workspace(ah, torch, pool)
+    ws = pool["ws"]
+    total_flops = sum(p.flops for p in prepared)
+
+    def step():
+        for p in prepared:
+            run_gemm(ah, p, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = max(e0.elapsed_time(e1) / args.steps, 0.0)
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    # Dominant kernel: the FP4 GEMM alone on the largest GEMM's quantised operands.
+    big = max(prepared, key=lambda p: p.flops)
+    run_gemm(ah, big, ws, strategy=inputs.IHT, k=0)
+    L = ah.adahop_gemm_workspace_layout(big.M, big.N, big.K, inputs.IHT, 0)
+    view = lambda off, n: ws[off:off + n]
+    ac, asc = view(L.a_codes, big.M * big.K // 2), view(L.a_scales, big.M * big.K // 32)
+    bc, bsc = view(L.b_codes, big.N * big.K // 2), view(L.b_scales, big.N * big.K // 32)
+    ac, asc = ac.view(big.M, -1), asc.view(big.M, -1)
+    bc, bsc = bc.view(big.N, -1), bsc.view(big.N, -1)
+    gemm_ms = time_ms(torch, lambda: ah.adahop_gemm_mx(ac, asc, bc, bsc, big.C), max(5, args.steps))
+    achieved = big.flops / (gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "mxfp4 gemm", "achieved": achieved, "peak": MXFP4_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / MXFP4_PEAK_TFLOPS, "traffic": None,
+                "shape": [big.M, big.N, big.K], "ms": gemm_ms}
+
+    out = {"metric": "effective TFLOP/s of IHT+MXFP4(+OE) GEMM vs BF16 GEMM; % MXFP4 MFMA peak",
+           "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "mxfp4 (e2m1 x e8m0) with fp32 accumulate; bf16 outlier path", "data": "synthetic",
+           "config": {"workload": desc, "gemms": [p.g.name for p in prepared], "flops_per_step": total_flops},
+           "pct_mxfp4_peak": 100.0 * value / MXFP4_PEAK_TFLOPS, "wall_ms_per_step": wall_ms, "roofline": roofline}
+
+    if not args.no_extras:
+        extras = {}
+        # per-GEMM pipeline time and the same GEMM with pure IHT (no extraction)
+        per = []
+        for p in prepared:
+            t_cfg = time_ms(torch, lambda: run_gemm(ah, p, ws), 5)
+            t_iht = time_ms(torch, lambda: run_gemm(ah, p, ws, strategy=inputs.IHT, k=0), 5)
+            a16 = p.A.tensor.view(torch.bfloat16)
+            b16 = p.B.tensor.view(torch.bfloat16)
+            am = a16 if p.A.k_contig else a16.t()
+            bm = b16.t() if p.B.k_contig else b16
+            t_bf16 = time_ms(torch, lambda: torch.matmul(am, bm), 5)
+            per.append({"name": p.g.name, "shape": [p.M, p.N, p.K], "strategy": inputs.STRATEGY_NAMES[p.g.strategy],
+                        "k": p.g.k, "ms": t_cfg, "tflops": p.flops / t_cfg / 1e9, "ms_iht_only": t_iht,
+                        "tflops_iht_only": p.flops / t_iht / 1e9, "oe_overhead_pct": 100.0 * (t_cfg - t_iht) / t_iht,
+                        "ms_bf16_hipblaslt": t_bf16, "tflops_bf16_hipblaslt": p.flops / t_bf16 / 1e9,
+                        "speedup_vs_bf16": t_bf16 / t_cfg})
+        extras["per_gemm"] = per
+        t_iht_total = sum(x["ms_iht_only"] for x in per)
+        extras["iht_only_tflops"] = total_flops / t_iht_total / 1e9
+        extras["iht_only_pct_mxfp4_peak"] = 100.0 * extras["iht_only_tflops"] / MXFP4_PEAK_TFLOPS
+        extras["bf16_hipblaslt_tflops"] = total_flops / sum(x["ms_bf16_hipblaslt"] for x in per) / 1e9
+        # quantiser bandwidth on the largest operand of the largest GEMM (2 + 1/2 + 1/32 bytes / element)
+        qx = big.B if big.N >= big.M else big.A
+        codes = torch.empty((qx.outer, qx.K // 2), dtype=torch.uint8, device="cuda")
+        scales = torch.empty((qx.outer, qx.K // 32), dtype=torch.uint8, device="cuda")
+        q_ms = time_ms(torch, lambda: ah.adahop_iht_quantize(qx, big.g.iht_block, None, None, codes, scales), 10)
+        extras["iht_quantize"] = {"outer": qx.outer, "K": qx.K, "k_contig": qx.k_contig, "ms": q_ms,
+                                  "GBps": 2.53125 * qx.outer * qx.K / (q_ms * 1e-3) / 1e9, "peak_GBps": 8000.0}
+        out["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(gemms)
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

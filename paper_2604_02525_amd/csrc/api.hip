@@ -25,7 +25,8 @@ int validate_operand(const adahop_operand_t *x)
     return ADAHOP_OK;
 }
 
-static int kpad_of(int k) { return (k + 15) / 16 * 16; }
+// gathered K-channels are zero-padded to whole 64-channel pipeline stages of the GEMM
+static int kpad_of(int k) { return (k + 63) / 64 * 64; }
 
 static int extracted_dim(adahop_strategy_t s, int64_t M, int64_t N, int64_t K, int64_t *dim)
 {

@@ -82,7 +82,7 @@ def test_gemm_argument_and_workspace_checks():
     assert need == lay.total and need % 256 == 0
     offs = [lay.a_codes, lay.a_scales, lay.b_codes, lay.b_scales, lay.mask, lay.scores, lay.gather_a, lay.gather_b]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
-    assert lay.a_scales - lay.a_codes >= 64 * 128 and lay.gather_b - lay.gather_a >= 64 * 16 * 2
+    assert lay.a_scales - lay.a_codes >= 64 * 128 and lay.gather_b - lay.gather_a >= 64 * 64 * 2
     call = lambda **kw: L.adahop_gemm(C.byref(kw.get("A", A)), C.byref(kw.get("B", B)), kw.get("C", FAKE),
                                       kw.get("ldc", 32), kw.get("s", ah.ADAHOP_IHT), kw.get("b", 64), kw.get("k", 0),
                                       kw.get("idx", FAKE), 0, kw.get("ws", FAKE), kw.get("wsb", need), None)
@@ -109,7 +109,7 @@ def test_oe_gemm_argument_checks():
     assert f(ah.ADAHOP_IHT_OE_ROW, FAKE, 65, None, 0) == ah.ADAHOP_E_INVALID_ARG
     assert f(ah.ADAHOP_IHT_OE_K, FAKE, 4, None, 0) == ah.ADAHOP_E_WORKSPACE
     assert f(ah.ADAHOP_IHT_OE_K, FAKE, 0, None, 0) == ah.ADAHOP_OK      # nothing to do
-    assert L.adahop_oe_gather_bytes(64, 32, 256, ah.ADAHOP_IHT_OE_K, 4) == 64 * 16 * 2 + 32 * 16 * 2
+    assert L.adahop_oe_gather_bytes(64, 32, 256, ah.ADAHOP_IHT_OE_K, 4) == 64 * 64 * 2 + 32 * 64 * 2
 
 
 def test_status_strings():

@@ -155,7 +155,7 @@ def test_foid_topk_bit_exact(ah, axis, k_contig):
 # ----------------------------------------------------------------------------- MXFP4 product
 
 @pytest.mark.parametrize("shape", [(32, 32, 64), (128, 128, 256), (200, 136, 96), (257, 129, 32), (64, 384, 1056),
-                                   (512, 512, 512)])
+                                   (256, 256, 256), (512, 512, 512), (768, 1280, 2304), (2304, 512, 256)])
 def test_gemm_mx_matches_emulation(ah, shape):
     M, N, K = shape
     rng = np.random.default_rng(M + N + K)
@@ -260,6 +260,18 @@ def test_whole_path_small_all_layouts(ah, strategy, kind):
                                                       inputs.IHT_OE_K: K}[strategy])[:k].astype(np.int32)
         say("whole path, caller-chosen indices", kind, inputs.STRATEGY_NAMES[strategy])
         run_whole(ah, g, given_idx=given)
+
+
+@pytest.mark.parametrize("strategy,k", [(inputs.IHT, 0), (inputs.IHT_OE_K, 5), (inputs.IHT_OE_K, 70),
+                                        (inputs.IHT_OE_ROW, 6), (inputs.IHT_OE_COL, 3)])
+def test_whole_path_tile_aligned_shape(ah, strategy, k):
+    """M, N, K multiples of 256: the tiled GEMM kernel (LDS-staged, K-channel part fused) runs."""
+    M, N, K = 768, 512, 1024
+    A = inputs.Operand(inputs.matrix(M, K, 1.0, 60, row_outliers=(4, 100.0, 100.0), col_outliers=(5, 50.0, 50.0)), True)
+    B = inputs.Operand(np.ascontiguousarray(inputs.matrix(N, K, 0.02, 61).T), False)
+    g = inputs.Gemm("tiled", A, B, strategy, 256, k)
+    say("tile-aligned whole path", inputs.STRATEGY_NAMES[strategy], k)
+    run_whole(ah, g)
 
 
 def test_oe_k_zero_equals_iht(ah):
