@@ -155,7 +155,8 @@ def main():
     bc, bsc = view(L.b_codes, big.N * big.K // 2), view(L.b_scales, big.N * big.K // 32)
     ac, asc = ac.view(big.M, -1), asc.view(big.M, -1)
     bc, bsc = bc.view(big.N, -1), bsc.view(big.N, -1)
-    gemm_ms = time_ms(torch, lambda: ah.adahop_gemm_mx(ac, asc, bc, bsc, big.C), max(5, args.steps))
+    gemm_ws = torch.empty(ah.adahop_gemm_mx_workspace_bytes(big.M, big.N, big.K), dtype=torch.uint8, device="cuda")
+    gemm_ms = time_ms(torch, lambda: ah.adahop_gemm_mx(ac, asc, bc, bsc, big.C, gemm_ws), max(5, args.steps))
     achieved = big.flops / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "mxfp4 gemm", "achieved": achieved, "peak": MXFP4_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MXFP4_PEAK_TFLOPS, "traffic": None,

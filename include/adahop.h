@@ -104,9 +104,15 @@ int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_ou
  *   C[m, n] = sum_blk 2^(sa[m,blk]-127) 2^(sb[n,blk]-127) sum_{i<32} a[m, 32 blk + i] b[n, 32 blk + i]
  * fp32 accumulation and output, C row-major with leading dimension ldc >= N.
  * codes / scales in the canonical layout above; codes 16-byte aligned, K % 32 == 0.
+ * workspace: device scratch of at least adahop_gemm_mx_workspace_bytes(M, N, K) bytes, 256-byte
+ * aligned (the kernel keeps a re-ordered copy of the scales there); contents undefined on return.
+ * Shapes with M % 256 == 0, N % 256 == 0, K % 256 == 0 take the tiled, LDS-pipelined kernel; any
+ * other shape takes a slower bounds-checked kernel with the same results.
  * ------------------------------------------------------------------------------------------- */
+size_t adahop_gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int adahop_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
-                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *stream);
+                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *workspace,
+                   size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * The whole path (App. F: FOID -> IHT + quantise -> MXFP4 product + BF16 outlier product -> sum).
@@ -126,6 +132,7 @@ typedef struct {
     size_t mask;                                 /* uint8 [extracted dim]           */
     size_t scores;                               /* float [extracted dim]           */
     size_t gather_a, gather_b;                   /* bf16 staging for the BF16 part  */
+    size_t gemm;                                 /* scratch of the MXFP4 product    */
     size_t total;                                /* bytes required                  */
 } adahop_ws_layout_t;
 

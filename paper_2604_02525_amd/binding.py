@@ -17,6 +17,7 @@ ADAHOP_NONE, ADAHOP_IHT, ADAHOP_IHT_OE_ROW, ADAHOP_IHT_OE_COL, ADAHOP_IHT_OE_K =
 ADAHOP_OK, ADAHOP_E_INVALID_ARG, ADAHOP_E_WORKSPACE, ADAHOP_E_HIP = 0, -1, -2, -3
 
 EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_gemm_mx",
+           "adahop_gemm_mx_workspace_bytes",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
            "adahop_oe_gemm_bf16", "adahop_last_hip_error", "adahop_status_string", "adahop_abi_version"]
 
@@ -36,7 +37,7 @@ class adahop_operand_t(C.Structure):
 
 class adahop_ws_layout_t(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("a_codes", "a_scales", "b_codes", "b_scales", "mask", "scores",
-                                          "gather_a", "gather_b", "total")]
+                                          "gather_a", "gather_b", "gemm", "total")]
 
 
 _lib = None
@@ -55,7 +56,9 @@ def lib():
         L.adahop_quantize_mx.argtypes = [OP, P, P, P]
         L.adahop_iht_quantize.argtypes = [OP, I, P, P, P, P, P]
         L.adahop_foid_topk.argtypes = [OP, I, I, P, P, P, P]
-        L.adahop_gemm_mx.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P]
+        L.adahop_gemm_mx.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P, SZ, P]
+        L.adahop_gemm_mx_workspace_bytes.argtypes = [I64, I64, I64]
+        L.adahop_gemm_mx_workspace_bytes.restype = SZ
         L.adahop_gemm_workspace_layout.argtypes = [I64, I64, I64, I, I, C.POINTER(adahop_ws_layout_t)]
         L.adahop_gemm_workspace_bytes.argtypes = [I64, I64, I64, I, I]
         L.adahop_gemm_workspace_bytes.restype = SZ
@@ -142,13 +145,19 @@ def adahop_foid_topk(x, axis, k, stream=None):
     return idx[:k], mask, scores
 
 
-def adahop_gemm_mx(a_codes, a_scales, b_codes, b_scales, Cout=None, stream=None):
+def adahop_gemm_mx_workspace_bytes(M, N, K):
+    return int(lib().adahop_gemm_mx_workspace_bytes(M, N, K))
+
+
+def adahop_gemm_mx(a_codes, a_scales, b_codes, b_scales, Cout=None, workspace=None, stream=None):
     M, N, K = a_codes.shape[0], b_codes.shape[0], a_codes.shape[1] * 2
     assert b_codes.shape[1] * 2 == K
     if Cout is None:
         Cout = torch.empty((M, N), dtype=torch.float32, device=a_codes.device)
+    if workspace is None:
+        workspace = _u8((adahop_gemm_mx_workspace_bytes(M, N, K),), a_codes.device)
     _check(lib().adahop_gemm_mx(M, N, K, _ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), _ptr(Cout),
-                                Cout.stride(0), _stream(stream)), "adahop_gemm_mx")
+                                Cout.stride(0), _ptr(workspace), workspace.numel(), _stream(stream)), "adahop_gemm_mx")
     return Cout
 
 

@@ -89,14 +89,23 @@ int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_ou
     return launch_foid_topk(*x, axis, k, idx_out, mask_out, scores_ws, static_cast<hipStream_t>(stream));
 }
 
+size_t adahop_gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M < 1 || N < 1 || K < 32 || K % 32 != 0 || M > MAX_OUTER || N > MAX_OUTER || K > MAX_K) return 0;
+    return gemm_mx_workspace_bytes(M, N, K);
+}
+
 int adahop_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
-                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *stream)
+                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *workspace,
+                   size_t workspace_bytes, void *stream)
 {
     if (M < 1 || N < 1 || K < 32 || K % 32 != 0 || M > MAX_OUTER || N > MAX_OUTER || K > MAX_K)
         return ADAHOP_E_INVALID_ARG;
     if (!a_codes || !a_scales || !b_codes || !b_scales || !C || ldc < N) return ADAHOP_E_INVALID_ARG;
     if (!aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(C, 4)) return ADAHOP_E_INVALID_ARG;
-    return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0,
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < gemm_mx_workspace_bytes(M, N, K))
+        return ADAHOP_E_WORKSPACE;
+    return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0, workspace,
                           static_cast<hipStream_t>(stream));
 }
 
@@ -123,6 +132,7 @@ int adahop_gemm_workspace_layout(int64_t M, int64_t N, int64_t K, adahop_strateg
     const bool oek = strategy == ADAHOP_IHT_OE_K && k > 0;
     out->gather_a = take(oek ? (size_t)M * kpad_of(k) * 2 : 0);
     out->gather_b = take(oek ? (size_t)N * kpad_of(k) * 2 : 0);
+    out->gemm = take(gemm_mx_workspace_bytes(M, N, K));
     out->total = off;
     return ADAHOP_OK;
 }
@@ -231,9 +241,9 @@ int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, 
         if (rc != ADAHOP_OK) return rc;
         rc = launch_gather_k(*B, idx_inout, k, kpad, Bg, st);
         if (rc != ADAHOP_OK) return rc;
-        return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, Ag, Bg, kpad, st);
+        return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, Ag, Bg, kpad, ws + L.gemm, st);
     }
-    rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0, st);
+    rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0, ws + L.gemm, st);
     if (rc != ADAHOP_OK) return rc;
     if (oe) rc = launch_oe_rowcol(*A, *B, strategy, idx_inout, k, C, ldc, st);
     return rc;

@@ -34,7 +34,8 @@ int launch_mask_from_idx(const int32_t *idx, int k, uint8_t *mask, int64_t dim, 
 // OE-K operands for the fused prologue: Ag [M, kpad], Bg [N, kpad] bf16, K-contiguous, zero padded.
 int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
                    const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc,
-                   const uint16_t *Ag, const uint16_t *Bg, int kpad, hipStream_t st);
+                   const uint16_t *Ag, const uint16_t *Bg, int kpad, void *workspace, hipStream_t st);
+size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kpad, uint16_t *out, hipStream_t st);
 int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int kind, const int32_t *idx, int k,
                      float *C, int64_t ldc, hipStream_t st);

@@ -122,71 +122,135 @@ __global__ __launch_bounds__(256) void k_gemm_mx_generic(int64_t M, int64_t N, i
 //
 // One workgroup (4 waves, 2x2) per 256x256 tile of C; each wave owns 128x128 = 4x4 matrix-core
 // tiles, i.e. 256 fp32 accumulators per lane, and the workgroup is alone on its compute unit.
-// A pipeline stage holds 128 bytes of K per row for the 256 A rows and the 256 B rows (64 KiB):
-// either 256 FP4 K-elements (8 MX blocks) or 64 gathered bf16 K-channels.  Two stages are double
-// buffered; global memory is copied straight into LDS (global_load_lds, 16 bytes per lane) while
-// the matrix cores work on the other stage, with one barrier per stage.
 //
-// LDS layout of an operand slab: row r at r*128, its 16-byte chunk c stored at chunk position
-// c ^ (r & 7), which makes both the DMA writes (8 rows x 8 chunks per wave instruction, linear in
-// the lane id) and the 16-byte fragment reads (32 consecutive rows, same logical chunk) free of
-// bank conflicts.
+// Pipeline.  A stage holds 128 bytes of K per row for the 256 A rows and the 256 B rows -- 256 FP4
+// K-elements (8 MX blocks, four matrix-core steps) or 64 gathered bf16 K-channels -- plus the 8 scale
+// bytes per row: 68 KiB.  Two stages rotate in LDS and global memory is copied straight into LDS
+// (global_load_lds): whole 128-byte lines per row, which is what the vector L1 moves fastest.  The
+// one barrier per stage sits before the last matrix-core step of the stage: by then every wave has
+// read its last fragments of the stage, so that buffer is refilled at once (the copy for stage t+2
+// runs during the last step of stage t and all of stage t+1), and the next stage has landed, so its
+// first fragments are read while the last step still runs.
+//
+// LDS layout of an operand slab: row r at r*128, its 16-byte chunk c at chunk position
+// c ^ ((r / 2) & 7).  The LDS has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a
+// time; 16 consecutive rows of one logical chunk then cover all 64 banks exactly once, and the DMA
+// writes (8 rows x 8 chunks per wave instruction, linear in the lane id) are conflict-free too.
 //
 // K order: within a stage lane-half h of matrix-core step s takes chunk 4h+s (for FP4: MX block
 // 4h+s), the same for A and B, so the four scale bytes a lane needs for a stage are one aligned
-// dword of the canonical scale array and the step's byte is picked by the instruction's op_sel.
+// dword and the step's byte is picked by the instruction's op_sel.
+//
+// Scales reach LDS by DMA as well, so the main loop has no register-targeted global loads and only
+// waits where the kernel says so.  Fetching 8 bytes per row from the canonical [rows, K/32] array
+// would cost one cache-line request per row and stage -- as many requests as the codes need -- so a
+// small pre-pass (k_stage_major_scales) first rewrites the scales stage-major, [K/256][rows][8],
+// where the 256 rows of a slab are 2 KiB contiguous.
 // ------------------------------------------------------------------------------------------------
-constexpr int TM = 256, TN = 256, TKB = 128;
-constexpr int STAGE_BYTES = (TM + TN) * TKB;
+constexpr int TM = 256, TN = 256, TKB = 128, NSTAGE = 2;
+constexpr int SLAB_BYTES = (TM + TN) * TKB;             // codes (or gathered bf16) of one stage
+constexpr int STAGE_BYTES = SLAB_BYTES + (TM + TN) * 8; // + 8 scale bytes per row
+constexpr int TILED_LDS_BYTES = NSTAGE * STAGE_BYTES;
 
-typedef __attribute__((address_space(1))) const void *gptr_t;
-typedef __attribute__((address_space(3))) void *lptr_t;
-
-template <int S>
-__device__ __forceinline__ void stage_step_fp4(const uint8_t *sA, const uint8_t *sB, int off, v16f (&acc)[4][4],
-                                               const int (&sa)[4], const int (&sb)[4])
+// out[s][row][0..7] = in[row][8s .. 8s+7]   (8-byte units; KB8 = K/256 units per row)
+__global__ __launch_bounds__(256) void k_stage_major_scales(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
+                                                            int64_t rows, int64_t KB8)
 {
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= rows * KB8) return;
+    const int64_t s = g / rows, r = g - s * rows; // consecutive threads: consecutive rows (coalesced writes)
+    out[g] = in[r * KB8 + s];
+}
+
+// Copies from global memory straight into LDS: lane i's 16 bytes land at lds_addr + 16 i (lds_addr
+// wave-uniform).  Inline assembly on purpose: with the builtin the compiler's wait-count pass makes
+// every later LDS read wait for ALL outstanding copies (it cannot tell that they target the other
+// stage), which serialises the copies with the matrix-core work.  The kernel waits for the copies
+// itself (s_waitcnt vmcnt(0) before the stage barrier).  M0 is written here and used by nothing else
+// in these kernels (no dynamic register indexing, no other DMA).
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+struct frags_t {
     uint4 a[4], b[4];
+};
+
+// Fragments of one matrix-core step for this lane: rows l32 (+32 i) of the wave's A and B slabs.
+__device__ __forceinline__ void read_frags(const uint8_t *sA, const uint8_t *sB, int off, frags_t &f)
+{
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        a[i] = *reinterpret_cast<const uint4 *>(sA + i * 4096 + off);
-        b[i] = *reinterpret_cast<const uint4 *>(sB + i * 4096 + off);
+        f.a[i] = *reinterpret_cast<const uint4 *>(sA + i * 32 * TKB + off);
+        f.b[i] = *reinterpret_cast<const uint4 *>(sB + i * 32 * TKB + off);
     }
+}
+
+struct scales_t {
+    int a[4], b[4];
+};
+
+__device__ __forceinline__ void read_scales(const uint8_t *sSa, const uint8_t *sSb, scales_t &sc)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        sc.a[i] = *reinterpret_cast<const int *>(sSa + i * 32 * 8);
+        sc.b[i] = *reinterpret_cast<const int *>(sSb + i * 32 * 8);
+    }
+}
+
+template <int S> __device__ __forceinline__ void mma_fp4(const frags_t &f, v16f (&acc)[4][4], const scales_t &sc)
+{
+#ifdef ADAHOP_DBG_NO_MMA
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j][S] += __int_as_float((f.a[i].x ^ f.b[j].y ^ sc.a[i] ^ sc.b[j]) & 0x3fffffff);
+    return;
+#endif
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            v8i av = {(int)a[i].x, (int)a[i].y, (int)a[i].z, (int)a[i].w, 0, 0, 0, 0};
-            v8i bv = {(int)b[j].x, (int)b[j].y, (int)b[j].z, (int)b[j].w, 0, 0, 0, 0};
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc[i][j], 4, 4, S, sa[i], S, sb[j]);
+            v8i av = {(int)f.a[i].x, (int)f.a[i].y, (int)f.a[i].z, (int)f.a[i].w, 0, 0, 0, 0};
+            v8i bv = {(int)f.b[j].x, (int)f.b[j].y, (int)f.b[j].z, (int)f.b[j].w, 0, 0, 0, 0};
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc[i][j], 4, 4, S, sc.a[i], S, sc.b[j]);
         }
 }
 
-__device__ __forceinline__ void stage_step_bf16(const uint8_t *sA, const uint8_t *sB, int off, v16f (&acc)[4][4])
+__device__ __forceinline__ void mma_bf16(const frags_t &f, v16f (&acc)[4][4])
 {
-    uint4 a[4], b[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        a[i] = *reinterpret_cast<const uint4 *>(sA + i * 4096 + off);
-        b[i] = *reinterpret_cast<const uint4 *>(sB + i * 4096 + off);
-    }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
+        for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16(f.a[i], f.b[j], acc[i][j]);
 }
 
+// Keeps the instruction scheduler from moving LDS reads and matrix-core instructions across this
+// point (one wave per SIMD: the order written here is what hides the LDS latency).
+#define ADAHOP_PIN() __builtin_amdgcn_sched_barrier(0)
+
+// BF16 = true: the stage loop over the gathered bf16 K-channels; false: the FP4 stages.  The two
+// loops run back to back on one pipeline: `stage` counts over both.
 template <bool OEK>
 __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_t *__restrict__ a_codes,
-                                                         const uint8_t *__restrict__ a_scales,
+                                                         const uint8_t *__restrict__ a_scales_sm,
                                                          const uint8_t *__restrict__ b_codes,
-                                                         const uint8_t *__restrict__ b_scales, float *__restrict__ C,
-                                                         int64_t ldc, const uint16_t *__restrict__ Ag,
+                                                         const uint8_t *__restrict__ b_scales_sm, int64_t M, int64_t N,
+                                                         float *__restrict__ C, int64_t ldc,
+                                                         const uint16_t *__restrict__ Ag,
                                                          const uint16_t *__restrict__ Bg, int kpad, int tiles_m,
                                                          int tiles_n, int group_m)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with its
     // own L2), so give every XCD a contiguous run of the tile sequence, and order that sequence in
@@ -202,46 +266,57 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     const int64_t m0 = (int64_t)tm * TM, n0 = (int64_t)tn * TN;
     const int wm = w >> 1, wn = w & 1;
 
-    // ---- copy engine: wave w moves rows [64w, 64w+64) of both slabs, 8 rows per instruction
+    // ---- copy engine: wave w moves rows [64w, 64w+64) of both slabs, 8 rows per instruction.
+    // Lane i of instruction g writes LDS row 8g + i/8, chunk position i%8, which must hold logical
+    // chunk (i%8) ^ ((row/2) & 7) = (i%8) ^ (4*(g&1) + i/16).
     const int lrow = lane >> 3;
-    const int lchunk = (lane & 7) ^ lrow;
+    const int c_even = ((lane & 7) ^ (lane >> 4)) * 16, c_odd = c_even ^ 64;
     const int64_t pitch = K >> 1, gpitch = (int64_t)kpad * 2;
-    const uint8_t *ga = a_codes + (m0 + w * 64 + lrow) * pitch + lchunk * 16;
-    const uint8_t *gb = b_codes + (n0 + w * 64 + lrow) * pitch + lchunk * 16;
-    const uint8_t *gga = reinterpret_cast<const uint8_t *>(Ag) + (m0 + w * 64 + lrow) * gpitch + lchunk * 16;
-    const uint8_t *ggb = reinterpret_cast<const uint8_t *>(Bg) + (n0 + w * 64 + lrow) * gpitch + lchunk * 16;
-    const int nbf = OEK ? (kpad >> 6) : 0, ntile = nbf + (int)(K >> 8);
+    const uint8_t *ga = a_codes + (m0 + w * 64 + lrow) * pitch;
+    const uint8_t *gb = b_codes + (n0 + w * 64 + lrow) * pitch;
+    const uint8_t *gga = reinterpret_cast<const uint8_t *>(Ag) + (m0 + w * 64 + lrow) * gpitch;
+    const uint8_t *ggb = reinterpret_cast<const uint8_t *>(Bg) + (n0 + w * 64 + lrow) * gpitch;
+    // scales (stage-major): waves 0,1 move the two 1 KiB halves of the A slab's scales, waves 2,3 of B's
+    const uint8_t *gs = (w < 2 ? a_scales_sm + (m0 + w * 128) * 8 : b_scales_sm + (n0 + (w - 2) * 128) * 8) + lane * 16;
+    const int64_t s_stride = (w < 2 ? M : N) * 8;
+    const int nbf = OEK ? (kpad >> 6) : 0, nstage = nbf + (int)(K >> 8);
+    const uint32_t smem_base = __builtin_amdgcn_readfirstlane(lds_address(smem));
 
-    auto issue = [&](int tile, int stage) {
-        uint8_t *sA = smem + stage * STAGE_BYTES + w * 64 * TKB;
-        uint8_t *sB = sA + TM * TKB;
+    auto issue = [&](int stage) {
+#ifdef ADAHOP_DBG_NO_DMA
+        return;
+#endif
+        const uint32_t sbase = smem_base + (stage & 1) * STAGE_BYTES;
+        const uint32_t sA = sbase + w * 64 * TKB, sB = sA + TM * TKB;
         const uint8_t *pa, *pb;
         int64_t rp;
-        if (OEK && tile < nbf) {
-            pa = gga + (int64_t)tile * TKB;
-            pb = ggb + (int64_t)tile * TKB;
+        const bool bf = OEK && stage < nbf;
+        if (bf) {
+            pa = gga + (int64_t)stage * TKB;
+            pb = ggb + (int64_t)stage * TKB;
             rp = gpitch * 8;
         } else {
-            pa = ga + (int64_t)(tile - nbf) * TKB;
-            pb = gb + (int64_t)(tile - nbf) * TKB;
+            pa = ga + (int64_t)(stage - nbf) * TKB;
+            pb = gb + (int64_t)(stage - nbf) * TKB;
             rp = pitch * 8;
         }
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(pa + g * rp), (lptr_t)(sA + g * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(pb + g * rp), (lptr_t)(sB + g * 1024), 16, 0, 0);
+            const int co = (g & 1) ? c_odd : c_even;
+            dma16(pa + g * rp + co, sA + g * 1024);
+            dma16(pb + g * rp + co, sB + g * 1024);
         }
+        if (!bf) dma16(gs + (int64_t)(stage - nbf) * s_stride, sbase + SLAB_BYTES + w * 1024);
     };
 
-    // ---- fragment reads
-    const int rx = l32 & 7;
+    // ---- fragment reads: row l32 (+32 i) of the wave's slab, logical chunk 4h + s
+    const int rx = (l32 >> 1) & 7;
     const int off0 = ((4 * h + 0) ^ rx) * 16, off1 = ((4 * h + 1) ^ rx) * 16;
     const int off2 = ((4 * h + 2) ^ rx) * 16, off3 = ((4 * h + 3) ^ rx) * 16;
     const int a_row = (wm * 128 + l32) * TKB;
     const int b_row = TM * TKB + (wn * 128 + l32) * TKB;
-    const int64_t KB = K >> 5;
-    const uint8_t *psa = a_scales + (m0 + wm * 128 + l32) * KB + 4 * h;
-    const uint8_t *psb = b_scales + (n0 + wn * 128 + l32) * KB + 4 * h;
+    const int sa_row = SLAB_BYTES + (wm * 128 + l32) * 8 + 4 * h;
+    const int sb_row = SLAB_BYTES + TM * 8 + (wn * 128 + l32) * 8 + 4 * h;
 
     v16f acc[4][4];
 #pragma unroll
@@ -251,52 +326,77 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // scales of the stage after the current one are fetched while the current one is multiplied
-    int sa[4] = {0, 0, 0, 0}, sb[4] = {0, 0, 0, 0}, sa_next[4] = {0, 0, 0, 0}, sb_next[4] = {0, 0, 0, 0};
-    auto load_scales = [&](int fp_tile) {
+    frags_t f0, f1;
+    scales_t sc, sc_next;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sa_next[i] = *reinterpret_cast<const int *>(psa + (int64_t)i * 32 * KB + (int64_t)fp_tile * 8);
-            sb_next[i] = *reinterpret_cast<const int *>(psb + (int64_t)i * 32 * KB + (int64_t)fp_tile * 8);
+    for (int i = 0; i < 4; ++i) sc.a[i] = sc.b[i] = sc_next.a[i] = sc_next.b[i] = 0;
+
+    // prologue: both buffers filled, stage 0 landed, its first fragments read
+    issue(0);
+    if (nstage > 1) {
+        issue(1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(16) : "memory"); // stage 1 (>= 16 copies) may still fly
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();
+    read_frags(smem + a_row, smem + b_row, off0, f0);
+    if (!(OEK && nbf > 0)) read_scales(smem + sa_row, smem + sb_row, sc);
+
+    // Everything of a stage except its last matrix-core step, then the hand-over to the next stage.
+    auto hand_over = [&](int stage) {
+        if (stage + 1 < nstage) {
+            asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)" ::: "memory"); // next stage landed; my reads done
+            __syncthreads();
+            if (stage + 2 < nstage) issue(stage + 2); // refills the buffer just released
+            const uint8_t *sn = smem + ((stage + 1) & 1) * STAGE_BYTES;
+            read_frags(sn + a_row, sn + b_row, off0, f0);
+            if (!(OEK && stage + 1 < nbf)) read_scales(sn + sa_row, sn + sb_row, sc_next);
         }
     };
 
-    issue(0, 0);
-    if (nbf == 0) load_scales(0);
-    int tile = 0;
+    int stage = 0;
     if constexpr (OEK) {
-        // gathered K-channels first: BF16 matrix-core steps on the same accumulators
-        for (; tile < nbf; ++tile) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            issue(tile + 1, (tile + 1) & 1); // the FP4 part has at least one stage, so tile + 1 < ntile
-            if (tile + 1 >= nbf) load_scales(tile + 1 - nbf);
-            const uint8_t *sA = smem + (tile & 1) * STAGE_BYTES + a_row;
-            const uint8_t *sB = smem + (tile & 1) * STAGE_BYTES + b_row;
-            stage_step_bf16(sA, sB, off0, acc);
-            stage_step_bf16(sA, sB, off1, acc);
-            stage_step_bf16(sA, sB, off2, acc);
-            stage_step_bf16(sA, sB, off3, acc);
+        for (; stage < nbf; ++stage) {
+            const uint8_t *st = smem + (stage & 1) * STAGE_BYTES;
+            read_frags(st + a_row, st + b_row, off1, f1);
+            ADAHOP_PIN();
+            mma_bf16(f0, acc);
+            ADAHOP_PIN();
+            read_frags(st + a_row, st + b_row, off2, f0);
+            ADAHOP_PIN();
+            mma_bf16(f1, acc);
+            ADAHOP_PIN();
+            read_frags(st + a_row, st + b_row, off3, f1);
+            ADAHOP_PIN();
+            mma_bf16(f0, acc);
+            ADAHOP_PIN();
+            hand_over(stage);
+            ADAHOP_PIN();
+            mma_bf16(f1, acc);
+            ADAHOP_PIN();
+            sc = sc_next;
         }
     }
-    for (; tile < ntile; ++tile) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sa[i] = sa_next[i];
-            sb[i] = sb_next[i];
-        }
-        if (tile + 1 < ntile) {
-            issue(tile + 1, (tile + 1) & 1);
-            load_scales(tile + 1 - nbf);
-        }
-        const uint8_t *sA = smem + (tile & 1) * STAGE_BYTES + a_row;
-        const uint8_t *sB = smem + (tile & 1) * STAGE_BYTES + b_row;
-        stage_step_fp4<0>(sA, sB, off0, acc, sa, sb);
-        stage_step_fp4<1>(sA, sB, off1, acc, sa, sb);
-        stage_step_fp4<2>(sA, sB, off2, acc, sa, sb);
-        stage_step_fp4<3>(sA, sB, off3, acc, sa, sb);
+    for (; stage < nstage; ++stage) {
+        const uint8_t *st = smem + (stage & 1) * STAGE_BYTES;
+        read_frags(st + a_row, st + b_row, off1, f1);
+        ADAHOP_PIN();
+        mma_fp4<0>(f0, acc, sc);
+        ADAHOP_PIN();
+        read_frags(st + a_row, st + b_row, off2, f0);
+        ADAHOP_PIN();
+        mma_fp4<1>(f1, acc, sc);
+        ADAHOP_PIN();
+        read_frags(st + a_row, st + b_row, off3, f1);
+        ADAHOP_PIN();
+        mma_fp4<2>(f0, acc, sc);
+        ADAHOP_PIN();
+        hand_over(stage);
+        ADAHOP_PIN();
+        mma_fp4<3>(f1, acc, sc);
+        ADAHOP_PIN();
+        sc = sc_next;
     }
 
     float *crow = C + (m0 + wm * 128 + h * 4) * ldc + n0 + wn * 128 + l32;
@@ -311,33 +411,48 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
 
 } // namespace
 
+size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    return align_up((size_t)M * (K / 32), 256) + align_up((size_t)N * (K / 32), 256);
+}
+
 int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
                    const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, const uint16_t *Ag,
-                   const uint16_t *Bg, int kpad, hipStream_t st)
+                   const uint16_t *Bg, int kpad, void *workspace, hipStream_t st)
 {
     if (M == 0 || N == 0) return ADAHOP_OK;
-    const bool tiled = M % TM == 0 && N % TN == 0 && K % 256 == 0 && kpad % 64 == 0 && aligned(a_scales, 4) &&
-                       aligned(b_scales, 4) && (M / TM) * (N / TN) < (1 << 30);
+    const bool tiled = M % TM == 0 && N % TN == 0 && K % 256 == 0 && kpad % 64 == 0 && aligned(a_scales, 8) &&
+                       aligned(b_scales, 8) && (M / TM) * (N / TN) < (1 << 30);
     if (tiled) {
         static bool configured = false;
         if (!configured) {
             int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE_BYTES));
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
             if (rc != ADAHOP_OK) return rc;
             rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE_BYTES));
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
             if (rc != ADAHOP_OK) return rc;
             configured = true;
         }
+        // scales, stage-major, in the caller's workspace
+        uint8_t *a_sm = static_cast<uint8_t *>(workspace);
+        uint8_t *b_sm = a_sm + align_up((size_t)M * (K / 32), 256);
+        const int64_t KB8 = K / 256;
+        hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(M * KB8, 256)), dim3(256), 0, st,
+                           reinterpret_cast<const uint64_t *>(a_scales), reinterpret_cast<uint64_t *>(a_sm), M, KB8);
+        hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(N * KB8, 256)), dim3(256), 0, st,
+                           reinterpret_cast<const uint64_t *>(b_scales), reinterpret_cast<uint64_t *>(b_sm), N, KB8);
+        int rc = check_launch();
+        if (rc != ADAHOP_OK) return rc;
         const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
         const int group_m = tiles_m < 8 ? tiles_m : 8;
         const dim3 grid((unsigned)(tiles_m * tiles_n));
         if (kpad > 0)
-            hipLaunchKernelGGL((k_gemm_mx_tile256<true>), grid, dim3(256), 2 * STAGE_BYTES, st, K, a_codes, a_scales,
-                               b_codes, b_scales, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
+            hipLaunchKernelGGL((k_gemm_mx_tile256<true>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
+                               b_sm, M, N, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
         else
-            hipLaunchKernelGGL((k_gemm_mx_tile256<false>), grid, dim3(256), 2 * STAGE_BYTES, st, K, a_codes, a_scales,
-                               b_codes, b_scales, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
+            hipLaunchKernelGGL((k_gemm_mx_tile256<false>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm,
+                               b_codes, b_sm, M, N, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
         return check_launch();
     }
     dim3 grid((unsigned)ceil_div(N, 128), (unsigned)ceil_div(M, 128));

@@ -67,11 +67,17 @@ def test_foid_rejects_bad_arguments():
 
 def test_gemm_mx_rejects_bad_arguments():
     L = ah.lib()
-    ok = [64, 64, 128, FAKE, FAKE, FAKE, FAKE, FAKE, 64, None]
+    need = L.adahop_gemm_mx_workspace_bytes(64, 64, 128)
+    assert need >= 2 * 64 * 4 and need % 256 == 0
+    ok = [64, 64, 128, FAKE, FAKE, FAKE, FAKE, FAKE, 64, FAKE, need, None]
     for pos, val in ((0, 0), (2, 48), (2, 0), (3, None), (7, None), (8, 63), (3, FAKE + 8)):
         a = list(ok)
         a[pos] = val
         assert L.adahop_gemm_mx(*a) == ah.ADAHOP_E_INVALID_ARG, (pos, val)
+    for pos, val in ((9, None), (9, FAKE + 64), (10, need - 1)):
+        a = list(ok)
+        a[pos] = val
+        assert L.adahop_gemm_mx(*a) == ah.ADAHOP_E_WORKSPACE, (pos, val)
 
 
 def test_gemm_argument_and_workspace_checks():
@@ -80,7 +86,8 @@ def test_gemm_argument_and_workspace_checks():
     need = L.adahop_gemm_workspace_bytes(64, 32, 256, ah.ADAHOP_IHT_OE_K, 8)
     lay = ah.adahop_gemm_workspace_layout(64, 32, 256, ah.ADAHOP_IHT_OE_K, 8)
     assert need == lay.total and need % 256 == 0
-    offs = [lay.a_codes, lay.a_scales, lay.b_codes, lay.b_scales, lay.mask, lay.scores, lay.gather_a, lay.gather_b]
+    offs = [lay.a_codes, lay.a_scales, lay.b_codes, lay.b_scales, lay.mask, lay.scores, lay.gather_a, lay.gather_b,
+            lay.gemm]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert lay.a_scales - lay.a_codes >= 64 * 128 and lay.gather_b - lay.gather_a >= 64 * 64 * 2
     call = lambda **kw: L.adahop_gemm(C.byref(kw.get("A", A)), C.byref(kw.get("B", B)), kw.get("C", FAKE),
