@@ -66,8 +66,13 @@ void orc_fwht(float *v, int b)
         }
     }
     float c = (float)(1.0 / sqrt((double)b));
-    for (int j = 0; j < b; ++j)
+    for (int j = 0; j < b; ++j) {
         v[j] = v[j] * c;
+        /* A transformed value that is exactly zero carries no sign: it is stored as +0.  (The paper
+         * does not say; without this the sign of such a zero would depend on the order in which
+         * cancelling terms were added, which is not part of the definition of H v.) */
+        if (v[j] == 0.0f) v[j] = 0.0f;
+    }
 }
 
 /* ------------------------------------------------------------------ FOID (App. F item 1) */

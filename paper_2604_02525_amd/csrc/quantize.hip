@@ -8,7 +8,8 @@
 // Numerics are fixed so that the packed bytes are reproducible: fp32 butterflies in ascending
 // stride order (x+y to the lower index, x-y to the upper), one fp32 multiply by (float)(1/sqrt(B)),
 // amax on those fp32 values, scale = biased exponent of amax minus 2, round-to-nearest-even to E2M1
-// with saturation at 6.  The file is compiled with -ffp-contract=off.
+// with saturation at 6; a transformed value that is exactly zero is stored as +0.  The file is
+// compiled with -ffp-contract=off.
 //
 // Two kernels, one per storage order of the operand:
 //   k_quant_kc  K contiguous: a lane owns 8 consecutive K-elements (one 16-byte load); strides
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(256) void k_quant_kc(const uint16_t *__restrict__ x
         lane_stage<16, B>(v, lane);
         const float c = hadamard_norm<B>();
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = v[i] * c;
+        for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f); // exact zeros become +0
     }
 
     float amax = 0.0f;
@@ -235,8 +236,8 @@ __global__ __launch_bounds__(ks_cfg<B>::NW * 64) void k_quant_ks(const uint16_t 
         const float cn = hadamard_norm<(B >= 32 ? B : 32)>();
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
-            v[i].x = v[i].x * cn;
-            v[i].y = v[i].y * cn;
+            v[i].x = __builtin_fmaf(v[i].x, cn, 0.0f); // exact zeros become +0
+            v[i].y = __builtin_fmaf(v[i].y, cn, 0.0f);
         }
     }
 
@@ -263,11 +264,300 @@ __global__ __launch_bounds__(ks_cfg<B>::NW * 64) void k_quant_ks(const uint16_t 
     }
 }
 
+// ================================================================================================
+// Fast kernels for K % 256 == 0.  Both quantisers are bound by vector-ALU work long before HBM unless
+// the per-element instruction count is kept near 12, so these kernels
+//   - let the hardware convert: v_cvt_scalef32_pk_fp4_f32 rounds two fp32 values / 2^(s-127) to E2M1
+//     (nearest even, saturating, first value in the low nibble) in one instruction;
+//   - do every cross-lane butterfly as ONE fused multiply-add whose first operand comes through DPP:
+//     w <- partner * t + w with t = +1 on the lower lane of the pair and -1 on the upper one.  That
+//     yields L+U on the lower lane and -(L-U) on the upper lane; the stray sign is not fixed up but
+//     tracked (it only depends on the lane) and folded into the final 1/sqrt(B) multiply.  Negation
+//     commutes with rounding, so the stored bits are exactly those of the plain butterflies.
+//
+// Work split: 16 lanes (one DPP row) own 256 consecutive K-elements of one row; a lane holds two
+// groups of 8 consecutive elements, 128 apart (chunk c of each half).  Strides 1, 2, 4 are register
+// butterflies inside a group, strides 8..64 pair lanes, stride 128 pairs the lane's two groups.  A
+// gfx9 DPP row offers the lane exchanges xor 1, xor 2 (quad_perm), xor 7 (row_half_mirror) and xor 8
+// (row_ror:8) but not xor 4, so chunk c sits on lane (c0 ^ c2, c1 ^ c2, c2, c3): flipping chunk bit 2
+// then is the xor-7 exchange.
+// ================================================================================================
+template <int CTRL> __device__ __forceinline__ float dpp_get(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+struct lane_plan_t {
+    int chunk;     // which 8-element chunk (0..15) of each 128-element half this lane owns
+    float t[4];    // multiplier of the partner value in cross-lane stage b
+    float fin;     // sign left over from the stages times 1/sqrt(B)
+};
+
+template <int B> __device__ __forceinline__ lane_plan_t make_plan(int lane)
+{
+    constexpr int NS = B >= 128 ? 4 : (B == 64 ? 3 : (B == 32 ? 2 : 0));
+    const int r = lane & 15, r2 = (r >> 2) & 1;
+    lane_plan_t p;
+    p.chunk = ((r ^ r2) & 1) | ((r ^ (r2 << 1)) & 2) | (r & 12);
+    float sign = 1.0f;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const bool upper = b < NS && ((p.chunk >> b) & 1);
+        p.t[b] = upper ? -1.0f : 1.0f;
+        if (upper) sign = -sign;
+    }
+    if constexpr (B > 0)
+        p.fin = sign * hadamard_norm<B>();
+    else
+        p.fin = 1.0f;
+    return p;
+}
+
+// One cross-lane butterfly stage on all 16 values of the lane: w <- partner(w) * t + w, the partner
+// being the lane of the DPP row whose chunk index differs in bit STAGE.  Written as assembly because
+// the compiler does not fold the DPP move into the multiply-add (it emits a move, wait states and a
+// separate v_fmac per value, doubling the cost of the stage).  The leading s_nop covers the two wait
+// states a DPP read needs after a vector write of the same register; inside the block each
+// instruction reads a register last written 16 instructions earlier.
+#define ADAHOP_FMAC_DPP16(CTRL)                                                                        \
+    asm volatile("s_nop 1\n\t"                                                                        \
+                 "v_fmac_f32_dpp %0, %0, %16 " CTRL "\n\tv_fmac_f32_dpp %1, %1, %16 " CTRL "\n\t"     \
+                 "v_fmac_f32_dpp %2, %2, %16 " CTRL "\n\tv_fmac_f32_dpp %3, %3, %16 " CTRL "\n\t"     \
+                 "v_fmac_f32_dpp %4, %4, %16 " CTRL "\n\tv_fmac_f32_dpp %5, %5, %16 " CTRL "\n\t"     \
+                 "v_fmac_f32_dpp %6, %6, %16 " CTRL "\n\tv_fmac_f32_dpp %7, %7, %16 " CTRL "\n\t"     \
+                 "v_fmac_f32_dpp %8, %8, %16 " CTRL "\n\tv_fmac_f32_dpp %9, %9, %16 " CTRL "\n\t"     \
+                 "v_fmac_f32_dpp %10, %10, %16 " CTRL "\n\tv_fmac_f32_dpp %11, %11, %16 " CTRL "\n\t" \
+                 "v_fmac_f32_dpp %12, %12, %16 " CTRL "\n\tv_fmac_f32_dpp %13, %13, %16 " CTRL "\n\t" \
+                 "v_fmac_f32_dpp %14, %14, %16 " CTRL "\n\tv_fmac_f32_dpp %15, %15, %16 " CTRL "\n\t" \
+                 "s_nop 1"                                                                            \
+                 : "+v"(w0[0]), "+v"(w0[1]), "+v"(w0[2]), "+v"(w0[3]), "+v"(w0[4]), "+v"(w0[5]), "+v"(w0[6]),   \
+                   "+v"(w0[7]), "+v"(w1[0]), "+v"(w1[1]), "+v"(w1[2]), "+v"(w1[3]), "+v"(w1[4]), "+v"(w1[5]),   \
+                   "+v"(w1[6]), "+v"(w1[7])                                                            \
+                 : "v"(t))
+
+template <int STAGE> __device__ __forceinline__ void cross_stage(float (&w0)[8], float (&w1)[8], float t)
+{
+    if constexpr (STAGE == 0)
+        ADAHOP_FMAC_DPP16("quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf");
+    else if constexpr (STAGE == 1)
+        ADAHOP_FMAC_DPP16("quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf");
+    else if constexpr (STAGE == 2)
+        ADAHOP_FMAC_DPP16("row_half_mirror row_mask:0xf bank_mask:0xf");
+    else
+        ADAHOP_FMAC_DPP16("row_ror:8 row_mask:0xf bank_mask:0xf");
+}
+
+// Transform (B > 0) and quantise the lane's two groups; returns the packed codes of each group and
+// the scale code of the MX block each group belongs to (identical on the 4 lanes of the block).
+template <int B>
+__device__ __forceinline__ void transform_quantize16(float (&w0)[8], float (&w1)[8], const lane_plan_t &p,
+                                                     uint32_t &codes0, uint32_t &codes1, int &s0, int &s1)
+{
+    if constexpr (B > 0) {
+#pragma unroll
+        for (int h = 1; h < 8; h *= 2)
+#pragma unroll
+            for (int i = 0; i < 8; i += 2 * h)
+#pragma unroll
+                for (int j = i; j < i + h; ++j) {
+                    float a = w0[j], b = w0[j + h];
+                    w0[j] = a + b;
+                    w0[j + h] = a - b;
+                    a = w1[j], b = w1[j + h];
+                    w1[j] = a + b;
+                    w1[j + h] = a - b;
+                }
+        cross_stage<0>(w0, w1, p.t[0]);                        // stride 8: chunk bit 0
+        cross_stage<1>(w0, w1, p.t[1]);                        // stride 16: chunk bit 1
+        if constexpr (B >= 64) cross_stage<2>(w0, w1, p.t[2]); // stride 32: chunk bit 2
+        if constexpr (B >= 128) cross_stage<3>(w0, w1, p.t[3]); // stride 64: chunk bit 3
+        if constexpr (B == 256) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { // stride 128: the lane's two groups (same leftover sign)
+                const float a = w0[i], b = w1[i];
+                w0[i] = a + b;
+                w1[i] = a - b;
+            }
+        }
+        // the "+ 0" turns an exactly zero result into +0 whatever sign the lane carries (and changes
+        // nothing else): transformed zeros are stored unsigned
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            w0[i] = __builtin_fmaf(w0[i], p.fin, 0.0f);
+            w1[i] = __builtin_fmaf(w1[i], p.fin, 0.0f);
+        }
+    }
+    float m0 = 0.0f, m1 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        m0 = fmaxf(m0, fabsf(w0[i]));
+        m1 = fmaxf(m1, fabsf(w1[i]));
+    }
+    m0 = fmaxf(m0, dpp_get<0xB1>(m0)); // the MX block = chunks 4q..4q+3 = the lane's quad
+    m1 = fmaxf(m1, dpp_get<0xB1>(m1));
+    m0 = fmaxf(m0, dpp_get<0x4E>(m0));
+    m1 = fmaxf(m1, dpp_get<0x4E>(m1));
+    s0 = e8m0_of_amax(m0);
+    s1 = e8m0_of_amax(m1);
+    const float x0 = __uint_as_float((uint32_t)s0 << 23), x1 = __uint_as_float((uint32_t)s1 << 23);
+    codes0 = 0;
+    codes1 = 0;
+    codes0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes0, w0[0], w0[1], x0, 0);
+    codes0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes0, w0[2], w0[3], x0, 1);
+    codes0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes0, w0[4], w0[5], x0, 2);
+    codes0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes0, w0[6], w0[7], x0, 3);
+    codes1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes1, w1[0], w1[1], x1, 0);
+    codes1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes1, w1[2], w1[3], x1, 1);
+    codes1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes1, w1[4], w1[5], x1, 2);
+    codes1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes1, w1[6], w1[7], x1, 3);
+}
+
+__device__ __forceinline__ void apply_k_mask(float (&w)[8], const uint8_t *zero_k, int64_t kk)
+{
+    const uint64_t zm = *reinterpret_cast<const uint64_t *>(zero_k + kk);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if ((zm >> (8 * i)) & 0xffu) w[i] = 0.0f;
+}
+
+__device__ __forceinline__ void store_codes_scales(uint8_t *codes, uint8_t *scales, int64_t row, int64_t K, int64_t k0,
+                                                   int chunk, uint32_t c0, uint32_t c1, int s0, int s1)
+{
+    uint8_t *crow = codes + row * (K >> 1) + ((k0 + chunk * 8) >> 1);
+    *reinterpret_cast<uint32_t *>(crow) = c0;
+    *reinterpret_cast<uint32_t *>(crow + 64) = c1;
+    if ((chunk & 3) == 0) {
+        uint8_t *srow = scales + row * (K >> 5) + ((k0 + chunk * 8) >> 5);
+        srow[0] = (uint8_t)s0;
+        srow[4] = (uint8_t)s1;
+    }
+}
+
+// K-contiguous operand: 16 lanes per 256 K-elements of a row.  FLAT as in k_quant_kc.
+template <int B, int FLAT>
+__global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__ x, int64_t outer, int64_t K,
+                                                    int64_t ld, const uint8_t *__restrict__ zero_outer,
+                                                    const uint8_t *__restrict__ zero_k,
+                                                    uint8_t *__restrict__ codes, uint8_t *__restrict__ scales)
+{
+    const uint32_t upr = (uint32_t)(K >> 8); // 256-element units per row
+    int64_t row;
+    uint32_t unit;
+    bool active;
+    if constexpr (FLAT) {
+        const uint32_t u = (blockIdx.x * 256u + threadIdx.x) >> 4;
+        const uint32_t r = u / upr;
+        row = r;
+        unit = u - r * upr;
+        active = row < outer;
+    } else {
+        row = blockIdx.x;
+        unit = (blockIdx.y * 256u + threadIdx.x) >> 4;
+        active = unit < upr;
+    }
+    const lane_plan_t plan = make_plan<B>(threadIdx.x & 63);
+    const int64_t k0 = (int64_t)unit * 256, kk = k0 + plan.chunk * 8;
+
+    uint4 r0 = make_uint4(0, 0, 0, 0), r1 = make_uint4(0, 0, 0, 0);
+    if (active && !(zero_outer && zero_outer[row])) {
+        const uint16_t *src = x + row * ld + kk;
+        r0 = *reinterpret_cast<const uint4 *>(src);
+        r1 = *reinterpret_cast<const uint4 *>(src + 128);
+    }
+    float w0[8] = {bf16_lo(r0.x), bf16_hi(r0.x), bf16_lo(r0.y), bf16_hi(r0.y),
+                   bf16_lo(r0.z), bf16_hi(r0.z), bf16_lo(r0.w), bf16_hi(r0.w)};
+    float w1[8] = {bf16_lo(r1.x), bf16_hi(r1.x), bf16_lo(r1.y), bf16_hi(r1.y),
+                   bf16_lo(r1.z), bf16_hi(r1.z), bf16_lo(r1.w), bf16_hi(r1.w)};
+    if (zero_k && active) {
+        apply_k_mask(w0, zero_k, kk);
+        apply_k_mask(w1, zero_k, kk + 128);
+    }
+    uint32_t c0, c1;
+    int s0, s1;
+    transform_quantize16<B>(w0, w1, plan, c0, c1, s0, s1);
+    if (active) store_codes_scales(codes, scales, row, K, k0, plan.chunk, c0, c1, s0, s1);
+}
+
+// K-strided operand (element (o, kk) at x[kk*ld + o]).  A workgroup takes a tile of 256 K-rows x 64
+// columns: coalesced 16-byte loads (8 columns of one K-row per lane) go to LDS as they are, then each
+// wave takes 4 columns at a time and every lane pulls its two 8-element groups out of LDS with
+// 2-byte reads -- the transposition -- and carries on exactly like the K-contiguous kernel.  The LDS
+// row pitch of 66 elements keeps those reads down to 2-way bank conflicts.
+constexpr int KS_COLS = 64, KS_PITCH = 66;
+
+template <int B>
+__global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__ x, int64_t outer, int64_t K,
+                                                    int64_t ld, const uint8_t *__restrict__ zero_outer,
+                                                    const uint8_t *__restrict__ zero_k,
+                                                    uint8_t *__restrict__ codes, uint8_t *__restrict__ scales)
+{
+    __shared__ uint16_t tile[256 * KS_PITCH];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t o0 = (int64_t)blockIdx.x * KS_COLS, k0 = (int64_t)blockIdx.y * 256;
+
+    {
+        const int cg = tid & 7, r0 = tid >> 3; // 8 column groups x 32 rows per pass
+        const bool ok = o0 + cg * 8 < outer;
+        uint4 v[8];
+#pragma unroll
+        for (int it = 0; it < 8; ++it)
+            v[it] = ok ? *reinterpret_cast<const uint4 *>(x + (k0 + it * 32 + r0) * ld + o0 + cg * 8) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            uint32_t *dst = reinterpret_cast<uint32_t *>(tile + (it * 32 + r0) * KS_PITCH + cg * 8);
+            dst[0] = v[it].x;
+            dst[1] = v[it].y;
+            dst[2] = v[it].z;
+            dst[3] = v[it].w;
+        }
+    }
+    __syncthreads();
+
+    const lane_plan_t plan = make_plan<B>(lane);
+    const int kc = plan.chunk * 8;
+#pragma unroll 1
+    for (int it = 0; it < 4; ++it) {
+        const int col = w * 16 + it * 4 + (lane >> 4);
+        const int64_t o = o0 + col;
+        const bool active = o < outer;
+        const bool zrow = active && zero_outer && zero_outer[o];
+        float w0[8], w1[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            w0[i] = bf16_one(tile[(kc + i) * KS_PITCH + col]);
+            w1[i] = bf16_one(tile[(kc + 128 + i) * KS_PITCH + col]);
+            if (zrow) {
+                w0[i] = 0.0f;
+                w1[i] = 0.0f;
+            }
+        }
+        if (zero_k) {
+            apply_k_mask(w0, zero_k, k0 + kc);
+            apply_k_mask(w1, zero_k, k0 + kc + 128);
+        }
+        uint32_t c0, c1;
+        int s0, s1;
+        transform_quantize16<B>(w0, w1, plan, c0, c1, s0, s1);
+        if (active) store_codes_scales(codes, scales, o, K, k0, plan.chunk, c0, c1, s0, s1);
+    }
+}
+
 template <int B>
 int launch_kc(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
               hipStream_t st)
 {
     const uint16_t *d = static_cast<const uint16_t *>(x.data);
+    if (x.K % 256 == 0) {
+        const int64_t tpr = x.K / 16; // threads per row
+        if (tpr >= 128) {
+            dim3 grid((unsigned)x.outer, (unsigned)ceil_div(tpr, 256));
+            hipLaunchKernelGGL((k_quant_kc16<B, 0>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes, scales);
+        } else {
+            dim3 grid((unsigned)ceil_div(x.outer * tpr, 256));
+            hipLaunchKernelGGL((k_quant_kc16<B, 1>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes, scales);
+        }
+        return check_launch();
+    }
     const int64_t cpr = x.K / 8;
     if (cpr >= 128) {
         dim3 grid((unsigned)x.outer, (unsigned)ceil_div(cpr, 256));
@@ -283,6 +573,12 @@ template <int B>
 int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
               hipStream_t st)
 {
+    if (x.K % 256 == 0 && x.K / 256 <= 65535) {
+        dim3 grid((unsigned)ceil_div(x.outer, KS_COLS), (unsigned)(x.K / 256));
+        hipLaunchKernelGGL((k_quant_ks16<B>), grid, dim3(256), 0, st, static_cast<const uint16_t *>(x.data), x.outer,
+                           x.K, x.ld, zo, zk, codes, scales);
+        return check_launch();
+    }
     constexpr int NW = ks_cfg<B>::NW;
     constexpr int NCH = ks_cfg<B>::NCH;
     const size_t lds = NCH > 1 ? (size_t)NW * 32 * 64 * sizeof(float2) : 0;

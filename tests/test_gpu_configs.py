@@ -1,0 +1,87 @@
+"""Parity at the full BASELINE sizes, in the launch configuration bench.py times.
+
+For every GEMM of configs[1..4]: FOID indices, masks, packed codes and scales of both operands are
+compared bit for bit over the whole operand; C is compared with the oracle on a seeded sample of
+rows x columns (always containing some extracted rows / columns when the strategy extracts any),
+within 1e-3 relative Frobenius error.
+"""
+import numpy as np
+import pytest
+
+from oracle import reference as orc
+from paper_2604_02525_amd import inputs
+from test_gpu_parity import ah, run_whole, say, host, dev_op  # noqa: F401  (ah is a fixture)
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def sample(g, nrows=40, ncols=160, seed=0):
+    """Seeded rows x cols sample of C; when rows / columns are extracted, a few of them are included."""
+    M, N, K = g.shape
+    rng = np.random.default_rng(seed + M + N)
+    rows = rng.permutation(M)[:nrows]
+    cols = rng.permutation(N)[:ncols]
+    if g.k > 0 and g.strategy == inputs.IHT_OE_ROW:
+        sel, _ = orc.foid_topk(g.A.bits, g.A.k_contig, 0, g.k)
+        rows[:6] = sel[np.linspace(0, len(sel) - 1, 6).astype(int)]
+    if g.k > 0 and g.strategy == inputs.IHT_OE_COL:
+        sel, _ = orc.foid_topk(g.B.bits, g.B.k_contig, 0, g.k)
+        cols[:6] = sel[np.linspace(0, len(sel) - 1, 6).astype(int)]
+    return np.unique(rows).astype(np.int32), np.unique(cols).astype(np.int32)
+
+
+def check(ah, g, rows_cols=None):
+    rows, cols = rows_cols if rows_cols is not None else sample(g)
+    say("config GEMM", g.name, inputs.STRATEGY_NAMES[g.strategy], "k =", g.k, g.shape)
+    return run_whole(ah, g, rows=rows, cols=cols)
+
+
+def test_config1_forward_up_projection(ah):
+    g = inputs.config1()[0]
+    _, q_iht = check(ah, g)
+    g_oe = inputs.config1(strategy=inputs.IHT_OE_K, k=8)[0]
+    _, q_oe = check(ah, g_oe)
+    # the 8 amplified channels are exactly what FOID finds, and routing them to BF16 must help
+    assert q_oe < q_iht
+
+
+def test_config2_oe_row(ah):
+    g = inputs.config2()[0]
+    _, q_oe = check(ah, g)
+    g_iht = inputs.config2()[0]
+    g_iht.strategy, g_iht.k = inputs.IHT, 0
+    _, q_iht = check(ah, g_iht)
+    assert q_oe < q_iht                       # RC pair: IHT alone is not enough (paper Sec. 3.2, Eq. 7)
+
+
+@pytest.mark.parametrize("linear", [name for name, _, _ in inputs.CFG3_LINEARS])
+def test_config3_llama7b_layer(ah, linear):
+    for g in inputs.config3(linears=(linear,)):
+        check(ah, g)
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config4_stress_shapes(ah, which):
+    """fwd / wgrad with OE-K, dgrad with OE-row, k = 1 % (what bench.py runs)."""
+    for g in inputs.config4(which=(which,), strategies=(inputs.IHT_OE_K, inputs.IHT_OE_ROW, inputs.IHT_OE_K), k_pct=1.0):
+        check(ah, g)
+    torch.cuda.empty_cache()
+
+
+def test_config4_k_sweep_error_is_non_increasing(ah):
+    """k in {0, 0.25 %, 1 %, 2 %} on the up-projection dgrad (OE-row) and forward (OE-K): parity at every k,
+    and the error against the exact product must not grow with k (paper App. G)."""
+    base = inputs.config4(which=("up",), strategies=(inputs.IHT_OE_K, inputs.IHT_OE_ROW, inputs.IHT), k_pct=1.0)
+    for g in base[:2]:
+        dim = g.A.K if g.strategy == inputs.IHT_OE_K else g.A.outer
+        errs = []
+        g.k = inputs.pct(2.0, dim)
+        fixed = sample(g)                     # one sample for the whole sweep, so the errors are comparable
+        for pct in (0.0, 0.25, 1.0, 2.0):
+            g.k = inputs.pct(pct, dim)
+            errs.append(check(ah, g, fixed)[1])
+        say("  k-sweep error vs exact:", [f"{e:.3e}" for e in errs])
+        assert all(b <= a * 1.02 for a, b in zip(errs, errs[1:]))
+    torch.cuda.empty_cache()

@@ -288,6 +288,23 @@ def test_fused_closed_form_hadamard_rows(b, golden_dir):
     assert nblk * b == x.shape[1]
 
 
+def test_sign_of_zero_rules():
+    """Without a transform the sign bit of a zero is the input's; a transformed value that is exactly
+    zero is stored as +0 (its sign would otherwise depend on the order of cancelling additions)."""
+    x = np.zeros((1, 64), dtype=np.float32)
+    x[0, :32] = -0.0
+    x[0, 32] = 1.0
+    x[0, 33] = -1.0                      # cancels in the first butterfly of the transform
+    bits = bf16_bits(x)
+    assert bits[0, 0] == 0x8000
+    codes, scales = orc.quantize_mx(bits, True)
+    assert np.all(codes[0, :16] == 0x88) and scales[0, 0] == 0
+    codes_t, _ = orc.iht_quantize(bits, True, 32)
+    assert np.all(codes_t[0, :16] == 0)                       # all -0 block -> +0 codes
+    t = orc.transform(bits, True, 32)[0]
+    assert not np.any(np.signbit(t[t == 0]))
+
+
 # ----------------------------------------------------------------------------- emulated GEMM
 
 def test_mx_gemm_matches_numpy_on_independent_dequant(golden_dir):
