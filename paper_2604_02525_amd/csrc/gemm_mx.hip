@@ -162,15 +162,30 @@ __global__ __launch_bounds__(256) void k_stage_major_scales(const uint64_t *__re
     out[g] = in[r * KB8 + s];
 }
 
-// Copies from global memory straight into LDS: lane i's 16 bytes land at lds_addr + 16 i (lds_addr
-// wave-uniform).  Inline assembly on purpose: with the builtin the compiler's wait-count pass makes
-// every later LDS read wait for ALL outstanding copies (it cannot tell that they target the other
-// stage), which serialises the copies with the matrix-core work.  The kernel waits for the copies
-// itself (s_waitcnt vmcnt(0) before the stage barrier).  M0 is written here and used by nothing else
-// in these kernels (no dynamic register indexing, no other DMA).
-__device__ __forceinline__ void dma16(const void *g, uint32_t lds_addr)
+// Copies from global memory straight into LDS: lane i's 16 bytes, read at base + voff, land at
+// lds_addr + 16 i (base and lds_addr wave-uniform, voff a 32-bit per-lane byte offset).  Inline
+// assembly on purpose: with the builtin the compiler's wait-count pass makes every later LDS read
+// wait for ALL outstanding copies (it cannot tell that they target the other stage), which
+// serialises the copies with the matrix-core work.  The kernel waits for the copies itself
+// (s_waitcnt vmcnt(0) before the stage barrier).  M0 is written here and used by nothing else in
+// these kernels (no dynamic register indexing, no other DMA).
+__device__ __forceinline__ const uint8_t *uniform_ptr(const uint8_t *p)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ void dma16(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
+{
+    // Both are wave-uniform by construction; reading them through the first lane makes sure they sit
+    // in scalar registers, which the instruction requires, whatever the register allocator did.
+    base = uniform_ptr(base);
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(base), "s"(lds_addr)
+                 : "memory");
 }
 
 __device__ __forceinline__ uint32_t lds_address(const void *p)
@@ -182,62 +197,194 @@ struct frags_t {
     uint4 a[4], b[4];
 };
 
-// Fragments of one matrix-core step for this lane: rows l32 (+32 i) of the wave's A and B slabs.
-__device__ __forceinline__ void read_frags(const uint8_t *sA, const uint8_t *sB, int off, frags_t &f)
-{
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        f.a[i] = *reinterpret_cast<const uint4 *>(sA + i * 32 * TKB + off);
-        f.b[i] = *reinterpret_cast<const uint4 *>(sB + i * 32 * TKB + off);
-    }
-}
-
 struct scales_t {
     int a[4], b[4];
 };
 
-__device__ __forceinline__ void read_scales(const uint8_t *sSa, const uint8_t *sSb, scales_t &sc)
-{
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        sc.a[i] = *reinterpret_cast<const int *>(sSa + i * 32 * 8);
-        sc.b[i] = *reinterpret_cast<const int *>(sSb + i * 32 * 8);
-    }
-}
+// Keeps the instruction scheduler from moving anything across this point (one wave per SIMD: the
+// order written here is what hides the LDS and copy-issue latency behind the matrix cores).
+#define ADAHOP_PIN() __builtin_amdgcn_sched_barrier(0)
 
-template <int S> __device__ __forceinline__ void mma_fp4(const frags_t &f, v16f (&acc)[4][4], const scales_t &sc)
+// Everything one wave keeps across the stages of a tile.
+struct tile_state_t {
+    v16f acc[4][4];
+    frags_t f0, f1;
+    scales_t sc, scn;
+    // fragment reads: byte offsets inside a stage buffer
+    int a_row, b_row, sa_row, sb_row, off[4];
+    // copy engine (see k_gemm_mx_tile256)
+    const uint8_t *ga, *gb, *gga, *ggb, *gs; // wave-uniform bases of stage 0
+    uint32_t lrow, c_even, c_odd, vs;        // per-lane: row within an 8-row group, byte of its chunk in even / odd
+                                             // groups, offset of the scale copy
+    uint32_t pitch, gpitch;                  // bytes between rows of the codes / of the gathered bf16 operands
+    int64_t s_stride;
+    uint32_t lds_w;                          // LDS address of this wave's 64 rows of the A slab, buffer 0
+    uint32_t lds_s;                          // LDS address of this wave's 1 KiB of scales, buffer 0
+    int nbf;
+#ifdef ADAHOP_DBG_TIMING
+    uint64_t dbg_dma, dbg_bar;
+#endif
+};
+#ifdef ADAHOP_DBG_TIMING
+__device__ unsigned long long g_dbg[8];
+#endif
+
+__device__ __forceinline__ void read_frags(const uint8_t *buf, const tile_state_t &t, int s, frags_t &f)
 {
-#ifdef ADAHOP_DBG_NO_MMA
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j][S] += __int_as_float((f.a[i].x ^ f.b[j].y ^ sc.a[i] ^ sc.b[j]) & 0x3fffffff);
+#ifdef ADAHOP_DBG_NO_LDSREAD
     return;
 #endif
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            v8i av = {(int)f.a[i].x, (int)f.a[i].y, (int)f.a[i].z, (int)f.a[i].w, 0, 0, 0, 0};
-            v8i bv = {(int)f.b[j].x, (int)f.b[j].y, (int)f.b[j].z, (int)f.b[j].w, 0, 0, 0, 0};
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc[i][j], 4, 4, S, sc.a[i], S, sc.b[j]);
-        }
+    for (int i = 0; i < 4; ++i) {
+        f.a[i] = *reinterpret_cast<const uint4 *>(buf + t.a_row + i * 32 * TKB + t.off[s]);
+        f.b[i] = *reinterpret_cast<const uint4 *>(buf + t.b_row + i * 32 * TKB + t.off[s]);
+    }
 }
 
-__device__ __forceinline__ void mma_bf16(const frags_t &f, v16f (&acc)[4][4])
+__device__ __forceinline__ void read_scales(const uint8_t *buf, const tile_state_t &t, scales_t &sc)
 {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16(f.a[i], f.b[j], acc[i][j]);
+    for (int i = 0; i < 4; ++i) {
+        sc.a[i] = *reinterpret_cast<const int *>(buf + t.sa_row + i * 32 * 8);
+        sc.b[i] = *reinterpret_cast<const int *>(buf + t.sb_row + i * 32 * 8);
+    }
 }
 
-// Keeps the instruction scheduler from moving LDS reads and matrix-core instructions across this
-// point (one wave per SIMD: the order written here is what hides the LDS latency).
-#define ADAHOP_PIN() __builtin_amdgcn_sched_barrier(0)
+// One row of matrix-core tiles (4 instructions) of step S of a stage.
+template <bool BF, int S> __device__ __forceinline__ void mma_row(const frags_t &f, tile_state_t &t, int i)
+{
+#ifdef ADAHOP_DBG_NO_MMA
+#pragma unroll
+    for (int j = 0; j < 4; ++j) t.acc[i][j][S] += __int_as_float((f.a[i].x ^ f.b[j].y ^ t.sc.a[i] ^ t.sc.b[j]) & 0x3fffffff);
+    return;
+#endif
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if constexpr (BF) {
+            t.acc[i][j] = mfma_bf16(f.a[i], f.b[j], t.acc[i][j]);
+        } else {
+            v8i av = {(int)f.a[i].x, (int)f.a[i].y, (int)f.a[i].z, (int)f.a[i].w, 0, 0, 0, 0};
+            v8i bv = {(int)f.b[j].x, (int)f.b[j].y, (int)f.b[j].z, (int)f.b[j].w, 0, 0, 0, 0};
+            t.acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, t.acc[i][j], 4, 4, S, t.sc.a[i], S, t.sc.b[j]);
+        }
+    }
+}
 
-// BF16 = true: the stage loop over the gathered bf16 K-channels; false: the FP4 stages.  The two
-// loops run back to back on one pipeline: `stage` counts over both.
+template <bool BF, int S> __device__ __forceinline__ void mma_step(const frags_t &f, tile_state_t &t)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) mma_row<BF, S>(f, t, i);
+}
+
+// Copies d0 .. d1-1 of the 17 copies of one stage: copy 2g + o (g < 8) is row group g of slab o
+// (0 = A, 1 = B), copy 16 the scales.  TBF: the stage is one of the gathered-bf16 stages, whose
+// operands have their own row pitch; such a stage has no scales and copy 16 is skipped.
+template <bool TBF, int D0, int D1> __device__ __forceinline__ void issue_copies(const tile_state_t &t, int stage)
+{
+#ifdef ADAHOP_DBG_NO_DMA
+    return;
+#endif
+    const uint32_t boff = (stage & 1) * STAGE_BYTES;
+    const int cs = stage - t.nbf;                      // index among the FP4 stages
+    const uint32_t rp = TBF ? t.gpitch : t.pitch;      // row pitch of this stage's operands
+    const uint8_t *pa = TBF ? t.gga + (int64_t)stage * TKB : t.ga + (int64_t)cs * TKB;
+    const uint8_t *pb = TBF ? t.ggb + (int64_t)stage * TKB : t.gb + (int64_t)cs * TKB;
+    // row group g starts 8 g rows further: a wave-uniform term that goes into the base address
+    const uint32_t v_even = t.lrow * rp + t.c_even, v_odd = t.lrow * rp + t.c_odd;
+#pragma unroll
+    for (int d = D0; d < D1; ++d) {
+        if (d == 16) {
+            if constexpr (!TBF) dma16(t.gs + (int64_t)cs * t.s_stride, t.vs, t.lds_s + boff);
+        } else {
+            const int g = d >> 1;
+            const uint32_t vo = (g & 1) ? v_odd : v_even;
+            const int64_t goff = (int64_t)(8 * g) * rp;
+            if (d & 1)
+                dma16(pb + goff, vo, t.lds_w + boff + TM * TKB + g * 1024);
+            else
+                dma16(pa + goff, vo, t.lds_w + boff + g * 1024);
+        }
+    }
+}
+
+// The copy path of a compute unit moves about 1 KiB per 16 .. 22 cycles, so the 68 copies of a stage
+// (4 waves x 17) keep it busy for most of a stage; waves that issue copies faster than that block,
+// and their matrix-core instructions with them.  The copies of a stage are therefore spread over
+// SPREAD matrix-core steps (4 slots per step, one after each row of instructions): the last step of
+// the stage that released the buffer and the first SPREAD - 1 steps of the following stage.
+#ifndef ADAHOP_SPREAD
+#define ADAHOP_SPREAD 3
+#endif
+constexpr int SPREAD = ADAHOP_SPREAD, NSLOT = 4 * SPREAD;
+constexpr int slot_lo(int k) { return 17 * k / NSLOT; }
+
+template <bool TBF, int K> __device__ __forceinline__ void issue_slot(const tile_state_t &t, int stage)
+{
+    if constexpr (K < NSLOT) issue_copies<TBF, slot_lo(K), slot_lo(K + 1)>(t, stage);
+}
+
+// One pipeline stage: four matrix-core steps on the fragments of buffer stage % 2.
+//   BF:       this stage holds gathered bf16 K-channels (else FP4 codes and scales).
+//   BF1, BF2: the same for stages stage + 1 and stage + 2 (they decide what the copies fetch).
+//   HAS_NEXT: stage + 1 exists.  Its copies were begun during the previous stage (or the
+//             prologue) and continue during the first steps of this one.  Before the last step,
+//             wait until it has landed and every wave has read its last fragments of this stage
+//             (one barrier), then read its first fragments while the last step runs.
+//   ISSUE:    stage + 2 exists -- its copies go into the buffer just released, starting between the
+//             instructions of the last step.
+// The body has no branches, so the order written here is the order that runs.
+template <bool BF, bool BF1, bool BF2, bool HAS_NEXT, bool ISSUE>
+__device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, int stage)
+{
+    const uint8_t *st = smem + (stage & 1) * STAGE_BYTES;
+    const uint8_t *sn = smem + ((stage + 1) & 1) * STAGE_BYTES;
+    read_frags(st, t, 1, t.f1);
+    ADAHOP_PIN();
+#define ADAHOP_ROW(S, F, I, SLOT, COND, TBF, WHICH)     \
+    mma_row<BF, S>(F, t, I);                             \
+    ADAHOP_PIN();                                        \
+    if constexpr (COND) {                                \
+        issue_slot<TBF, SLOT>(t, WHICH);                 \
+        ADAHOP_PIN();                                    \
+    }
+    ADAHOP_ROW(0, t.f0, 0, 4, HAS_NEXT, BF1, stage + 1)
+    ADAHOP_ROW(0, t.f0, 1, 5, HAS_NEXT, BF1, stage + 1)
+    ADAHOP_ROW(0, t.f0, 2, 6, HAS_NEXT, BF1, stage + 1)
+    ADAHOP_ROW(0, t.f0, 3, 7, HAS_NEXT, BF1, stage + 1)
+    read_frags(st, t, 2, t.f0);
+    ADAHOP_PIN();
+    ADAHOP_ROW(1, t.f1, 0, 8, HAS_NEXT, BF1, stage + 1)
+    ADAHOP_ROW(1, t.f1, 1, 9, HAS_NEXT, BF1, stage + 1)
+    ADAHOP_ROW(1, t.f1, 2, 10, HAS_NEXT, BF1, stage + 1)
+    ADAHOP_ROW(1, t.f1, 3, 11, HAS_NEXT, BF1, stage + 1)
+    read_frags(st, t, 3, t.f1);
+    ADAHOP_PIN();
+    mma_step<BF, 2>(t.f0, t);
+    ADAHOP_PIN();
+    if constexpr (HAS_NEXT) {
+#ifdef ADAHOP_DBG_NO_VMWAIT
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#else
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)" ::: "memory"); // next stage landed; my reads done
+#endif
+#ifndef ADAHOP_DBG_NO_BARRIER
+        __syncthreads();
+#endif
+        read_frags(sn, t, 0, t.f0);
+        if constexpr (!BF1) read_scales(sn, t, t.scn);
+        ADAHOP_PIN();
+    }
+    ADAHOP_ROW(3, t.f1, 0, 0, ISSUE, BF2, stage + 2)
+    ADAHOP_ROW(3, t.f1, 1, 1, ISSUE, BF2, stage + 2)
+    ADAHOP_ROW(3, t.f1, 2, 2, ISSUE, BF2, stage + 2)
+    ADAHOP_ROW(3, t.f1, 3, 3, ISSUE, BF2, stage + 2)
+#undef ADAHOP_ROW
+    if constexpr (HAS_NEXT && !BF1) t.sc = t.scn;
+}
+
+// The stage loop runs over the gathered bf16 K-channels first (OEK), then over the FP4 stages, on
+// one pipeline: `stage` counts over both.  Host side guarantees K >= 512 (two FP4 stages), so that
+// every bf16 stage has two successors and the last two stages are FP4 stages.
 template <bool OEK>
 __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_t *__restrict__ a_codes,
                                                          const uint8_t *__restrict__ a_scales_sm,
@@ -256,160 +403,160 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     // own L2), so give every XCD a contiguous run of the tile sequence, and order that sequence in
     // bands of group_m tile rows so that concurrently running tiles share A and B panels.
     const int ntiles = tiles_m * tiles_n;
-    int t = blockIdx.x;
-    if (ntiles % 8 == 0) t = (t & 7) * (ntiles >> 3) + (t >> 3);
+    int tix = blockIdx.x;
+    if (ntiles % 8 == 0) tix = (tix & 7) * (ntiles >> 3) + (tix >> 3);
     const int band = group_m * tiles_n;
-    const int first_m = (t / band) * group_m;
+    const int first_m = (tix / band) * group_m;
     const int gsz = min(group_m, tiles_m - first_m);
-    const int tm = first_m + (t % band) % gsz;
-    const int tn = (t % band) / gsz;
+    const int tm = first_m + (tix % band) % gsz;
+    const int tn = (tix % band) / gsz;
     const int64_t m0 = (int64_t)tm * TM, n0 = (int64_t)tn * TN;
     const int wm = w >> 1, wn = w & 1;
 
+    tile_state_t t;
+#ifdef ADAHOP_DBG_TIMING
+    t.dbg_dma = t.dbg_bar = 0;
+    const uint64_t dbg_start = __builtin_readcyclecounter();
+#endif
     // ---- copy engine: wave w moves rows [64w, 64w+64) of both slabs, 8 rows per instruction.
     // Lane i of instruction g writes LDS row 8g + i/8, chunk position i%8, which must hold logical
     // chunk (i%8) ^ ((row/2) & 7) = (i%8) ^ (4*(g&1) + i/16).
-    const int lrow = lane >> 3;
-    const int c_even = ((lane & 7) ^ (lane >> 4)) * 16, c_odd = c_even ^ 64;
-    const int64_t pitch = K >> 1, gpitch = (int64_t)kpad * 2;
-    const uint8_t *ga = a_codes + (m0 + w * 64 + lrow) * pitch;
-    const uint8_t *gb = b_codes + (n0 + w * 64 + lrow) * pitch;
-    const uint8_t *gga = reinterpret_cast<const uint8_t *>(Ag) + (m0 + w * 64 + lrow) * gpitch;
-    const uint8_t *ggb = reinterpret_cast<const uint8_t *>(Bg) + (n0 + w * 64 + lrow) * gpitch;
-    // scales (stage-major): waves 0,1 move the two 1 KiB halves of the A slab's scales, waves 2,3 of B's
-    const uint8_t *gs = (w < 2 ? a_scales_sm + (m0 + w * 128) * 8 : b_scales_sm + (n0 + (w - 2) * 128) * 8) + lane * 16;
-    const int64_t s_stride = (w < 2 ? M : N) * 8;
-    const int nbf = OEK ? (kpad >> 6) : 0, nstage = nbf + (int)(K >> 8);
-    const uint32_t smem_base = __builtin_amdgcn_readfirstlane(lds_address(smem));
-
-    auto issue = [&](int stage) {
-#ifdef ADAHOP_DBG_NO_DMA
-        return;
-#endif
-        const uint32_t sbase = smem_base + (stage & 1) * STAGE_BYTES;
-        const uint32_t sA = sbase + w * 64 * TKB, sB = sA + TM * TKB;
-        const uint8_t *pa, *pb;
-        int64_t rp;
-        const bool bf = OEK && stage < nbf;
-        if (bf) {
-            pa = gga + (int64_t)stage * TKB;
-            pb = ggb + (int64_t)stage * TKB;
-            rp = gpitch * 8;
-        } else {
-            pa = ga + (int64_t)(stage - nbf) * TKB;
-            pb = gb + (int64_t)(stage - nbf) * TKB;
-            rp = pitch * 8;
-        }
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            const int co = (g & 1) ? c_odd : c_even;
-            dma16(pa + g * rp + co, sA + g * 1024);
-            dma16(pb + g * rp + co, sB + g * 1024);
-        }
-        if (!bf) dma16(gs + (int64_t)(stage - nbf) * s_stride, sbase + SLAB_BYTES + w * 1024);
-    };
+    {
+        t.lrow = lane >> 3;
+        t.c_even = ((lane & 7) ^ (lane >> 4)) * 16;
+        t.c_odd = t.c_even ^ 64;
+        t.pitch = (uint32_t)(K >> 1);
+        t.gpitch = (uint32_t)kpad * 2;
+        const int64_t pitch = t.pitch, gpitch = t.gpitch;
+        t.ga = uniform_ptr(a_codes + (m0 + w * 64) * (int64_t)pitch);
+        t.gb = uniform_ptr(b_codes + (n0 + w * 64) * (int64_t)pitch);
+        t.gga = uniform_ptr(reinterpret_cast<const uint8_t *>(Ag) + (m0 + w * 64) * (int64_t)gpitch);
+        t.ggb = uniform_ptr(reinterpret_cast<const uint8_t *>(Bg) + (n0 + w * 64) * (int64_t)gpitch);
+        // scales (stage-major): waves 0,1 move the two 1 KiB halves of the A slab's scales, waves 2,3 of B's
+        t.gs = uniform_ptr(w < 2 ? a_scales_sm + (m0 + w * 128) * 8 : b_scales_sm + (n0 + (w - 2) * 128) * 8);
+        t.vs = lane * 16;
+        t.s_stride = (w < 2 ? M : N) * 8;
+        const uint32_t smem_base = __builtin_amdgcn_readfirstlane(lds_address(smem));
+        t.lds_w = smem_base + w * 64 * TKB;
+        t.lds_s = smem_base + SLAB_BYTES + w * 1024;
+        t.nbf = OEK ? (kpad >> 6) : 0;
+    }
+    const int nstage = t.nbf + (int)(K >> 8);
 
     // ---- fragment reads: row l32 (+32 i) of the wave's slab, logical chunk 4h + s
-    const int rx = (l32 >> 1) & 7;
-    const int off0 = ((4 * h + 0) ^ rx) * 16, off1 = ((4 * h + 1) ^ rx) * 16;
-    const int off2 = ((4 * h + 2) ^ rx) * 16, off3 = ((4 * h + 3) ^ rx) * 16;
-    const int a_row = (wm * 128 + l32) * TKB;
-    const int b_row = TM * TKB + (wn * 128 + l32) * TKB;
-    const int sa_row = SLAB_BYTES + (wm * 128 + l32) * 8 + 4 * h;
-    const int sb_row = SLAB_BYTES + TM * 8 + (wn * 128 + l32) * 8 + 4 * h;
+    {
+        const int rx = (l32 >> 1) & 7;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) t.off[s] = ((4 * h + s) ^ rx) * 16;
+        t.a_row = (wm * 128 + l32) * TKB;
+        t.b_row = TM * TKB + (wn * 128 + l32) * TKB;
+        t.sa_row = SLAB_BYTES + (wm * 128 + l32) * 8 + 4 * h;
+        t.sb_row = SLAB_BYTES + TM * 8 + (wn * 128 + l32) * 8 + 4 * h;
+    }
 
-    v16f acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    frags_t f0, f1;
-    scales_t sc, sc_next;
+            for (int r = 0; r < 16; ++r) t.acc[i][j][r] = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sc.a[i] = sc.b[i] = sc_next.a[i] = sc_next.b[i] = 0;
+    for (int i = 0; i < 4; ++i) t.sc.a[i] = t.sc.b[i] = t.scn.a[i] = t.scn.b[i] = 0;
 
-    // prologue: both buffers filled, stage 0 landed, its first fragments read
-    issue(0);
-    if (nstage > 1) {
-        issue(1);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(16) : "memory"); // stage 1 (>= 16 copies) may still fly
+    // prologue: stage 0 copied and landed, the first slots of stage 1 under way (the rest of stage 1
+    // follows during stage 0, as in every later stage), first fragments of stage 0 read.
+    // Host side guarantees at least two FP4 stages.
+    constexpr int PRO = slot_lo(4); // copies of the four slots that fall into the step before a stage
+    if constexpr (OEK) {
+        issue_copies<true, 0, 17>(t, 0);
+        if (t.nbf > 1)
+            issue_copies<true, 0, PRO>(t, 1);
+        else
+            issue_copies<false, 0, PRO>(t, 1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PRO) : "memory");
     } else {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        issue_copies<false, 0, 17>(t, 0);
+        issue_copies<false, 0, PRO>(t, 1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PRO) : "memory");
     }
     __syncthreads();
-    read_frags(smem + a_row, smem + b_row, off0, f0);
-    if (!(OEK && nbf > 0)) read_scales(smem + sa_row, smem + sb_row, sc);
+    read_frags(smem, t, 0, t.f0);
+    if constexpr (!OEK) read_scales(smem, t, t.sc);
 
-    // Everything of a stage except its last matrix-core step, then the hand-over to the next stage.
-    auto hand_over = [&](int stage) {
-        if (stage + 1 < nstage) {
-            asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)" ::: "memory"); // next stage landed; my reads done
-            __syncthreads();
-            if (stage + 2 < nstage) issue(stage + 2); // refills the buffer just released
-            const uint8_t *sn = smem + ((stage + 1) & 1) * STAGE_BYTES;
-            read_frags(sn + a_row, sn + b_row, off0, f0);
-            if (!(OEK && stage + 1 < nbf)) read_scales(sn + sa_row, sn + sb_row, sc_next);
-        }
-    };
-
+#ifdef ADAHOP_DBG_TIMING
+    const uint64_t dbg_loop_start = __builtin_readcyclecounter();
+#endif
     int stage = 0;
     if constexpr (OEK) {
-        for (; stage < nbf; ++stage) {
-            const uint8_t *st = smem + (stage & 1) * STAGE_BYTES;
-            read_frags(st + a_row, st + b_row, off1, f1);
-            ADAHOP_PIN();
-            mma_bf16(f0, acc);
-            ADAHOP_PIN();
-            read_frags(st + a_row, st + b_row, off2, f0);
-            ADAHOP_PIN();
-            mma_bf16(f1, acc);
-            ADAHOP_PIN();
-            read_frags(st + a_row, st + b_row, off3, f1);
-            ADAHOP_PIN();
-            mma_bf16(f0, acc);
-            ADAHOP_PIN();
-            hand_over(stage);
-            ADAHOP_PIN();
-            mma_bf16(f1, acc);
-            ADAHOP_PIN();
-            sc = sc_next;
+        for (; stage + 2 < t.nbf; ++stage) run_stage<true, true, true, true, true>(t, smem, stage);
+        if (stage + 1 < t.nbf) {
+            run_stage<true, true, false, true, true>(t, smem, stage);
+            ++stage;
         }
+        run_stage<true, false, false, true, true>(t, smem, stage);
+        ++stage;
     }
-    for (; stage < nstage; ++stage) {
-        const uint8_t *st = smem + (stage & 1) * STAGE_BYTES;
-        read_frags(st + a_row, st + b_row, off1, f1);
-        ADAHOP_PIN();
-        mma_fp4<0>(f0, acc, sc);
-        ADAHOP_PIN();
-        read_frags(st + a_row, st + b_row, off2, f0);
-        ADAHOP_PIN();
-        mma_fp4<1>(f1, acc, sc);
-        ADAHOP_PIN();
-        read_frags(st + a_row, st + b_row, off3, f1);
-        ADAHOP_PIN();
-        mma_fp4<2>(f0, acc, sc);
-        ADAHOP_PIN();
-        hand_over(stage);
-        ADAHOP_PIN();
-        mma_fp4<3>(f1, acc, sc);
-        ADAHOP_PIN();
-        sc = sc_next;
-    }
+    for (; stage + 2 < nstage; ++stage) run_stage<false, false, false, true, true>(t, smem, stage);
+    run_stage<false, false, false, true, false>(t, smem, stage);
+    run_stage<false, false, false, false, false>(t, smem, stage + 1);
 
+#ifdef ADAHOP_DBG_TIMING
+    const uint64_t dbg_loop_end = __builtin_readcyclecounter();
+#endif
+#ifndef ADAHOP_DBG_NO_STORE
+#ifdef ADAHOP_DBG_STORE_SMALL
+    const int64_t m0s = (int64_t)((blockIdx.x & 255) / tiles_n) * TM, n0s = (int64_t)((blockIdx.x & 255) % tiles_n) * TN;
+    float *crow = C + (m0s + wm * 128 + h * 4) * ldc + n0s + wn * 128 + l32;
+#else
     float *crow = C + (m0 + wm * 128 + h * 4) * ldc + n0 + wn * 128 + l32;
+#endif
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32] = acc[i][j][r];
+#ifndef ADAHOP_DBG_PLAIN_STORE
+                __builtin_nontemporal_store(t.acc[i][j][r], &crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32]);
+#else
+                crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32] = t.acc[i][j][r];
+#endif
+#else
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += t.acc[i][j][r];
+    if (sum == 123.456f) C[0] = sum;
+#endif
+#ifdef ADAHOP_DBG_TIMING
+    const uint64_t dbg_end = __builtin_readcyclecounter();
+    if (lane == 0) {
+        atomicAdd(&g_dbg[0], (unsigned long long)(dbg_end - dbg_start));
+        atomicAdd(&g_dbg[1], (unsigned long long)t.dbg_dma);
+        atomicAdd(&g_dbg[2], (unsigned long long)t.dbg_bar);
+        atomicAdd(&g_dbg[3], (unsigned long long)(dbg_end - dbg_loop_end));
+        atomicAdd(&g_dbg[4], 1ull);
+        atomicAdd(&g_dbg[5], (unsigned long long)(dbg_loop_end - dbg_loop_start));
+    }
+#endif
 }
 
 } // namespace
+
+#ifdef ADAHOP_DBG_TIMING
+extern "C" void adahop_dbg_read(unsigned long long *out, int reset)
+{
+    (void)hipDeviceSynchronize();
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg), sizeof(g_dbg));
+    if (reset) {
+        unsigned long long z[8] = {0};
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_dbg), z, sizeof(z));
+    }
+}
+#endif
 
 size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
@@ -422,7 +569,7 @@ int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, cons
 {
     if (M == 0 || N == 0) return ADAHOP_OK;
     const bool tiled = M % TM == 0 && N % TN == 0 && K % 256 == 0 && kpad % 64 == 0 && aligned(a_scales, 8) &&
-                       aligned(b_scales, 8) && (M / TM) * (N / TN) < (1 << 30);
+                       aligned(b_scales, 8) && (M / TM) * (N / TN) < (1 << 30) && K >= 512;
     if (tiled) {
         static bool configured = false;
         if (!configured) {
