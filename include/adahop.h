@@ -131,7 +131,7 @@ typedef struct {
     size_t a_codes, a_scales, b_codes, b_scales; /* byte offsets into the workspace */
     size_t mask;                                 /* uint8 [extracted dim]           */
     size_t scores;                               /* float [extracted dim]           */
-    size_t gather_a, gather_b;                   /* bf16 staging for the BF16 part  */
+    size_t gather_a, gather_b;                   /* scratch of the BF16 part        */
     size_t gemm;                                 /* scratch of the MXFP4 product    */
     size_t total;                                /* bytes required                  */
 } adahop_ws_layout_t;
@@ -150,7 +150,9 @@ int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, 
  *   kind OE_COL: C[:, idx[t]]  = A * B[:, idx[t]]          (overwrites those columns)
  *   kind OE_K  : C            += A[:, idx] * B[idx, :]     (accumulates)
  * idx int32 [k] device, distinct, in range.  gather_ws: device scratch of at least
- * adahop_oe_gather_bytes(M, N, K, kind, k) bytes, 256-byte aligned. */
+ * adahop_oe_gather_bytes(M, N, K, kind, k) bytes, 256-byte aligned (the gathered rows / columns /
+ * K-channels and, for OE_ROW and OE_COL, the partial products of the K slices); contents undefined
+ * on return. */
 size_t adahop_oe_gather_bytes(int64_t M, int64_t N, int64_t K, adahop_strategy_t kind, int k);
 int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, adahop_strategy_t kind,
                         const int32_t *idx, int k, float *C, int64_t ldc, void *gather_ws,

@@ -130,7 +130,8 @@ int adahop_gemm_workspace_layout(int64_t M, int64_t N, int64_t K, adahop_strateg
     out->mask = take((size_t)dim);
     out->scores = take((size_t)dim * sizeof(float));
     const bool oek = strategy == ADAHOP_IHT_OE_K && k > 0;
-    out->gather_a = take(oek ? (size_t)M * kpad_of(k) * 2 : 0);
+    const bool oerc = (strategy == ADAHOP_IHT_OE_ROW || strategy == ADAHOP_IHT_OE_COL) && k > 0;
+    out->gather_a = take(oek ? (size_t)M * kpad_of(k) * 2 : oerc ? oe_rowcol_workspace_bytes(M, N, K, strategy, k) : 0);
     out->gather_b = take(oek ? (size_t)N * kpad_of(k) * 2 : 0);
     out->gemm = take(gemm_mx_workspace_bytes(M, N, K));
     out->total = off;
@@ -146,8 +147,9 @@ size_t adahop_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, adahop_strat
 
 size_t adahop_oe_gather_bytes(int64_t M, int64_t N, int64_t K, adahop_strategy_t kind, int k)
 {
-    (void)K;
-    if (kind != ADAHOP_IHT_OE_K || k <= 0 || M < 1 || N < 1) return 0;
+    if (k <= 0 || M < 1 || N < 1 || K < 1) return 0;
+    if (kind == ADAHOP_IHT_OE_ROW || kind == ADAHOP_IHT_OE_COL) return oe_rowcol_workspace_bytes(M, N, K, kind, k);
+    if (kind != ADAHOP_IHT_OE_K) return 0;
     return align_up((size_t)M * kpad_of(k) * 2, 256) + align_up((size_t)N * kpad_of(k) * 2, 256);
 }
 
@@ -172,9 +174,9 @@ int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, ad
     if (k < 0 || k > dim || (k > 0 && !idx)) return ADAHOP_E_INVALID_ARG;
     if (k == 0) return ADAHOP_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (kind != ADAHOP_IHT_OE_K) return launch_oe_rowcol(*A, *B, kind, idx, k, C, ldc, st);
     const size_t need = adahop_oe_gather_bytes(A->outer, B->outer, A->K, kind, k);
     if (!gather_ws || !aligned(gather_ws, 256) || gather_bytes < need) return ADAHOP_E_WORKSPACE;
+    if (kind != ADAHOP_IHT_OE_K) return launch_oe_rowcol(*A, *B, kind, idx, k, C, ldc, gather_ws, st);
     const int kpad = kpad_of(k);
     uint16_t *Ag = static_cast<uint16_t *>(gather_ws);
     uint16_t *Bg = reinterpret_cast<uint16_t *>(static_cast<char *>(gather_ws) + align_up((size_t)A->outer * kpad * 2, 256));
@@ -245,7 +247,7 @@ int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, 
     }
     rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0, ws + L.gemm, st);
     if (rc != ADAHOP_OK) return rc;
-    if (oe) rc = launch_oe_rowcol(*A, *B, strategy, idx_inout, k, C, ldc, st);
+    if (oe) rc = launch_oe_rowcol(*A, *B, strategy, idx_inout, k, C, ldc, ws + L.gather_a, st);
     return rc;
 }
 

@@ -37,8 +37,10 @@ int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, cons
                    const uint16_t *Ag, const uint16_t *Bg, int kpad, void *workspace, hipStream_t st);
 size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kpad, uint16_t *out, hipStream_t st);
+// Row / column outlier product; workspace of oe_rowcol_workspace_bytes() bytes, 256-byte aligned.
+size_t oe_rowcol_workspace_bytes(int64_t M, int64_t N, int64_t K, int kind, int k);
 int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int kind, const int32_t *idx, int k,
-                     float *C, int64_t ldc, hipStream_t st);
+                     float *C, int64_t ldc, void *workspace, hipStream_t st);
 int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint16_t *Bg, int kpad, float *C,
                            int64_t ldc, hipStream_t st);
 

@@ -16,52 +16,197 @@ namespace {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
-// Eight consecutive K-elements (kk .. kk+7) of row o of an operand, as packed bf16.
-__device__ __forceinline__ uint4 load8(const uint16_t *__restrict__ d, int64_t ld, int k_contig, int64_t o, int64_t kk)
+// ------------------------------------------------------------------------------------------------
+// Row / column form.  With S the k extracted rows of the "short" operand (A for OE-row, B for
+// OE-col) and L the other, "long" operand, both products are  P[t, l] = sum_kk S(idx[t], kk) L(l, kk),
+// a skinny product: a few hundred rows against a whole operand, bound by reading L once.
+//
+//   1. k_gather_rows   copies the extracted rows into a K-contiguous staging matrix Sg, zero padded to
+//                      whole 32-row matrix-core tiles;
+//   2. k_oe_skinny     workgroup = (RT x 32 rows of Sg) x (128 rows of L) x (one slice of K); both
+//                      operands go through LDS in a K-contiguous [row][64 K] layout, so a K-strided L
+//                      is transposed on its way into LDS (16-bit scatter stores) while its global reads
+//                      stay 16 bytes per lane; the next stage is fetched into registers while the
+//                      matrix cores work on the current one.  K is split over workgroups so that the
+//                      chip is full although there are few tiles; every slice writes its own partial
+//                      tile (no atomics: the result does not depend on scheduling);
+//   3. k_oe_reduce     adds the slices in a fixed order and writes the rows / columns of C.
+// ------------------------------------------------------------------------------------------------
+constexpr int SK_LCOLS = 128;  // rows of L per workgroup
+constexpr int SK_KSTAGE = 64;  // K-elements per pipeline stage
+constexpr int SK_PITCH = 72;   // LDS row pitch in bf16 (144 bytes: 16-byte fragment reads of 16
+                               // consecutive rows then cover the 64 banks exactly once)
+
+__global__ __launch_bounds__(256) void k_gather_rows(const uint16_t *__restrict__ x, int64_t ld, int k_contig, int64_t K,
+                                                     const int32_t *__restrict__ idx, int k, int rows_alloc,
+                                                     uint16_t *__restrict__ out)
 {
-    if (k_contig) return *reinterpret_cast<const uint4 *>(d + o * ld + kk);
-    uint32_t e[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) e[t] = d[(kk + t) * ld + o];
-    return make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k_contig) { // one thread = 8 consecutive K-elements of one row
+        const int64_t per_row = K >> 3;
+        if (g >= rows_alloc * per_row) return;
+        const int64_t t = g / per_row, c = g - t * per_row;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (t < k) v = *reinterpret_cast<const uint4 *>(x + (int64_t)idx[t] * ld + c * 8);
+        *reinterpret_cast<uint4 *>(out + t * K + c * 8) = v;
+    } else {        // one thread = one element; neighbouring threads write neighbouring K
+        if (g >= rows_alloc * K) return;
+        const int64_t t = g / K, kk = g - t * K;
+        out[g] = t < k ? x[kk * ld + idx[t]] : (uint16_t)0;
+    }
 }
 
-// Workgroup tile 64x64 (four waves, one 32x32 matrix-core tile each).  ROWS: the tile's rows are
-// gathered through idx (OE-row); else its columns are (OE-col).
-template <bool ROWS>
-__global__ __launch_bounds__(256) void k_oe_rowcol(const uint16_t *__restrict__ A, int64_t lda, int a_kc,
-                                                   const uint16_t *__restrict__ B, int64_t ldb, int b_kc, int64_t M,
-                                                   int64_t N, int64_t K, const int32_t *__restrict__ idx, int k,
-                                                   float *__restrict__ C, int64_t ldc)
+template <int RT, bool LONG_KC>
+__global__ __launch_bounds__(256, 2) void k_oe_skinny(const uint16_t *__restrict__ Sg, const uint16_t *__restrict__ L,
+                                                      int64_t ldl, int64_t Lo, int64_t K, int stages_per_slice,
+                                                      float *__restrict__ P, int64_t rows_all)
 {
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int l32 = lane & 31, h = lane >> 5;
-    const int64_t R = ROWS ? k : M, Cn = ROWS ? N : k;
-    const int64_t r0 = (int64_t)blockIdx.y * 64 + (w >> 1) * 32;
-    const int64_t c0 = (int64_t)blockIdx.x * 64 + (w & 1) * 32;
-    const int64_t r = r0 + l32, c = c0 + l32;
-    const bool rok = r < R, cok = c < Cn;
-    const int64_t arow = rok ? (ROWS ? (int64_t)idx[r] : r) : 0;
-    const int64_t brow = cok ? (ROWS ? c : (int64_t)idx[c]) : 0;
+    __shared__ __attribute__((aligned(16))) uint16_t sS[RT * 32 * SK_PITCH];
+    __shared__ __attribute__((aligned(16))) uint16_t sL[SK_LCOLS * SK_PITCH];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const int64_t l0 = (int64_t)blockIdx.x * SK_LCOLS;
+    const int nstage_all = (int)((K + SK_KSTAGE - 1) / SK_KSTAGE);
+    const int s0 = blockIdx.y * stages_per_slice, s1 = min(s0 + stages_per_slice, nstage_all);
+    Sg += (int64_t)blockIdx.z * RT * 32 * K;
+    P += ((int64_t)blockIdx.y * rows_all + (int64_t)blockIdx.z * RT * 32) * Lo;
 
-    v16f acc;
+    // loader geometry
+    const int c8 = tid & 7, r32 = tid >> 3;           // K-contiguous: 16-byte chunk c8 of rows r32 + 32 i
+    const int lane16 = lane & 15, grp = lane >> 4;    // K-strided: K offset lane16, 8 L-rows at 32 w + 8 grp
+    uint4 ps[RT], pl[4];
+
+    auto fetch = [&](int stage) {
+        const int64_t kk0 = (int64_t)stage * SK_KSTAGE;
 #pragma unroll
-    for (int t = 0; t < 16; ++t) acc[t] = 0.0f;
-    for (int64_t kk = 0; kk < K; kk += 16) {
-        uint4 a = rok ? load8(A, lda, a_kc, arow, kk + h * 8) : make_uint4(0, 0, 0, 0);
-        uint4 b = cok ? load8(B, ldb, b_kc, brow, kk + h * 8) : make_uint4(0, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), acc, 0, 0, 0);
+        for (int i = 0; i < RT; ++i) {
+            const int64_t kk = kk0 + c8 * 8;
+            ps[i] = kk < K ? *reinterpret_cast<const uint4 *>(Sg + (int64_t)(r32 + 32 * i) * K + kk) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (LONG_KC) {
+                const int64_t kk = kk0 + c8 * 8, l = l0 + r32 + 32 * i;
+                pl[i] = (kk < K && l < Lo) ? *reinterpret_cast<const uint4 *>(L + l * ldl + kk) : make_uint4(0, 0, 0, 0);
+            } else {
+                const int64_t kk = kk0 + 16 * i + lane16, l = l0 + 32 * w + 8 * grp;
+                pl[i] = (kk < K && l < Lo) ? *reinterpret_cast<const uint4 *>(L + kk * ldl + l) : make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < RT; ++i) *reinterpret_cast<uint4 *>(sS + (r32 + 32 * i) * SK_PITCH + c8 * 8) = ps[i];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (LONG_KC) {
+                *reinterpret_cast<uint4 *>(sL + (r32 + 32 * i) * SK_PITCH + c8 * 8) = pl[i];
+            } else {
+                uint16_t *d = sL + (32 * w + 8 * grp) * SK_PITCH + 16 * i + lane16;
+                const uint32_t e[4] = {pl[i].x, pl[i].y, pl[i].z, pl[i].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    d[(2 * j) * SK_PITCH] = (uint16_t)(e[j] & 0xffffu);
+                    d[(2 * j + 1) * SK_PITCH] = (uint16_t)(e[j] >> 16);
+                }
+            }
+        }
+    };
+
+    v16f acc[RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+
+    if (s0 < s1) {
+        fetch(s0);
+        stash();
     }
-    if (!cok) return;
-    const int64_t ocol = ROWS ? c : (int64_t)idx[c];
+    __syncthreads();
+    for (int stage = s0; stage < s1; ++stage) {
+        const bool more = stage + 1 < s1;
+        if (more) fetch(stage + 1);
 #pragma unroll
-    for (int t = 0; t < 16; ++t) {
-        const int64_t rr = r0 + (t >> 2) * 8 + h * 4 + (t & 3);
-        if (rr < R) {
-            const int64_t orow = ROWS ? (int64_t)idx[rr] : rr;
-            C[orow * ldc + ocol] = acc[t];
+        for (int ks = 0; ks < SK_KSTAGE / 16; ++ks) {
+            const uint4 b = *reinterpret_cast<const uint4 *>(sL + (32 * w + l32) * SK_PITCH + 16 * ks + 8 * h);
+#pragma unroll
+            for (int i = 0; i < RT; ++i) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(sS + (32 * i + l32) * SK_PITCH + 16 * ks + 8 * h);
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), acc[i], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+        if (more) stash();
+        __syncthreads();
+    }
+
+    const int64_t l = l0 + 32 * w + l32;
+    if (l < Lo) {
+#pragma unroll
+        for (int i = 0; i < RT; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) P[(int64_t)(32 * i + (r >> 2) * 8 + h * 4 + (r & 3)) * Lo + l] = acc[i][r];
+    }
+}
+
+// C[idx[t], l] (ROWS) or C[l, idx[t]] = sum over the K slices of P[s][t][l], in slice order.
+template <bool ROWS>
+__global__ __launch_bounds__(256) void k_oe_reduce(const float *__restrict__ P, int nslice, int64_t rows_all, int64_t Lo,
+                                                   const int32_t *__restrict__ idx, int k, float *__restrict__ C, int64_t ldc)
+{
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= (int64_t)k * Lo) return;
+    const int64_t t = g / Lo, l = g - t * Lo;
+    float s = 0.0f;
+    for (int i = 0; i < nslice; ++i) s += P[((int64_t)i * rows_all + t) * Lo + l];
+    const int64_t o = idx[t];
+    if (ROWS)
+        C[o * ldc + l] = s;
+    else
+        C[l * ldc + o] = s;
+}
+
+struct skinny_plan_t {
+    int rt, groups, nslice, stages_per_slice;
+    int64_t rows_all;
+    size_t sg_bytes, p_bytes;
+};
+
+// Row tiles per workgroup from {2, 4, 6, 8} with the least padding; K slices so that about two
+// workgroups per compute unit exist, each with at least 8 stages.
+skinny_plan_t plan_skinny(int64_t Lo, int64_t K, int k)
+{
+    skinny_plan_t p;
+    const int tiles = (k + 31) / 32;
+    p.rt = 8;
+    p.groups = (tiles + 7) / 8;
+    for (int rt = 6; rt >= 2; rt -= 2) {
+        const int g = (tiles + rt - 1) / rt;
+        if (g * rt < p.groups * p.rt || (g * rt == p.groups * p.rt && g < p.groups)) {
+            p.rt = rt;
+            p.groups = g;
         }
     }
+    p.rows_all = (int64_t)p.groups * p.rt * 32;
+    const int64_t nstage = ceil_div(K, SK_KSTAGE), wgs = ceil_div(Lo, SK_LCOLS) * p.groups;
+    int64_t want = ceil_div(512, wgs);
+    if (want > nstage / 8) want = nstage / 8;
+    if (want < 1) want = 1;
+    p.stages_per_slice = (int)ceil_div(nstage, want);
+    p.nslice = (int)ceil_div(nstage, p.stages_per_slice);
+    p.sg_bytes = align_up((size_t)p.rows_all * K * 2, 256);
+    p.p_bytes = align_up((size_t)p.nslice * p.rows_all * Lo * 4, 256);
+    return p;
+}
+
+template <int RT>
+void launch_skinny(bool long_kc, dim3 grid, hipStream_t st, const uint16_t *Sg, const uint16_t *L, int64_t ldl, int64_t Lo,
+                   int64_t K, int sps, float *P, int64_t rows_all)
+{
+    if (long_kc)
+        hipLaunchKernelGGL((k_oe_skinny<RT, true>), grid, dim3(256), 0, st, Sg, L, ldl, Lo, K, sps, P, rows_all);
+    else
+        hipLaunchKernelGGL((k_oe_skinny<RT, false>), grid, dim3(256), 0, st, Sg, L, ldl, Lo, K, sps, P, rows_all);
 }
 
 // out[o, t] = x(o, idx[t]) for t < k, 0 for k <= t < kpad.  out is [outer, kpad] bf16.
@@ -98,22 +243,47 @@ int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kp
     return check_launch();
 }
 
+size_t oe_rowcol_workspace_bytes(int64_t M, int64_t N, int64_t K, int kind, int k)
+{
+    if (k <= 0) return 0;
+    const skinny_plan_t p = plan_skinny(kind == ADAHOP_IHT_OE_ROW ? N : M, K, k);
+    return p.sg_bytes + p.p_bytes;
+}
+
 int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int kind, const int32_t *idx, int k,
-                     float *C, int64_t ldc, hipStream_t st)
+                     float *C, int64_t ldc, void *workspace, hipStream_t st)
 {
     const int64_t M = A.outer, N = B.outer, K = A.K;
     if (k == 0 || M == 0 || N == 0) return ADAHOP_OK;
-    const uint16_t *a = static_cast<const uint16_t *>(A.data);
-    const uint16_t *b = static_cast<const uint16_t *>(B.data);
-    if (kind == ADAHOP_IHT_OE_ROW) {
-        dim3 grid((unsigned)ceil_div(N, 64), (unsigned)ceil_div(k, 64));
-        hipLaunchKernelGGL((k_oe_rowcol<true>), grid, dim3(256), 0, st, a, A.ld, A.k_contig, b, B.ld, B.k_contig, M, N,
-                           K, idx, k, C, ldc);
-    } else {
-        dim3 grid((unsigned)ceil_div(k, 64), (unsigned)ceil_div(M, 64));
-        hipLaunchKernelGGL((k_oe_rowcol<false>), grid, dim3(256), 0, st, a, A.ld, A.k_contig, b, B.ld, B.k_contig, M,
-                           N, K, idx, k, C, ldc);
+    const bool rows = kind == ADAHOP_IHT_OE_ROW;
+    const adahop_operand_t &S = rows ? A : B, &L = rows ? B : A;
+    const int64_t Lo = L.outer;
+    const skinny_plan_t p = plan_skinny(Lo, K, k);
+    uint16_t *Sg = static_cast<uint16_t *>(workspace);
+    float *P = reinterpret_cast<float *>(static_cast<char *>(workspace) + p.sg_bytes);
+
+    const int64_t gthreads = S.k_contig ? p.rows_all * (K >> 3) : p.rows_all * K;
+    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)ceil_div(gthreads, 256)), dim3(256), 0, st,
+                       static_cast<const uint16_t *>(S.data), S.ld, S.k_contig, K, idx, k, (int)p.rows_all, Sg);
+    int rc = check_launch();
+    if (rc != ADAHOP_OK) return rc;
+
+    const dim3 grid((unsigned)ceil_div(Lo, SK_LCOLS), (unsigned)p.nslice, (unsigned)p.groups);
+    const uint16_t *l = static_cast<const uint16_t *>(L.data);
+    switch (p.rt) {
+    case 2: launch_skinny<2>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
+    case 4: launch_skinny<4>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
+    case 6: launch_skinny<6>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
+    default: launch_skinny<8>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
     }
+    rc = check_launch();
+    if (rc != ADAHOP_OK) return rc;
+
+    const unsigned rblocks = (unsigned)ceil_div((int64_t)k * Lo, 256);
+    if (rows)
+        hipLaunchKernelGGL((k_oe_reduce<true>), dim3(rblocks), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx, k, C, ldc);
+    else
+        hipLaunchKernelGGL((k_oe_reduce<false>), dim3(rblocks), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx, k, C, ldc);
     return check_launch();
 }
 

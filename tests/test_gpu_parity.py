@@ -283,15 +283,17 @@ def test_oe_k_zero_equals_iht(ah):
         assert np.array_equal(host(ah.adahop_gemm(A, B, s, 32, 0)["C"]), c_iht)
 
 
-def test_oe_gemm_bf16_standalone(ah):
+@pytest.mark.parametrize("M,N,K,k_row,k_col,k_k", [(152, 88, 160, 37, 5, 19), (520, 264, 1088, 300, 70, 33)])
+def test_oe_gemm_bf16_standalone(ah, M, N, K, k_row, k_col, k_k):
+    """Second term of Eq. 7 / Eq. 8 / the K-channel form alone; the larger case needs several row-tile groups
+    and several K slices of the row / column kernel."""
     rng = np.random.default_rng(3)
-    M, N, K = 152, 88, 160
     for a_kc, b_kc in LAYOUTS.values():
         A_log, B_log = rand_bits(rng, (M, K)), rand_bits(rng, (N, K), 0.05)
         A = inputs.Operand(A_log if a_kc else np.ascontiguousarray(A_log.T), a_kc)
         B = inputs.Operand(B_log if b_kc else np.ascontiguousarray(B_log.T), b_kc)
         dA, dB = dev_op(ah, A), dev_op(ah, B)
-        for kind, dim, k in ((inputs.IHT_OE_ROW, M, 37), (inputs.IHT_OE_COL, N, 5), (inputs.IHT_OE_K, K, 19)):
+        for kind, dim, k in ((inputs.IHT_OE_ROW, M, k_row), (inputs.IHT_OE_COL, N, k_col), (inputs.IHT_OE_K, K, k_k)):
             sel = np.sort(rng.permutation(dim)[:k]).astype(np.int32)
             base = rng.standard_normal((M, N)).astype(np.float32)
             C = torch.from_numpy(base.copy()).cuda()
