@@ -19,6 +19,11 @@ import numpy as np
 MXFP4_PEAK_TFLOPS = 10066.0   # MI355X dense FP4 matrix-core peak: 256 CU x 16384 flop/clk x 2.4 GHz
 BF16_PEAK_TFLOPS = 2516.0
 
+# HBM bytes per launch of the FP4 GEMM kernel, by (M, N, K): rocprofv3 FETCH_SIZE + WRITE_SIZE (KiB per
+# dispatch), each scaled by what the same counter reads for a plain 1 GiB copy (--copy-calibration);
+# the runs and the scaling are in profiles/gemm_mx_16384x28672x8192_counters.txt.
+GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 5.41e9}
+
 
 def parse():
     p = argparse.ArgumentParser()
@@ -29,6 +34,9 @@ def parse():
     p.add_argument("--k-pct", type=float, default=1.0, help="extraction count as %% of the extracted dim (cfg4)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the k-sweep / BF16 / per-stage extras")
+    p.add_argument("--copy-calibration", action="store_true",
+                   help="also run one plain 1 GiB device-to-device copy (reference reading for rocprofv3's "
+                        "FETCH_SIZE / WRITE_SIZE counters)")
     return p.parse_args()
 
 
@@ -99,7 +107,7 @@ def cpu_baseline(workload_gemms):
     from oracle import reference as orc
     g = workload_gemms[0]
     M, N, K = g.shape
-    ms, ns = min(M, 1024), min(N, 2048)
+    ms, ns = min(M, 4096), min(N, 8192)
     a = g.A.bits[:ms] if g.A.k_contig else g.A.bits[:, :ms]
     b = g.B.bits[:ns] if g.B.k_contig else g.B.bits[:, :ns]
     k = min(g.k, {2: ms, 3: ns, 4: K}.get(g.strategy, 0))
@@ -159,7 +167,8 @@ def main():
     gemm_ms = time_ms(torch, lambda: ah.adahop_gemm_mx(ac, asc, bc, bsc, big.C, gemm_ws), max(5, args.steps))
     achieved = big.flops / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "mxfp4 gemm", "achieved": achieved, "peak": MXFP4_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MXFP4_PEAK_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / MXFP4_PEAK_TFLOPS,
+                "traffic": GEMM_HBM_TRAFFIC_BYTES.get((big.M, big.N, big.K)),
                 "shape": [big.M, big.N, big.K], "ms": gemm_ms}
 
     out = {"metric": "effective TFLOP/s of IHT+MXFP4(+OE) GEMM vs BF16 GEMM; % MXFP4 MFMA peak",
@@ -191,6 +200,14 @@ def main():
         extras["iht_only_tflops"] = total_flops / t_iht_total / 1e9
         extras["iht_only_pct_mxfp4_peak"] = 100.0 * extras["iht_only_tflops"] / MXFP4_PEAK_TFLOPS
         extras["bf16_hipblaslt_tflops"] = total_flops / sum(x["ms_bf16_hipblaslt"] for x in per) / 1e9
+        # what the matrix cores sustain with no memory traffic at all (register-only loop, 256 workgroups)
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        probe = {}
+        for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
+            flop = ah.adahop_probe_mfma_rate(rnd, 256, 4000, sink)
+            p_ms = time_ms(torch, lambda: ah.adahop_probe_mfma_rate(rnd, 256, 4000, sink), 3)
+            probe[name] = flop / p_ms / 1e9
+        extras["mfma_only_tflops"] = probe
         # quantiser bandwidth on the largest operand of the largest GEMM (2 + 1/2 + 1/32 bytes / element)
         qx = big.B if big.N >= big.M else big.A
         codes = torch.empty((qx.outer, qx.K // 2), dtype=torch.uint8, device="cuda")
@@ -199,6 +216,14 @@ def main():
         extras["iht_quantize"] = {"outer": qx.outer, "K": qx.K, "k_contig": qx.k_contig, "ms": q_ms,
                                   "GBps": 2.53125 * qx.outer * qx.K / (q_ms * 1e-3) / 1e9, "peak_GBps": 8000.0}
         out["extras"] = extras
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration_bytes"] = src.numel() * 4
+        del src, dst
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(gemms)

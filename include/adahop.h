@@ -158,6 +158,14 @@ int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, ad
                         const int32_t *idx, int k, float *C, int64_t ldc, void *gather_ws,
                         size_t gather_bytes, void *stream);
 
+/* Measurement aid (not part of the method): launches `workgroups` x 4 waves that each run
+ * iters x 16 block-scaled FP4 matrix-core instructions (32x32x64, 131072 flop each) on register
+ * operands only -- constant bits, or pseudo-random bits if random_operands != 0 -- so that a caller
+ * timing the launch obtains the rate the matrix cores sustain on this machine without any memory
+ * traffic: 2 * 65536 * 16 * iters * 4 * workgroups flop.  sink: one device float (never written in
+ * practice).  Used by bench.py to report the power-limited ceiling beside the published peak. */
+int adahop_probe_mfma_rate(int random_operands, int workgroups, int iters, float *sink, void *stream);
+
 /* hipError_t (as int) of the most recent failed HIP call on this thread, 0 if none. */
 int adahop_last_hip_error(void);
 const char *adahop_status_string(int status);

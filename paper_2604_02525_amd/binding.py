@@ -19,7 +19,8 @@ ADAHOP_OK, ADAHOP_E_INVALID_ARG, ADAHOP_E_WORKSPACE, ADAHOP_E_HIP = 0, -1, -2, -
 EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_gemm_mx",
            "adahop_gemm_mx_workspace_bytes",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
-           "adahop_oe_gemm_bf16", "adahop_last_hip_error", "adahop_status_string", "adahop_abi_version"]
+           "adahop_oe_gemm_bf16", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
+           "adahop_abi_version"]
 
 
 class AdahopError(RuntimeError):
@@ -66,6 +67,7 @@ def lib():
         L.adahop_oe_gather_bytes.argtypes = [I64, I64, I64, I, I]
         L.adahop_oe_gather_bytes.restype = SZ
         L.adahop_oe_gemm_bf16.argtypes = [OP, OP, I, P, I, P, I64, P, SZ, P]
+        L.adahop_probe_mfma_rate.argtypes = [I, I, I, P, P]
         L.adahop_status_string.restype = C.c_char_p
         L.adahop_status_string.argtypes = [I]
         for name in EXPORTS:
@@ -208,3 +210,10 @@ def adahop_oe_gemm_bf16(A, B, kind, idx, Cout, gather_ws=None, stream=None):
                                      _ptr(gather_ws), 0 if gather_ws is None else gather_ws.numel(), _stream(stream)),
            "adahop_oe_gemm_bf16")
     return Cout
+
+
+def adahop_probe_mfma_rate(random_operands, workgroups, iters, sink, stream=None):
+    """Measurement aid: register-only matrix-core loop; returns the flop count of the launch."""
+    _check(lib().adahop_probe_mfma_rate(int(bool(random_operands)), workgroups, iters, _ptr(sink), _stream(stream)),
+           "adahop_probe_mfma_rate")
+    return 2.0 * 65536 * 16 * iters * 4 * workgroups

@@ -34,15 +34,29 @@ __global__ __launch_bounds__(256) void k_foid_scores(const uint16_t *__restrict_
     scores[i] = v;
 }
 
-constexpr int TOPK_THREADS = 1024;
+constexpr int TOPK_THREADS = 1024, TOPK_WAVES = TOPK_THREADS / 64;
+
+// hist[bin] += 1 for every lane with valid set, one LDS atomic per distinct bin of the wave: the
+// scores of ordinary rows share their high bytes, and per-key atomics on one bin would serialise.
+__device__ __forceinline__ void wave_histogram(uint32_t *hist, bool valid, uint32_t bin)
+{
+    uint64_t todo = __ballot(valid);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const uint32_t b = __builtin_amdgcn_readlane(bin, leader);
+        const uint64_t same = __ballot(valid && bin == b);
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[b], (uint32_t)__popcll(same));
+        todo &= ~same;
+    }
+}
 
 __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__ scores, int dim, int k,
                                                        int32_t *__restrict__ idx, uint8_t *__restrict__ mask)
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sh_prefix, sh_remaining;
-    __shared__ uint32_t scan_gt[TOPK_THREADS], scan_eq[TOPK_THREADS];
-    const int tid = threadIdx.x;
+    __shared__ uint32_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const uint32_t *keys = reinterpret_cast<const uint32_t *>(scores);
 
     if (k <= 0) {
@@ -53,12 +67,13 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__
     // Radix select: after the 4 passes `prefix` is the key of the k-th largest score and
     // `remaining` is how many keys equal to it are still to be taken.
     uint32_t prefix = 0, pmask = 0, remaining = (uint32_t)k;
+    const int dim_up = (dim + TOPK_THREADS - 1) / TOPK_THREADS * TOPK_THREADS; // whole waves stay in the loop
     for (int shift = 24; shift >= 0; shift -= 8) {
         for (int b = tid; b < 256; b += TOPK_THREADS) hist[b] = 0;
         __syncthreads();
-        for (int i = tid; i < dim; i += TOPK_THREADS) {
-            const uint32_t key = keys[i];
-            if ((key & pmask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        for (int i = tid; i < dim_up; i += TOPK_THREADS) {
+            const uint32_t key = i < dim ? keys[i] : 0u;
+            wave_histogram(hist, i < dim && (key & pmask) == prefix, (key >> shift) & 255u);
         }
         __syncthreads();
         if (tid == 0) {
@@ -79,40 +94,41 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__
     }
     const uint32_t T = prefix;
 
-    // Ordered compaction: thread t owns the contiguous index range [t*per, (t+1)*per).
-    const int per = (dim + TOPK_THREADS - 1) / TOPK_THREADS;
-    const int lo = tid * per;
-    const int hi = min(dim, lo + per);
+    // Ordered compaction: wave w owns the contiguous index range [w*per, (w+1)*per), per a multiple
+    // of 64, and walks it 64 consecutive keys at a time.
+    const int per = ((dim + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64;
+    const int lo = w * per, hi = min(dim, lo + per);
     uint32_t gt = 0, eq = 0;
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t key = keys[i];
-        gt += key > T;
-        eq += key == T;
+    for (int i0 = lo; i0 < hi; i0 += 64) {
+        const int i = i0 + lane;
+        const uint32_t key = i < hi ? keys[i] : 0u;
+        gt += (uint32_t)__popcll(__ballot(i < hi && key > T));
+        eq += (uint32_t)__popcll(__ballot(i < hi && key == T));
     }
-    scan_gt[tid] = gt;
-    scan_eq[tid] = eq;
+    if (lane == 0) {
+        wave_gt[w] = gt;
+        wave_eq[w] = eq;
+    }
     __syncthreads();
-    for (int d = 1; d < TOPK_THREADS; d *= 2) {
-        uint32_t a = 0, b = 0;
-        if (tid >= d) {
-            a = scan_gt[tid - d];
-            b = scan_eq[tid - d];
-        }
-        __syncthreads();
-        scan_gt[tid] += a;
-        scan_eq[tid] += b;
-        __syncthreads();
+    uint32_t gt_before = 0, eq_before = 0;
+    for (int v = 0; v < w; ++v) {
+        gt_before += wave_gt[v];
+        eq_before += wave_eq[v];
     }
-    uint32_t gt_before = scan_gt[tid] - gt, eq_before = scan_eq[tid] - eq;
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t key = keys[i];
-        const bool is_gt = key > T;
-        const bool is_eq = key == T;
-        const bool sel = is_gt || (is_eq && eq_before < remaining);
-        if (sel) idx[gt_before + min(eq_before, remaining)] = i;
-        mask[i] = sel ? 1 : 0;
-        gt_before += is_gt;
-        eq_before += is_eq;
+    const uint64_t below = ((uint64_t)1 << lane) - 1;
+    for (int i0 = lo; i0 < hi; i0 += 64) {
+        const int i = i0 + lane;
+        const uint32_t key = i < hi ? keys[i] : 0u;
+        const bool is_gt = i < hi && key > T, is_eq = i < hi && key == T;
+        const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
+        const uint32_t my_gt = gt_before + (uint32_t)__popcll(m_gt & below);
+        const uint32_t my_eq = eq_before + (uint32_t)__popcll(m_eq & below);
+        const bool sel = is_gt || (is_eq && my_eq < remaining);
+        // selected entries before this one: every greater key, and the equal keys that were taken
+        if (sel) idx[my_gt + min(my_eq, remaining)] = i;
+        if (i < hi) mask[i] = sel ? 1 : 0;
+        gt_before += (uint32_t)__popcll(m_gt);
+        eq_before += (uint32_t)__popcll(m_eq);
     }
 }
 

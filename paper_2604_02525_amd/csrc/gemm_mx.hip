@@ -250,16 +250,16 @@ __device__ __forceinline__ void read_scales(const uint8_t *buf, const tile_state
     }
 }
 
-// One row of matrix-core tiles (4 instructions) of step S of a stage.
-template <bool BF, int S> __device__ __forceinline__ void mma_row(const frags_t &f, tile_state_t &t, int i)
+// Matrix-core instructions q0 .. q1-1 (of 16: instruction q is tile row q / 4, column q % 4) of step S.
+template <bool BF, int S> __device__ __forceinline__ void mma_some(const frags_t &f, tile_state_t &t, int q0, int q1)
 {
+#pragma unroll
+    for (int q = q0; q < q1; ++q) {
+        const int i = q >> 2, j = q & 3;
 #ifdef ADAHOP_DBG_NO_MMA
-#pragma unroll
-    for (int j = 0; j < 4; ++j) t.acc[i][j][S] += __int_as_float((f.a[i].x ^ f.b[j].y ^ t.sc.a[i] ^ t.sc.b[j]) & 0x3fffffff);
-    return;
+        t.acc[i][j][S] += __int_as_float((f.a[i].x ^ f.b[j].y ^ t.sc.a[i] ^ t.sc.b[j]) & 0x3fffffff);
+        continue;
 #endif
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
         if constexpr (BF) {
             t.acc[i][j] = mfma_bf16(f.a[i], f.b[j], t.acc[i][j]);
         } else {
@@ -272,8 +272,7 @@ template <bool BF, int S> __device__ __forceinline__ void mma_row(const frags_t 
 
 template <bool BF, int S> __device__ __forceinline__ void mma_step(const frags_t &f, tile_state_t &t)
 {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) mma_row<BF, S>(f, t, i);
+    mma_some<BF, S>(f, t, 0, 16);
 }
 
 // Copies d0 .. d1-1 of the 17 copies of one stage: copy 2g + o (g < 8) is row group g of slab o
@@ -287,10 +286,17 @@ template <bool TBF, int D0, int D1> __device__ __forceinline__ void issue_copies
     const uint32_t boff = (stage & 1) * STAGE_BYTES;
     const int cs = stage - t.nbf;                      // index among the FP4 stages
     const uint32_t rp = TBF ? t.gpitch : t.pitch;      // row pitch of this stage's operands
+#ifdef ADAHOP_DBG_CONTIG_DMA
+    // timing experiment only: every wave streams private contiguous 8 KiB pieces (within the first 32 MiB of A)
+    const uint8_t *pa = t.ga + (int64_t)cs * 8192;
+    const uint8_t *pb = t.gb + (int64_t)cs * 8192;
+    const uint32_t v_even = threadIdx.x % 64 * 16, v_odd = v_even;
+#else
     const uint8_t *pa = TBF ? t.gga + (int64_t)stage * TKB : t.ga + (int64_t)cs * TKB;
     const uint8_t *pb = TBF ? t.ggb + (int64_t)stage * TKB : t.gb + (int64_t)cs * TKB;
     // row group g starts 8 g rows further: a wave-uniform term that goes into the base address
     const uint32_t v_even = t.lrow * rp + t.c_even, v_odd = t.lrow * rp + t.c_odd;
+#endif
 #pragma unroll
     for (int d = D0; d < D1; ++d) {
         if (d == 16) {
@@ -298,7 +304,11 @@ template <bool TBF, int D0, int D1> __device__ __forceinline__ void issue_copies
         } else {
             const int g = d >> 1;
             const uint32_t vo = (g & 1) ? v_odd : v_even;
+#ifdef ADAHOP_DBG_CONTIG_DMA
+            const int64_t goff = (int64_t)g * 1024;
+#else
             const int64_t goff = (int64_t)(8 * g) * rp;
+#endif
             if (d & 1)
                 dma16(pb + goff, vo, t.lds_w + boff + TM * TKB + g * 1024);
             else
@@ -315,12 +325,33 @@ template <bool TBF, int D0, int D1> __device__ __forceinline__ void issue_copies
 #ifndef ADAHOP_SPREAD
 #define ADAHOP_SPREAD 3
 #endif
-constexpr int SPREAD = ADAHOP_SPREAD, NSLOT = 4 * SPREAD;
+#ifndef ADAHOP_SLOTS_PER_STEP
+#define ADAHOP_SLOTS_PER_STEP 16
+#endif
+constexpr int SPS = ADAHOP_SLOTS_PER_STEP;      // copy slots per matrix-core step: one after every 16 / SPS instructions
+constexpr int SPREAD = ADAHOP_SPREAD, NSLOT = SPS * SPREAD;
 constexpr int slot_lo(int k) { return 17 * k / NSLOT; }
 
 template <bool TBF, int K> __device__ __forceinline__ void issue_slot(const tile_state_t &t, int stage)
 {
     if constexpr (K < NSLOT) issue_copies<TBF, slot_lo(K), slot_lo(K + 1)>(t, stage);
+}
+
+// The 16 matrix-core instructions of step S, with copy slots SLOT0 .. SLOT0 + SPS - 1 of stage
+// `which` spread between them (COND: whether that stage exists).
+template <bool BF, int S, bool COND, bool TBF, int SLOT0, int U = 0>
+__device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t, int which)
+{
+    constexpr int PER = 16 / SPS;
+    if constexpr (U < SPS) {
+        mma_some<BF, S>(f, t, U * PER, (U + 1) * PER);
+        ADAHOP_PIN();
+        if constexpr (COND) {
+            issue_slot<TBF, SLOT0 + U>(t, which);
+            ADAHOP_PIN();
+        }
+        mma_and_copies<BF, S, COND, TBF, SLOT0, U + 1>(f, t, which);
+    }
 }
 
 // One pipeline stage: four matrix-core steps on the fragments of buffer stage % 2.
@@ -340,23 +371,10 @@ __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, 
     const uint8_t *sn = smem + ((stage + 1) & 1) * STAGE_BYTES;
     read_frags(st, t, 1, t.f1);
     ADAHOP_PIN();
-#define ADAHOP_ROW(S, F, I, SLOT, COND, TBF, WHICH)     \
-    mma_row<BF, S>(F, t, I);                             \
-    ADAHOP_PIN();                                        \
-    if constexpr (COND) {                                \
-        issue_slot<TBF, SLOT>(t, WHICH);                 \
-        ADAHOP_PIN();                                    \
-    }
-    ADAHOP_ROW(0, t.f0, 0, 4, HAS_NEXT, BF1, stage + 1)
-    ADAHOP_ROW(0, t.f0, 1, 5, HAS_NEXT, BF1, stage + 1)
-    ADAHOP_ROW(0, t.f0, 2, 6, HAS_NEXT, BF1, stage + 1)
-    ADAHOP_ROW(0, t.f0, 3, 7, HAS_NEXT, BF1, stage + 1)
+    mma_and_copies<BF, 0, HAS_NEXT, BF1, SPS>(t.f0, t, stage + 1);
     read_frags(st, t, 2, t.f0);
     ADAHOP_PIN();
-    ADAHOP_ROW(1, t.f1, 0, 8, HAS_NEXT, BF1, stage + 1)
-    ADAHOP_ROW(1, t.f1, 1, 9, HAS_NEXT, BF1, stage + 1)
-    ADAHOP_ROW(1, t.f1, 2, 10, HAS_NEXT, BF1, stage + 1)
-    ADAHOP_ROW(1, t.f1, 3, 11, HAS_NEXT, BF1, stage + 1)
+    mma_and_copies<BF, 1, HAS_NEXT, BF1, 2 * SPS>(t.f1, t, stage + 1);
     read_frags(st, t, 3, t.f1);
     ADAHOP_PIN();
     mma_step<BF, 2>(t.f0, t);
@@ -364,6 +382,8 @@ __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, 
     if constexpr (HAS_NEXT) {
 #ifdef ADAHOP_DBG_NO_VMWAIT
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#elif defined(ADAHOP_DBG_VMLAG)
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)" ::"n"(ADAHOP_DBG_VMLAG) : "memory");
 #else
         asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)" ::: "memory"); // next stage landed; my reads done
 #endif
@@ -374,11 +394,7 @@ __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, 
         if constexpr (!BF1) read_scales(sn, t, t.scn);
         ADAHOP_PIN();
     }
-    ADAHOP_ROW(3, t.f1, 0, 0, ISSUE, BF2, stage + 2)
-    ADAHOP_ROW(3, t.f1, 1, 1, ISSUE, BF2, stage + 2)
-    ADAHOP_ROW(3, t.f1, 2, 2, ISSUE, BF2, stage + 2)
-    ADAHOP_ROW(3, t.f1, 3, 3, ISSUE, BF2, stage + 2)
-#undef ADAHOP_ROW
+    mma_and_copies<BF, 3, ISSUE, BF2, 0>(t.f1, t, stage + 2);
     if constexpr (HAS_NEXT && !BF1) t.sc = t.scn;
 }
 
@@ -428,8 +444,13 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
         t.pitch = (uint32_t)(K >> 1);
         t.gpitch = (uint32_t)kpad * 2;
         const int64_t pitch = t.pitch, gpitch = t.gpitch;
+#ifdef ADAHOP_DBG_CONTIG_DMA
+        t.ga = uniform_ptr(a_codes + ((int64_t)(blockIdx.x % 16) * 4 + w) * (1 << 19));
+        t.gb = uniform_ptr(a_codes + ((int64_t)(blockIdx.x % 16) * 4 + w) * (1 << 19) + (1 << 18));
+#else
         t.ga = uniform_ptr(a_codes + (m0 + w * 64) * (int64_t)pitch);
         t.gb = uniform_ptr(b_codes + (n0 + w * 64) * (int64_t)pitch);
+#endif
         t.gga = uniform_ptr(reinterpret_cast<const uint8_t *>(Ag) + (m0 + w * 64) * (int64_t)gpitch);
         t.ggb = uniform_ptr(reinterpret_cast<const uint8_t *>(Bg) + (n0 + w * 64) * (int64_t)gpitch);
         // scales (stage-major): waves 0,1 move the two 1 KiB halves of the A slab's scales, waves 2,3 of B's
@@ -466,7 +487,7 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     // prologue: stage 0 copied and landed, the first slots of stage 1 under way (the rest of stage 1
     // follows during stage 0, as in every later stage), first fragments of stage 0 read.
     // Host side guarantees at least two FP4 stages.
-    constexpr int PRO = slot_lo(4); // copies of the four slots that fall into the step before a stage
+    constexpr int PRO = slot_lo(SPS); // copies of the four slots that fall into the step before a stage
     if constexpr (OEK) {
         issue_copies<true, 0, 17>(t, 0);
         if (t.nbf > 1)
@@ -592,7 +613,10 @@ int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, cons
         int rc = check_launch();
         if (rc != ADAHOP_OK) return rc;
         const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
-        const int group_m = tiles_m < 8 ? tiles_m : 8;
+#ifndef ADAHOP_GROUP_M
+#define ADAHOP_GROUP_M 8
+#endif
+        const int group_m = tiles_m < ADAHOP_GROUP_M ? tiles_m : ADAHOP_GROUP_M;
         const dim3 grid((unsigned)(tiles_m * tiles_n));
         if (kpad > 0)
             hipLaunchKernelGGL((k_gemm_mx_tile256<true>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
