@@ -241,6 +241,18 @@ __device__ __forceinline__ void read_frags(const uint8_t *buf, const tile_state_
     }
 }
 
+// Item 0..3: A fragment of tile row item; 4..7: B fragment of tile column item - 4.
+__device__ __forceinline__ void read_frag_item(const uint8_t *buf, const tile_state_t &t, int s, int item, frags_t &f)
+{
+#ifdef ADAHOP_DBG_NO_LDSREAD
+    return;
+#endif
+    if (item < 4)
+        f.a[item] = *reinterpret_cast<const uint4 *>(buf + t.a_row + item * 32 * TKB + t.off[s]);
+    else
+        f.b[item - 4] = *reinterpret_cast<const uint4 *>(buf + t.b_row + (item - 4) * 32 * TKB + t.off[s]);
+}
+
 __device__ __forceinline__ void read_scales(const uint8_t *buf, const tile_state_t &t, scales_t &sc)
 {
 #pragma unroll
@@ -337,20 +349,35 @@ template <bool TBF, int K> __device__ __forceinline__ void issue_slot(const tile
     if constexpr (K < NSLOT) issue_copies<TBF, slot_lo(K), slot_lo(K + 1)>(t, stage);
 }
 
-// The 16 matrix-core instructions of step S, with copy slots SLOT0 .. SLOT0 + SPS - 1 of stage
-// `which` spread between them (COND: whether that stage exists).
-template <bool BF, int S, bool COND, bool TBF, int SLOT0, int U = 0>
-__device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t, int which)
+// The 16 matrix-core instructions of step S on fragments f, and between them
+//   - the copy slots SLOT0 .. SLOT0 + SPS - 1 of stage `which` (COND: whether that stage exists);
+//   - the eight fragment reads of step RS of buffer rbuf into rf (RS < 0: none), one at a time behind
+//     the first instructions, and after them the scales of that buffer (RSC).
+// A wave issues in order, so a burst of LDS or copy instructions keeps it from feeding the matrix
+// cores; single instructions fit into the shadow of the matrix-core instruction before them.
+template <bool BF, int S, bool COND, bool TBF, int SLOT0, int RS, bool RSC, int U = 0>
+__device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t, int which, const uint8_t *rbuf, frags_t &rf)
 {
-    constexpr int PER = 16 / SPS;
+    constexpr int PER = 16 / SPS;                 // matrix-core instructions per unit
+    constexpr int RUNITS = SPS < 8 ? SPS : 8;     // units that carry fragment reads
+    constexpr int RPU = 8 / RUNITS;               // fragment reads per such unit
     if constexpr (U < SPS) {
         mma_some<BF, S>(f, t, U * PER, (U + 1) * PER);
         ADAHOP_PIN();
+        if constexpr (RS >= 0 && U < RUNITS) {
+#pragma unroll
+            for (int r = 0; r < RPU; ++r) read_frag_item(rbuf, t, RS, U * RPU + r, rf);
+            ADAHOP_PIN();
+        }
+        if constexpr (RSC && U == RUNITS) {
+            read_scales(rbuf, t, t.scn);
+            ADAHOP_PIN();
+        }
         if constexpr (COND) {
             issue_slot<TBF, SLOT0 + U>(t, which);
             ADAHOP_PIN();
         }
-        mma_and_copies<BF, S, COND, TBF, SLOT0, U + 1>(f, t, which);
+        mma_and_copies<BF, S, COND, TBF, SLOT0, RS, RSC, U + 1>(f, t, which, rbuf, rf);
     }
 }
 
@@ -369,16 +396,10 @@ __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, 
 {
     const uint8_t *st = smem + (stage & 1) * STAGE_BYTES;
     const uint8_t *sn = smem + ((stage + 1) & 1) * STAGE_BYTES;
-    read_frags(st, t, 1, t.f1);
-    ADAHOP_PIN();
-    mma_and_copies<BF, 0, HAS_NEXT, BF1, SPS>(t.f0, t, stage + 1);
-    read_frags(st, t, 2, t.f0);
-    ADAHOP_PIN();
-    mma_and_copies<BF, 1, HAS_NEXT, BF1, 2 * SPS>(t.f1, t, stage + 1);
-    read_frags(st, t, 3, t.f1);
-    ADAHOP_PIN();
-    mma_step<BF, 2>(t.f0, t);
-    ADAHOP_PIN();
+    // step j computes on the fragments read during step j - 1 and reads those of step j + 1
+    mma_and_copies<BF, 0, HAS_NEXT, BF1, SPS, 1, false>(t.f0, t, stage + 1, st, t.f1);
+    mma_and_copies<BF, 1, HAS_NEXT, BF1, 2 * SPS, 2, false>(t.f1, t, stage + 1, st, t.f0);
+    mma_and_copies<BF, 2, false, false, 0, 3, false>(t.f0, t, 0, st, t.f1);
     if constexpr (HAS_NEXT) {
 #ifdef ADAHOP_DBG_NO_VMWAIT
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -390,11 +411,8 @@ __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, 
 #ifndef ADAHOP_DBG_NO_BARRIER
         __syncthreads();
 #endif
-        read_frags(sn, t, 0, t.f0);
-        if constexpr (!BF1) read_scales(sn, t, t.scn);
-        ADAHOP_PIN();
     }
-    mma_and_copies<BF, 3, ISSUE, BF2, 0>(t.f1, t, stage + 2);
+    mma_and_copies<BF, 3, ISSUE, BF2, 0, (HAS_NEXT ? 0 : -1), (HAS_NEXT && !BF1)>(t.f1, t, stage + 2, sn, t.f0);
     if constexpr (HAS_NEXT && !BF1) t.sc = t.scn;
 }
 
