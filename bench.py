@@ -22,7 +22,7 @@ BF16_PEAK_TFLOPS = 2516.0
 # HBM bytes per launch of the FP4 GEMM kernel, by (M, N, K): rocprofv3 FETCH_SIZE + WRITE_SIZE (KiB per
 # dispatch), each scaled by what the same counter reads for a plain 1 GiB copy (--copy-calibration);
 # the runs and the scaling are in profiles/gemm_mx_16384x28672x8192_counters.txt.
-GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 5.41e9}
+GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 4.89e9}
 
 
 def parse():

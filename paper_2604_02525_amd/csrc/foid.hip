@@ -36,18 +36,22 @@ __global__ __launch_bounds__(256) void k_foid_scores(const uint16_t *__restrict_
 
 constexpr int TOPK_THREADS = 1024, TOPK_WAVES = TOPK_THREADS / 64;
 
-// hist[bin] += 1 for every lane with valid set, one LDS atomic per distinct bin of the wave: the
-// scores of ordinary rows share their high bytes, and per-key atomics on one bin would serialise.
+// hist[bin] += 1 for every lane with valid set.  The scores of ordinary rows share their high bytes,
+// and per-key atomics on one bin would serialise; so the most frequent bins of the wave are added with
+// one atomic each (up to two rounds), and whatever is left -- then spread over many bins -- with
+// plain per-lane atomics.
 __device__ __forceinline__ void wave_histogram(uint32_t *hist, bool valid, uint32_t bin)
 {
     uint64_t todo = __ballot(valid);
-    while (todo) {
+#pragma unroll 1
+    for (int round = 0; round < 2 && todo; ++round) {
         const int leader = __ffsll((long long)todo) - 1;
         const uint32_t b = __builtin_amdgcn_readlane(bin, leader);
         const uint64_t same = __ballot(valid && bin == b);
         if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[b], (uint32_t)__popcll(same));
         todo &= ~same;
     }
+    if ((todo >> (threadIdx.x & 63)) & 1) atomicAdd(&hist[bin], 1u);
 }
 
 __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__ scores, int dim, int k,
@@ -76,15 +80,37 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__
             wave_histogram(hist, i < dim && (key & pmask) == prefix, (key >> shift) & 255u);
         }
         __syncthreads();
-        if (tid == 0) {
-            uint32_t cum = 0;
-            int b = 255;
-            for (; b > 0; --b) {
-                if (cum + hist[b] >= remaining) break;
-                cum += hist[b];
+        // The digit of the k-th largest key: the highest bin b with (keys in bins above b) + hist[b] >=
+        // remaining.  Wave 0 scans the 256 bins in parallel: lane l owns bins 255 - 4l .. 252 - 4l.
+        if (w == 0) {
+            uint32_t c[4], mine = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                c[j] = hist[255 - 4 * lane - j];
+                mine += c[j];
             }
-            sh_prefix = prefix | ((uint32_t)b << shift);
-            sh_remaining = remaining - cum;
+            uint32_t incl = mine; // inclusive scan over lanes = over descending bins
+#pragma unroll
+            for (int d = 1; d < 64; d *= 2) {
+                const uint32_t up = __shfl_up(incl, d);
+                if (lane >= d) incl += up;
+            }
+            uint32_t cum = incl - mine; // keys in bins above this lane's
+            int found = -1;
+            uint32_t cum_at = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (found < 0 && cum + c[j] >= remaining) {
+                    found = 255 - 4 * lane - j;
+                    cum_at = cum;
+                }
+                cum += c[j];
+            }
+            const uint64_t hit = __ballot(found >= 0);
+            if (hit && lane == __ffsll((long long)hit) - 1) {
+                sh_prefix = prefix | ((uint32_t)found << shift);
+                sh_remaining = remaining - cum_at;
+            }
         }
         __syncthreads();
         prefix = sh_prefix;
