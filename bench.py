@@ -30,7 +30,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=10)
     p.add_argument("--warmup", type=int, default=3)
-    p.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg4-up", "cfg1", "cfg0"])
+    p.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg4-up", "cfg1", "cfg0", "paper-table3"])
     p.add_argument("--k-pct", type=float, default=1.0, help="extraction count as %% of the extracted dim (cfg4)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the k-sweep / BF16 / per-stage extras")
@@ -47,6 +47,9 @@ def build_workload(name, k_pct):
         return "configs[0]: M=N=K=256, IHT block 32", I.config0()
     if name == "cfg1":
         return "configs[1]: fwd X[8192,2048] W[8192,2048], IHT block 128", I.config1()
+    if name == "paper-table3":
+        return ("the two GEMMs of the paper's kernel latency table: (14336,4096,32768) and (4096,4096,32768) weight "
+                "gradients, IHT block 32, OE-col with rank 64"), I.paper_latency_shapes()
     which = ("up",) if name == "cfg4-up" else ("up", "down")
     # fwd: activation channel outliers are K-channels of A; dgrad: gradient token rows are rows of A;
     # wgrad: gradient token rows are K-channels of A = G_Y^T.

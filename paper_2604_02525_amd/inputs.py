@@ -153,3 +153,21 @@ def config4(which=("up", "down"), strategies=(IHT, IHT, IHT), k_pct=0.0, T=16384
     if "down" in which:
         out += linear_layer_gemms("cfg4.down", T, ffn, hidden, 4010, 256, strategies, k_pct)
     return out
+
+
+def paper_latency_shapes(which=("mlp", "attn"), T=32768, iht_block=32, k=64):
+    """The two GEMMs of the paper's kernel latency table (Table 3, right; App. F): (m, n, k) =
+    (14336, 4096, 32768) "MLP projection" and (4096, 4096, 32768) "attention projection" of Llama3.1-8B at
+    8 x 4096 tokens, i.e. the weight-gradient products G_W = G_Y^T X (Eq. 3) with the tokens as the
+    contraction axis, both operands stored token-major.  Same stand-in tensors as the configs: G_Y with
+    0.5 % token rows x100, X with 16 channels x50.  The paper's settings: IHT block 32, extraction rank 64;
+    the amplified channels of X are columns of B, which the paper's table routes to OE-Right (OE-col).
+    """
+    out = []
+    for name, d_out, seed in (("mlp", 14336, 5000), ("attn", 4096, 5010)):
+        if name not in which:
+            continue
+        X = matrix(T, 4096, 1.0, seed, col_outliers=(16, 50.0, 50.0))
+        G = matrix(T, d_out, 1e-3, seed + 2, row_outliers=(pct(0.5, T), 100.0, 100.0))
+        out.append(Gemm(f"table3.{name}.wgrad", Operand(G, False), Operand(X, False), IHT_OE_COL, iht_block, k))
+    return out

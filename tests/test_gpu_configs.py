@@ -85,3 +85,12 @@ def test_config4_k_sweep_error_is_non_increasing(ah):
         say("  k-sweep error vs exact:", [f"{e:.3e}" for e in errs])
         assert all(b <= a * 1.02 for a, b in zip(errs, errs[1:]))
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("which", ["mlp", "attn"])
+def test_paper_latency_table_shapes(ah, which):
+    """The two weight-gradient GEMMs of the paper's kernel latency table (Table 3, right): K = 32768 tokens,
+    both operands token-major, IHT block 32 and extraction rank 64 as in App. F."""
+    for g in inputs.paper_latency_shapes(which=(which,)):
+        check(ah, g)
+    torch.cuda.empty_cache()
