@@ -23,13 +23,39 @@ __global__ __launch_bounds__(256) void k_foid_scores(const uint16_t *__restrict_
     const bool along_contig = (axis == 0) == (k_contig != 0);
     const int64_t base = along_contig ? i * ld : i;
     const int64_t step = along_contig ? 1 : ld;
-    float s = 0.0f;
-    for (int j = 0; j < L; ++j) s = s + bf16_one(x[base + j * step]);
-    const float mean = s * inv_L;
-    float v = 0.0f;
-    for (int j = 0; j < L; ++j) {
-        const float d = bf16_one(x[base + j * step]) - mean;
-        v = __builtin_fmaf(d, d, v);
+    float s = 0.0f, v = 0.0f;
+    if (L == 64) {
+        // all 64 samples first (independent loads, in flight together), then the fixed-order arithmetic
+        float e[64];
+        if (along_contig) {
+            const uint4 *p = reinterpret_cast<const uint4 *>(x + base); // ld % 8 == 0 and 16-byte aligned data
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint4 u = p[q];
+                e[8 * q + 0] = bf16_lo(u.x); e[8 * q + 1] = bf16_hi(u.x);
+                e[8 * q + 2] = bf16_lo(u.y); e[8 * q + 3] = bf16_hi(u.y);
+                e[8 * q + 4] = bf16_lo(u.z); e[8 * q + 5] = bf16_hi(u.z);
+                e[8 * q + 6] = bf16_lo(u.w); e[8 * q + 7] = bf16_hi(u.w);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 64; ++j) e[j] = bf16_one(x[base + j * step]);
+        }
+#pragma unroll
+        for (int j = 0; j < 64; ++j) s = s + e[j];
+        const float mean = s * inv_L;
+#pragma unroll
+        for (int j = 0; j < 64; ++j) {
+            const float d = e[j] - mean;
+            v = __builtin_fmaf(d, d, v);
+        }
+    } else {
+        for (int j = 0; j < L; ++j) s = s + bf16_one(x[base + j * step]);
+        const float mean = s * inv_L;
+        for (int j = 0; j < L; ++j) {
+            const float d = bf16_one(x[base + j * step]) - mean;
+            v = __builtin_fmaf(d, d, v);
+        }
     }
     scores[i] = v;
 }

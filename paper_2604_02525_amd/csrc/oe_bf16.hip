@@ -232,12 +232,43 @@ __global__ __launch_bounds__(256) void k_gather_k(const uint16_t *__restrict__ x
     out[o * kpad + t] = v;
 }
 
+// The same for a K-strided operand (x stored [K, outer]): 64 channels x 64 rows per workgroup through
+// LDS, so that both the reads (along the rows of one channel) and the writes (along the channels of
+// one row) are whole 128-byte segments.
+__global__ __launch_bounds__(256) void k_gather_k_strided(const uint16_t *__restrict__ x, int64_t ld, int64_t outer,
+                                                          const int32_t *__restrict__ idx, int k, int kpad,
+                                                          uint16_t *__restrict__ out)
+{
+    __shared__ uint16_t tile[64][66];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t o0 = (int64_t)blockIdx.x * 64;
+    const int t0 = blockIdx.y * 64;
+#pragma unroll 4
+    for (int r = 0; r < 16; ++r) {
+        const int t = t0 + ty * 16 + r;
+        const int64_t o = o0 + tx;
+        tile[ty * 16 + r][tx] = (t < k && o < outer) ? x[(int64_t)idx[t] * ld + o] : (uint16_t)0;
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int r = 0; r < 16; ++r) {
+        const int64_t o = o0 + ty * 16 + r;
+        if (o < outer) out[o * kpad + t0 + tx] = tile[tx][ty * 16 + r];
+    }
+}
+
 } // namespace
 
 int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kpad, uint16_t *out, hipStream_t st)
 {
     const int64_t n = x.outer * kpad;
     if (n == 0) return ADAHOP_OK;
+    if (!x.k_contig && kpad % 64 == 0) {
+        const dim3 grid((unsigned)ceil_div(x.outer, 64), (unsigned)(kpad / 64));
+        hipLaunchKernelGGL(k_gather_k_strided, grid, dim3(256), 0, st, static_cast<const uint16_t *>(x.data), x.ld,
+                           x.outer, idx, k, kpad, out);
+        return check_launch();
+    }
     hipLaunchKernelGGL(k_gather_k, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st,
                        static_cast<const uint16_t *>(x.data), x.ld, x.k_contig, x.outer, idx, k, kpad, out);
     return check_launch();
