@@ -158,6 +158,38 @@ int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, ad
                         const int32_t *idx, int k, float *C, int64_t ldc, void *gather_ws,
                         size_t gather_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Outlier-pattern detection of one tensor and the pattern-pair -> strategy table (paper Sec. 4.1,
+ * 4.2, App. A) -- what the paper's 30-step calibration evaluates per tensor and per step; the
+ * majority vote over steps is left to the caller.
+ *
+ * For the operand in its logical [outer, K] shape: v_outer[o] = variance of x[o, :], v_k[kk] =
+ * variance of x[:, kk] (population variances, fp64), CV = std(v) / (mean(v) + 1e-12) for each vector,
+ * CV^_outer = CV_outer / sqrt(2 / (K - 1)), CV^_k = CV_k / sqrt(2 / (outer - 1)), and
+ *   ADAHOP_PATTERN_OUTER if CV^_outer / CV^_k > tau   (whole rows of A / whole columns of B stand out:
+ *                                                      the paper's Row-wise for A, Column-wise for B)
+ *   ADAHOP_PATTERN_K     if CV^_k / CV^_outer > tau   (whole K-channels: Column-wise for A, Row-wise for B)
+ *   ADAHOP_PATTERN_NONE  otherwise.                    A ratio with a zero denominator counts as
+ *                                                      infinite if its numerator is positive, else 0.
+ * pattern_out: one device int32; stats_out: four device doubles (CV_outer, CV_k, CV^_outer, CV^_k).
+ * Requires outer >= 2 and K >= 32.  workspace: adahop_detect_pattern_workspace_bytes(x) bytes, 256-byte
+ * aligned, contents undefined on return.
+ * ------------------------------------------------------------------------------------------- */
+typedef enum { ADAHOP_PATTERN_NONE = 0, ADAHOP_PATTERN_OUTER = 1, ADAHOP_PATTERN_K = 2 } adahop_pattern_t;
+
+size_t adahop_detect_pattern_workspace_bytes(const adahop_operand_t *x);
+int adahop_detect_pattern(const adahop_operand_t *x, double tau, int32_t *pattern_out, double *stats_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Strategy for the product of A and B from their patterns (Sec. 4.2; host-side, no GPU work):
+ *   B outer-wise (the paper's RC, NC, CC)              -> ADAHOP_IHT_OE_COL  (OE-Right)
+ *   else A outer-wise (RN; RR by the same argument)    -> ADAHOP_IHT_OE_ROW  (OE-Left)
+ *   else (CN, NN, CR; NR)                              -> ADAHOP_IHT
+ * level 2 (AdaHOP-Lv2) computes the CC pair (A K-wise, B outer-wise) fully in BF16: *full_bf16 is set
+ * to 1 and the return value is ADAHOP_NONE; in every other case *full_bf16 = 0.  level must be 1 or 2;
+ * returns ADAHOP_E_INVALID_ARG (as a negative value) on bad arguments. */
+int adahop_select_strategy(adahop_pattern_t pattern_a, adahop_pattern_t pattern_b, int level, int *full_bf16);
+
 /* Measurement aid (not part of the method): launches `workgroups` x 4 waves that each run
  * iters x 16 block-scaled FP4 matrix-core instructions (32x32x64, 131072 flop each) on register
  * operands only -- constant bits, or pseudo-random bits if random_operands != 0 -- so that a caller

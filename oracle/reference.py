@@ -213,3 +213,56 @@ def adahop_gemm(a_bits, a_k_contig, b_bits, b_k_contig, strategy, iht_block, k=0
         else:                             # C += A[:, S] B[S, :]
             Cm += bf16_gemm(a_bits, a_k_contig, b_bits, b_k_contig, ksel=sel, rows=rows_a, cols=cols_a)
     return dict(C=Cm, a_codes=a_codes, a_scales=a_scales, b_codes=b_codes, b_scales=b_scales, idx=sel)
+
+
+# ------------------------------------------------------------------------------------------------
+# Outlier-pattern detection and strategy table (paper Sec. 4.1, 4.2, App. A)
+# ------------------------------------------------------------------------------------------------
+PATTERN_NONE, PATTERN_OUTER, PATTERN_K = range(3)
+
+
+def _ratio(a, b):
+    if b > 0.0:
+        return a / b
+    return float("inf") if a > 0.0 else 0.0
+
+
+def detect_pattern(bits, k_contig, tau=2.0, eps=1e-12):
+    """App. A on the operand in its logical [outer, K] shape, in float64 with numpy's var / std / mean
+    (population forms): the variance of every outer index and of every K index, the coefficient of
+    variation of each variance vector, each divided by its IID value sqrt(2 / (samples - 1)), and the
+    class from the ratio of the two against tau.  "Outer-wise" is the paper's Row-wise for A (m x k)
+    and Column-wise for B (k x n); "K-wise" is Column-wise for A and Row-wise for B.
+    Returns (pattern, [CV_outer, CV_k, CVhat_outer, CVhat_k])."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    T = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    if not k_contig:
+        T = T.T
+    outer, K = T.shape
+    v_outer = T.var(axis=1)
+    v_k = T.var(axis=0)
+    cv_outer = v_outer.std() / (v_outer.mean() + eps)
+    cv_k = v_k.std() / (v_k.mean() + eps)
+    hat_outer = cv_outer / np.sqrt(2.0 / (K - 1))
+    hat_k = cv_k / np.sqrt(2.0 / (outer - 1))
+    if _ratio(hat_outer, hat_k) > tau:
+        p = PATTERN_OUTER
+    elif _ratio(hat_k, hat_outer) > tau:
+        p = PATTERN_K
+    else:
+        p = PATTERN_NONE
+    return p, np.array([cv_outer, cv_k, hat_outer, hat_k])
+
+
+def select_strategy(pattern_a, pattern_b, level=1):
+    """Sec. 4.2: pairs whose outliers lie along K in both operands (CN, NN, CR) take IHT alone; outlier
+    rows of A (RN) take OE-Left; outlier columns of B (RC, NC, CC) take OE-Right; AdaHOP-Lv2 computes CC
+    fully in BF16.  The pairs the section does not list follow the same argument (RR like RN, NR like NN).
+    Returns (strategy, full_bf16)."""
+    if pattern_b == PATTERN_OUTER:
+        if level == 2 and pattern_a == PATTERN_K:
+            return NONE, True
+        return IHT_OE_COL, False
+    if pattern_a == PATTERN_OUTER:
+        return IHT_OE_ROW, False
+    return IHT, False

@@ -15,11 +15,13 @@ LIB_PATH = os.path.join(HERE, "libadahop.so")
 
 ADAHOP_NONE, ADAHOP_IHT, ADAHOP_IHT_OE_ROW, ADAHOP_IHT_OE_COL, ADAHOP_IHT_OE_K = range(5)
 ADAHOP_OK, ADAHOP_E_INVALID_ARG, ADAHOP_E_WORKSPACE, ADAHOP_E_HIP = 0, -1, -2, -3
+ADAHOP_PATTERN_NONE, ADAHOP_PATTERN_OUTER, ADAHOP_PATTERN_K = range(3)
 
 EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_gemm_mx",
            "adahop_gemm_mx_workspace_bytes",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
-           "adahop_oe_gemm_bf16", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
+           "adahop_oe_gemm_bf16", "adahop_detect_pattern_workspace_bytes", "adahop_detect_pattern",
+           "adahop_select_strategy", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
            "adahop_abi_version"]
 
 
@@ -67,6 +69,10 @@ def lib():
         L.adahop_oe_gather_bytes.argtypes = [I64, I64, I64, I, I]
         L.adahop_oe_gather_bytes.restype = SZ
         L.adahop_oe_gemm_bf16.argtypes = [OP, OP, I, P, I, P, I64, P, SZ, P]
+        L.adahop_detect_pattern_workspace_bytes.argtypes = [OP]
+        L.adahop_detect_pattern_workspace_bytes.restype = SZ
+        L.adahop_detect_pattern.argtypes = [OP, C.c_double, P, P, P, SZ, P]
+        L.adahop_select_strategy.argtypes = [I, I, I, C.POINTER(C.c_int)]
         L.adahop_probe_mfma_rate.argtypes = [I, I, I, P, P]
         L.adahop_status_string.restype = C.c_char_p
         L.adahop_status_string.argtypes = [I]
@@ -217,3 +223,25 @@ def adahop_probe_mfma_rate(random_operands, workgroups, iters, sink, stream=None
     _check(lib().adahop_probe_mfma_rate(int(bool(random_operands)), workgroups, iters, _ptr(sink), _stream(stream)),
            "adahop_probe_mfma_rate")
     return 2.0 * 65536 * 16 * iters * 4 * workgroups
+
+
+def adahop_detect_pattern(x, tau=2.0, workspace=None, stream=None):
+    """Outlier pattern of one operand: returns (pattern int32[1], stats float64[4]) device tensors."""
+    dev = x.tensor.device
+    need = int(lib().adahop_detect_pattern_workspace_bytes(C.byref(x.c())))
+    if workspace is None:
+        workspace = _u8((max(need, 256),), dev)
+    pattern = torch.empty(1, dtype=torch.int32, device=dev)
+    stats = torch.empty(4, dtype=torch.float64, device=dev)
+    _check(lib().adahop_detect_pattern(C.byref(x.c()), float(tau), _ptr(pattern), _ptr(stats), _ptr(workspace),
+                                       workspace.numel(), _stream(stream)), "adahop_detect_pattern")
+    return pattern, stats
+
+
+def adahop_select_strategy(pattern_a, pattern_b, level=1):
+    """(strategy, full_bf16) for a product from the patterns of its operands (host-side table)."""
+    flag = C.c_int(0)
+    s = lib().adahop_select_strategy(int(pattern_a), int(pattern_b), int(level), C.byref(flag))
+    if s < 0:
+        raise AdahopError(s, "adahop_select_strategy")
+    return s, bool(flag.value)

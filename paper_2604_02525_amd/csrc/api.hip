@@ -187,6 +187,39 @@ int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, ad
     return launch_oe_k_accumulate(A->outer, B->outer, Ag, Bg, kpad, C, ldc, st);
 }
 
+size_t adahop_detect_pattern_workspace_bytes(const adahop_operand_t *x)
+{
+    if (validate_operand(x) != ADAHOP_OK || x->outer < 2) return 0;
+    return pattern_workspace_bytes(*x);
+}
+
+int adahop_detect_pattern(const adahop_operand_t *x, double tau, int32_t *pattern_out, double *stats_out,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = validate_operand(x);
+    if (rc != ADAHOP_OK) return rc;
+    if (x->outer < 2 || !(tau > 0.0) || !pattern_out || !stats_out || !aligned(stats_out, 8) || !aligned(pattern_out, 4))
+        return ADAHOP_E_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < pattern_workspace_bytes(*x)) return ADAHOP_E_WORKSPACE;
+    return launch_detect_pattern(*x, tau, 1e-12, pattern_out, stats_out, workspace, static_cast<hipStream_t>(stream));
+}
+
+int adahop_select_strategy(adahop_pattern_t pattern_a, adahop_pattern_t pattern_b, int level, int *full_bf16)
+{
+    auto ok = [](int p) { return p == ADAHOP_PATTERN_NONE || p == ADAHOP_PATTERN_OUTER || p == ADAHOP_PATTERN_K; };
+    if (!ok(pattern_a) || !ok(pattern_b) || (level != 1 && level != 2) || !full_bf16) return ADAHOP_E_INVALID_ARG;
+    *full_bf16 = 0;
+    if (pattern_b == ADAHOP_PATTERN_OUTER) {
+        if (level == 2 && pattern_a == ADAHOP_PATTERN_K) {
+            *full_bf16 = 1;
+            return ADAHOP_NONE;
+        }
+        return ADAHOP_IHT_OE_COL;
+    }
+    if (pattern_a == ADAHOP_PATTERN_OUTER) return ADAHOP_IHT_OE_ROW;
+    return ADAHOP_IHT;
+}
+
 int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, int64_t ldc,
                 adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
                 void *workspace, size_t workspace_bytes, void *stream)

@@ -44,6 +44,10 @@ int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int k
 int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint16_t *Bg, int kpad, float *C,
                            int64_t ldc, hipStream_t st);
 
+size_t pattern_workspace_bytes(const adahop_operand_t &x);
+int launch_detect_pattern(const adahop_operand_t &x, double tau, double eps, int32_t *pattern_out, double *stats_out,
+                          void *workspace, hipStream_t st);
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

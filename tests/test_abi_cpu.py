@@ -124,3 +124,34 @@ def test_status_strings():
     assert L.adahop_status_string(0) == b"ok"
     for s in (-1, -2, -3, -99):
         assert len(L.adahop_status_string(s)) > 3
+
+
+def test_pattern_argument_checks_and_strategy_table():
+    L = ah.lib()
+    x = op(64, 256)
+    need = L.adahop_detect_pattern_workspace_bytes(C.byref(x))
+    assert need > 0 and need % 256 == 0
+    f = lambda **kw: L.adahop_detect_pattern(C.byref(kw.get("x", x)), kw.get("tau", 2.0), kw.get("p", FAKE), kw.get("s", FAKE),
+                                             kw.get("ws", FAKE), kw.get("wsb", need), None)
+    assert f(x=op(1, 256)) == ah.ADAHOP_E_INVALID_ARG          # a variance vector needs two entries
+    assert f(tau=0.0) == ah.ADAHOP_E_INVALID_ARG
+    assert f(p=None) == ah.ADAHOP_E_INVALID_ARG
+    assert f(s=None) == ah.ADAHOP_E_INVALID_ARG
+    assert f(ws=None) == ah.ADAHOP_E_WORKSPACE
+    assert f(wsb=need - 1) == ah.ADAHOP_E_WORKSPACE
+    assert L.adahop_detect_pattern_workspace_bytes(C.byref(op(1, 256))) == 0
+    # Sec. 4.2, in operand-sense patterns (outer-wise = the paper's R for A and C for B)
+    N, O, K = ah.ADAHOP_PATTERN_NONE, ah.ADAHOP_PATTERN_OUTER, ah.ADAHOP_PATTERN_K
+    assert ah.adahop_select_strategy(K, N) == (ah.ADAHOP_IHT, False)          # CN
+    assert ah.adahop_select_strategy(N, N) == (ah.ADAHOP_IHT, False)          # NN
+    assert ah.adahop_select_strategy(K, K) == (ah.ADAHOP_IHT, False)          # CR
+    assert ah.adahop_select_strategy(O, N) == (ah.ADAHOP_IHT_OE_ROW, False)   # RN
+    assert ah.adahop_select_strategy(O, O) == (ah.ADAHOP_IHT_OE_COL, False)   # RC
+    assert ah.adahop_select_strategy(N, O) == (ah.ADAHOP_IHT_OE_COL, False)   # NC
+    assert ah.adahop_select_strategy(K, O) == (ah.ADAHOP_IHT_OE_COL, False)   # CC, level 1
+    assert ah.adahop_select_strategy(K, O, 2) == (ah.ADAHOP_NONE, True)       # CC, level 2: BF16
+    assert ah.adahop_select_strategy(N, O, 2) == (ah.ADAHOP_IHT_OE_COL, False)
+    with pytest.raises(ah.AdahopError):
+        ah.adahop_select_strategy(3, N)
+    with pytest.raises(ah.AdahopError):
+        ah.adahop_select_strategy(N, N, 3)

@@ -94,3 +94,26 @@ def test_paper_latency_table_shapes(ah, which):
     for g in inputs.paper_latency_shapes(which=(which,)):
         check(ah, g)
     torch.cuda.empty_cache()
+
+
+def test_patterns_and_strategy_selection_on_config_tensors(ah):
+    """Sec. 4.1-4.2 on the stand-in tensors at full size: patterns equal the oracle's, and the strategy table picks
+    what the paper reports for such tensors -- forward (activation channels x featureless weights: CN) -> IHT;
+    dgrad (gradient token rows x weights: RN) -> OE-Left; wgrad (G_Y^T x X: CC) -> OE-Right, or BF16 at level 2."""
+    want = {"fwd": (inputs.IHT, False), "dgrad": (inputs.IHT_OE_ROW, False), "wgrad": (inputs.IHT_OE_COL, False)}
+    for g in inputs.config3(linears=("o",)):
+        pats = []
+        for x in (g.A, g.B):
+            p, st = ah.adahop_detect_pattern(dev_op(ah, x))
+            torch.cuda.synchronize()
+            ref_p, ref_st = orc.detect_pattern(x.bits, x.k_contig)
+            say("pattern", g.name, "operand pattern", int(host(p)[0]), "normalised CVs", host(st)[2:])
+            assert int(host(p)[0]) == ref_p
+            assert np.allclose(host(st), ref_st, rtol=1e-9, atol=1e-12)
+            pats.append(ref_p)
+        kind = g.name.rsplit(".", 1)[1]
+        assert ah.adahop_select_strategy(pats[0], pats[1], 1) == want[kind], (g.name, pats)
+        assert orc.select_strategy(pats[0], pats[1], 1) == want[kind]
+        if kind == "wgrad":
+            assert ah.adahop_select_strategy(pats[0], pats[1], 2) == (inputs.NONE, True)
+    torch.cuda.empty_cache()

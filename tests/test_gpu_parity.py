@@ -308,3 +308,23 @@ def test_oe_gemm_bf16_standalone(ah, M, N, K, k_row, k_col, k_k):
             else:
                 want += orc.bf16_gemm(A.bits, a_kc, B.bits, b_kc, ksel=sel)
             assert rel_fro(host(C), want) < 1e-5
+
+
+# ----------------------------------------------------------------------------- pattern detection (App. A)
+
+@pytest.mark.parametrize("shape", [(600, 1056), (256, 512), (1030, 288)])
+@pytest.mark.parametrize("k_contig", [True, False])
+def test_detect_pattern_matches_oracle(ah, shape, k_contig):
+    """CV figures to 1e-9 relative and the class exactly, for plain, row-outlier and channel-outlier tensors in both
+    storage orders; sizes span several 256 x 512 blocks with ragged tails."""
+    outer, K = shape
+    for seed, kw in ((1, {}), (2, dict(row_outliers=(5, 100.0, 100.0))), (3, dict(col_outliers=(6, 50.0, 50.0)))):
+        logical = inputs.matrix(outer, K, 1.0, 9000 + seed, **kw)
+        arr, width = stored(logical, k_contig)
+        say("detect_pattern", shape, k_contig, kw)
+        x = ah.Operand(torch.from_numpy(arr.view(np.int16)).cuda()[:, :width], k_contig)
+        p, st = ah.adahop_detect_pattern(x)
+        torch.cuda.synchronize()
+        want_p, want_st = orc.detect_pattern(logical, True)
+        assert int(host(p)[0]) == want_p
+        assert np.allclose(host(st), want_st, rtol=1e-9, atol=1e-12), (host(st), want_st)

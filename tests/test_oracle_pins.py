@@ -478,3 +478,55 @@ def test_oe_row_error_non_increasing_in_rank():
         errs.append(np.linalg.norm(C - exact))
     assert errs[0] > errs[1] > errs[2] >= errs[3] * 0.999
     assert errs[2] < 0.2 * errs[0]
+
+
+# ----------------------------------------------------------------------------- pattern detection (App. A)
+
+def _paper_letters_to_patterns(pair):
+    """Paper letters (A is m x k, B is k x n) -> operand-sense patterns: for A, R = outer-wise and C = K-wise;
+    for B (passed as [n, k]), C = outer-wise and R = K-wise."""
+    a = {"R": orc.PATTERN_OUTER, "C": orc.PATTERN_K, "N": orc.PATTERN_NONE}[pair[0]]
+    b = {"C": orc.PATTERN_OUTER, "R": orc.PATTERN_K, "N": orc.PATTERN_NONE}[pair[1]]
+    return a, b
+
+
+def test_strategy_table_matches_the_papers_section():
+    names = {"IHT": (orc.IHT, False), "OE-LEFT": (orc.IHT_OE_ROW, False), "OE-RIGHT": (orc.IHT_OE_COL, False),
+             "BF16": (orc.NONE, True)}
+    rows = load_table(os.path.join(os.path.dirname(__file__), "golden", "strategy_table.txt"))
+    assert len(rows) == 13
+    for pair, level, want in rows:
+        a, b = _paper_letters_to_patterns(pair)
+        assert orc.select_strategy(a, b, int(level)) == names[want], (pair, level)
+
+
+def test_pattern_closed_form_rank_one():
+    """T[i, j] = a_i * s_j with s = +-1 alternating: every row has mean 0 and variance a_i^2 exactly, every
+    column has the same variance var(a) -> CV of the column variances is 0 and CV_row = std(a^2) / mean(a^2).
+    a = (1, 2, 1, 2, ...): a^2 in {1, 4}: mean 2.5, std 1.5 -> CV_row = 0.6 (up to the 1e-12 in the denominator)."""
+    m, n = 64, 128
+    a = np.where(np.arange(m) % 2 == 0, 1.0, 2.0)
+    s = np.where(np.arange(n) % 2 == 0, 1.0, -1.0)
+    T = bf16_bits(np.outer(a, s))
+    p, st = orc.detect_pattern(T, True)
+    assert abs(st[0] - 0.6) < 1e-9 and st[1] < 1e-12
+    assert abs(st[2] - 0.6 / np.sqrt(2.0 / (n - 1))) < 1e-8
+    assert p == orc.PATTERN_OUTER                       # a ratio with a zero denominator counts as infinite
+    # the same matrix stored transposed is the same logical operand
+    p2, st2 = orc.detect_pattern(np.ascontiguousarray(T.T), False)
+    assert p2 == p and np.allclose(st2, st, rtol=1e-12, atol=1e-15)
+    # and read as an [outer = n, K = m] operand the roles swap
+    p3, st3 = orc.detect_pattern(np.ascontiguousarray(T.T), True)
+    assert p3 == orc.PATTERN_K and abs(st3[1] - 0.6) < 1e-9
+
+
+def test_pattern_iid_gives_unit_normalised_cv_and_planted_outliers_are_found():
+    """App. A: for IID data both normalised CVs are about 1 (whatever the aspect ratio), hence class None;
+    amplified rows give Row-wise, amplified columns Column-wise."""
+    for rows, cols in ((512, 2048), (2048, 256)):
+        p, st = orc.detect_pattern(inputs.matrix(rows, cols, 1.0, 77), True)
+        assert p == orc.PATTERN_NONE and 0.8 < st[2] < 1.25 and 0.8 < st[3] < 1.25, st
+    p, _ = orc.detect_pattern(inputs.matrix(512, 1024, 1.0, 78, row_outliers=(5, 100.0, 100.0)), True)
+    assert p == orc.PATTERN_OUTER
+    p, _ = orc.detect_pattern(inputs.matrix(512, 1024, 1.0, 79, col_outliers=(8, 50.0, 50.0)), True)
+    assert p == orc.PATTERN_K
