@@ -106,8 +106,8 @@ int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_ou
  * codes / scales in the canonical layout above; codes 16-byte aligned, K % 32 == 0.
  * workspace: device scratch of at least adahop_gemm_mx_workspace_bytes(M, N, K) bytes, 256-byte
  * aligned (the kernel keeps a re-ordered copy of the scales there); contents undefined on return.
- * Shapes with M % 256 == 0, N % 256 == 0, K % 256 == 0 take the tiled, LDS-pipelined kernel; any
- * other shape takes a slower bounds-checked kernel with the same results.
+ * With K % 256 == 0 and K >= 512 the whole 256x256 tiles of C take the tiled, LDS-pipelined kernel
+ * and only the ragged edges a slower bounds-checked kernel; any other K takes the latter throughout.
  * ------------------------------------------------------------------------------------------- */
 size_t adahop_gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int adahop_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,

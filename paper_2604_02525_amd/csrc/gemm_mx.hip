@@ -607,47 +607,62 @@ int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, cons
                    const uint16_t *Bg, int kpad, void *workspace, hipStream_t st)
 {
     if (M == 0 || N == 0) return ADAHOP_OK;
-    const bool tiled = M % TM == 0 && N % TN == 0 && K % 256 == 0 && kpad % 64 == 0 && aligned(a_scales, 8) &&
-                       aligned(b_scales, 8) && (M / TM) * (N / TN) < (1 << 30) && K >= 512;
-    if (tiled) {
-        static bool configured = false;
-        if (!configured) {
-            int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
-            if (rc != ADAHOP_OK) return rc;
-            rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true>),
+    auto generic = [&](int64_t m, int64_t n, const uint8_t *ac, const uint8_t *as, const uint8_t *bc, const uint8_t *bs,
+                       float *c, const uint16_t *ag, const uint16_t *bg) {
+        dim3 grid((unsigned)ceil_div(n, 128), (unsigned)ceil_div(m, 128));
+        hipLaunchKernelGGL((k_gemm_mx_generic<false>), grid, dim3(256), 0, st, m, n, K, ac, as, bc, bs, c, ldc, ag, bg, kpad);
+        return check_launch();
+    };
+    // The tiled kernel takes the whole 256x256 tiles; ragged edges (and shapes it cannot take at all) go to
+    // the bounds-checked kernel.
+    const bool fast_k = K % 256 == 0 && K >= 512 && kpad % 64 == 0 && aligned(a_scales, 8) && aligned(b_scales, 8);
+    const int64_t Mi = fast_k ? M / TM * TM : 0, Ni = fast_k ? N / TN * TN : 0;
+    if (Mi == 0 || Ni == 0 || (Mi / TM) * (Ni / TN) >= (1 << 30))
+        return generic(M, N, a_codes, a_scales, b_codes, b_scales, C, Ag, Bg);
+
+    static bool configured = false;
+    if (!configured) {
+        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
-            if (rc != ADAHOP_OK) return rc;
-            configured = true;
-        }
-        // scales, stage-major, in the caller's workspace
-        uint8_t *a_sm = static_cast<uint8_t *>(workspace);
-        uint8_t *b_sm = a_sm + align_up((size_t)M * (K / 32), 256);
-        const int64_t KB8 = K / 256;
-        hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(M * KB8, 256)), dim3(256), 0, st,
-                           reinterpret_cast<const uint64_t *>(a_scales), reinterpret_cast<uint64_t *>(a_sm), M, KB8);
-        hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(N * KB8, 256)), dim3(256), 0, st,
-                           reinterpret_cast<const uint64_t *>(b_scales), reinterpret_cast<uint64_t *>(b_sm), N, KB8);
-        int rc = check_launch();
         if (rc != ADAHOP_OK) return rc;
-        const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
+        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
+        if (rc != ADAHOP_OK) return rc;
+        configured = true;
+    }
+    // scales of the tiled part, stage-major, in the caller's workspace
+    uint8_t *a_sm = static_cast<uint8_t *>(workspace);
+    uint8_t *b_sm = a_sm + align_up((size_t)M * (K / 32), 256);
+    const int64_t KB8 = K / 256;
+    hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(Mi * KB8, 256)), dim3(256), 0, st,
+                       reinterpret_cast<const uint64_t *>(a_scales), reinterpret_cast<uint64_t *>(a_sm), Mi, KB8);
+    hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(Ni * KB8, 256)), dim3(256), 0, st,
+                       reinterpret_cast<const uint64_t *>(b_scales), reinterpret_cast<uint64_t *>(b_sm), Ni, KB8);
+    int rc = check_launch();
+    if (rc != ADAHOP_OK) return rc;
+    const int tiles_m = (int)(Mi / TM), tiles_n = (int)(Ni / TN);
 #ifndef ADAHOP_GROUP_M
 #define ADAHOP_GROUP_M 8
 #endif
-        const int group_m = tiles_m < ADAHOP_GROUP_M ? tiles_m : ADAHOP_GROUP_M;
-        const dim3 grid((unsigned)(tiles_m * tiles_n));
-        if (kpad > 0)
-            hipLaunchKernelGGL((k_gemm_mx_tile256<true>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
-                               b_sm, M, N, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
-        else
-            hipLaunchKernelGGL((k_gemm_mx_tile256<false>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm,
-                               b_codes, b_sm, M, N, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
-        return check_launch();
+    const int group_m = tiles_m < ADAHOP_GROUP_M ? tiles_m : ADAHOP_GROUP_M;
+    const dim3 grid((unsigned)(tiles_m * tiles_n));
+    if (kpad > 0)
+        hipLaunchKernelGGL((k_gemm_mx_tile256<true>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes, b_sm,
+                           Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
+    else
+        hipLaunchKernelGGL((k_gemm_mx_tile256<false>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
+                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
+    rc = check_launch();
+    if (rc != ADAHOP_OK) return rc;
+    if (Mi < M) { // bottom strip: rows [Mi, M), all columns
+        rc = generic(M - Mi, N, a_codes + Mi * (K / 2), a_scales + Mi * (K / 32), b_codes, b_scales, C + Mi * ldc,
+                     Ag ? Ag + Mi * kpad : nullptr, Bg);
+        if (rc != ADAHOP_OK) return rc;
     }
-    dim3 grid((unsigned)ceil_div(N, 128), (unsigned)ceil_div(M, 128));
-    hipLaunchKernelGGL((k_gemm_mx_generic<false>), grid, dim3(256), 0, st, M, N, K, a_codes, a_scales, b_codes,
-                       b_scales, C, ldc, Ag, Bg, kpad);
-    return check_launch();
+    if (Ni < N) // right strip: rows [0, Mi), columns [Ni, N)
+        rc = generic(Mi, N - Ni, a_codes, a_scales, b_codes + Ni * (K / 2), b_scales + Ni * (K / 32), C + Ni, Ag,
+                     Bg ? Bg + Ni * kpad : nullptr);
+    return rc;
 }
 
 int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint16_t *Bg, int kpad, float *C,

@@ -155,7 +155,8 @@ def test_foid_topk_bit_exact(ah, axis, k_contig):
 # ----------------------------------------------------------------------------- MXFP4 product
 
 @pytest.mark.parametrize("shape", [(32, 32, 64), (128, 128, 256), (200, 136, 96), (257, 129, 32), (64, 384, 1056),
-                                   (256, 256, 256), (512, 512, 512), (768, 1280, 2304), (2304, 512, 256)])
+                                   (256, 256, 256), (512, 512, 512), (768, 1280, 2304), (2304, 512, 256),
+                                   (300, 520, 512), (700, 256, 768), (256, 333, 1024)])
 def test_gemm_mx_matches_emulation(ah, shape):
     M, N, K = shape
     rng = np.random.default_rng(M + N + K)
@@ -264,9 +265,11 @@ def test_whole_path_small_all_layouts(ah, strategy, kind):
 
 @pytest.mark.parametrize("strategy,k", [(inputs.IHT, 0), (inputs.IHT_OE_K, 5), (inputs.IHT_OE_K, 70),
                                         (inputs.IHT_OE_ROW, 6), (inputs.IHT_OE_COL, 3)])
-def test_whole_path_tile_aligned_shape(ah, strategy, k):
-    """M, N, K multiples of 256: the tiled GEMM kernel (LDS-staged, K-channel part fused) runs."""
-    M, N, K = 768, 512, 1024
+@pytest.mark.parametrize("M,N", [(768, 512), (840, 600)])
+def test_whole_path_tile_aligned_shape(ah, strategy, k, M, N):
+    """K a multiple of 256: the tiled GEMM kernel (LDS-staged, K-channel part fused) takes the whole 256x256
+    tiles, the bounds-checked kernel the ragged edges of the second shape."""
+    K = 1024
     A = inputs.Operand(inputs.matrix(M, K, 1.0, 60, row_outliers=(4, 100.0, 100.0), col_outliers=(5, 50.0, 50.0)), True)
     B = inputs.Operand(np.ascontiguousarray(inputs.matrix(N, K, 0.02, 61).T), False)
     g = inputs.Gemm("tiled", A, B, strategy, 256, k)
