@@ -221,19 +221,10 @@ struct tile_state_t {
     uint32_t lds_w;                          // LDS address of this wave's 64 rows of the A slab, buffer 0
     uint32_t lds_s;                          // LDS address of this wave's 1 KiB of scales, buffer 0
     int nbf;
-#ifdef ADAHOP_DBG_TIMING
-    uint64_t dbg_dma, dbg_bar;
-#endif
 };
-#ifdef ADAHOP_DBG_TIMING
-__device__ unsigned long long g_dbg[8];
-#endif
 
 __device__ __forceinline__ void read_frags(const uint8_t *buf, const tile_state_t &t, int s, frags_t &f)
 {
-#ifdef ADAHOP_DBG_NO_LDSREAD
-    return;
-#endif
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         f.a[i] = *reinterpret_cast<const uint4 *>(buf + t.a_row + i * 32 * TKB + t.off[s]);
@@ -244,9 +235,6 @@ __device__ __forceinline__ void read_frags(const uint8_t *buf, const tile_state_
 // Item 0..3: A fragment of tile row item; 4..7: B fragment of tile column item - 4.
 __device__ __forceinline__ void read_frag_item(const uint8_t *buf, const tile_state_t &t, int s, int item, frags_t &f)
 {
-#ifdef ADAHOP_DBG_NO_LDSREAD
-    return;
-#endif
     if (item < 4)
         f.a[item] = *reinterpret_cast<const uint4 *>(buf + t.a_row + item * 32 * TKB + t.off[s]);
     else
@@ -268,10 +256,6 @@ template <bool BF, int S> __device__ __forceinline__ void mma_some(const frags_t
 #pragma unroll
     for (int q = q0; q < q1; ++q) {
         const int i = q >> 2, j = q & 3;
-#ifdef ADAHOP_DBG_NO_MMA
-        t.acc[i][j][S] += __int_as_float((f.a[i].x ^ f.b[j].y ^ t.sc.a[i] ^ t.sc.b[j]) & 0x3fffffff);
-        continue;
-#endif
         if constexpr (BF) {
             t.acc[i][j] = mfma_bf16(f.a[i], f.b[j], t.acc[i][j]);
         } else {
@@ -292,23 +276,13 @@ template <bool BF, int S> __device__ __forceinline__ void mma_step(const frags_t
 // operands have their own row pitch; such a stage has no scales and copy 16 is skipped.
 template <bool TBF, int D0, int D1> __device__ __forceinline__ void issue_copies(const tile_state_t &t, int stage)
 {
-#ifdef ADAHOP_DBG_NO_DMA
-    return;
-#endif
     const uint32_t boff = (stage & 1) * STAGE_BYTES;
     const int cs = stage - t.nbf;                      // index among the FP4 stages
     const uint32_t rp = TBF ? t.gpitch : t.pitch;      // row pitch of this stage's operands
-#ifdef ADAHOP_DBG_CONTIG_DMA
-    // timing experiment only: every wave streams private contiguous 8 KiB pieces (within the first 32 MiB of A)
-    const uint8_t *pa = t.ga + (int64_t)cs * 8192;
-    const uint8_t *pb = t.gb + (int64_t)cs * 8192;
-    const uint32_t v_even = threadIdx.x % 64 * 16, v_odd = v_even;
-#else
     const uint8_t *pa = TBF ? t.gga + (int64_t)stage * TKB : t.ga + (int64_t)cs * TKB;
     const uint8_t *pb = TBF ? t.ggb + (int64_t)stage * TKB : t.gb + (int64_t)cs * TKB;
     // row group g starts 8 g rows further: a wave-uniform term that goes into the base address
     const uint32_t v_even = t.lrow * rp + t.c_even, v_odd = t.lrow * rp + t.c_odd;
-#endif
 #pragma unroll
     for (int d = D0; d < D1; ++d) {
         if (d == 16) {
@@ -316,11 +290,7 @@ template <bool TBF, int D0, int D1> __device__ __forceinline__ void issue_copies
         } else {
             const int g = d >> 1;
             const uint32_t vo = (g & 1) ? v_odd : v_even;
-#ifdef ADAHOP_DBG_CONTIG_DMA
-            const int64_t goff = (int64_t)g * 1024;
-#else
             const int64_t goff = (int64_t)(8 * g) * rp;
-#endif
             if (d & 1)
                 dma16(pb + goff, vo, t.lds_w + boff + TM * TKB + g * 1024);
             else
@@ -334,14 +304,9 @@ template <bool TBF, int D0, int D1> __device__ __forceinline__ void issue_copies
 // and their matrix-core instructions with them.  The copies of a stage are therefore spread over
 // SPREAD matrix-core steps (4 slots per step, one after each row of instructions): the last step of
 // the stage that released the buffer and the first SPREAD - 1 steps of the following stage.
-#ifndef ADAHOP_SPREAD
-#define ADAHOP_SPREAD 3
-#endif
-#ifndef ADAHOP_SLOTS_PER_STEP
-#define ADAHOP_SLOTS_PER_STEP 16
-#endif
-constexpr int SPS = ADAHOP_SLOTS_PER_STEP;      // copy slots per matrix-core step: one after every 16 / SPS instructions
-constexpr int SPREAD = ADAHOP_SPREAD, NSLOT = SPS * SPREAD;
+constexpr int SPS = 16;                         // copy slots per matrix-core step: one after every 16 / SPS instructions
+constexpr int SPREAD = 3, NSLOT = SPS * SPREAD; // the stage body wires up at most three steps
+static_assert(SPREAD >= 1 && SPREAD <= 3 && 16 % SPS == 0, "copy slots are placed in the last and the first two steps");
 constexpr int slot_lo(int k) { return 17 * k / NSLOT; }
 
 template <bool TBF, int K> __device__ __forceinline__ void issue_slot(const tile_state_t &t, int stage)
@@ -401,16 +366,8 @@ __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, 
     mma_and_copies<BF, 1, HAS_NEXT, BF1, 2 * SPS, 2, false>(t.f1, t, stage + 1, st, t.f0);
     mma_and_copies<BF, 2, false, false, 0, 3, false>(t.f0, t, 0, st, t.f1);
     if constexpr (HAS_NEXT) {
-#ifdef ADAHOP_DBG_NO_VMWAIT
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#elif defined(ADAHOP_DBG_VMLAG)
-        asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)" ::"n"(ADAHOP_DBG_VMLAG) : "memory");
-#else
         asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)" ::: "memory"); // next stage landed; my reads done
-#endif
-#ifndef ADAHOP_DBG_NO_BARRIER
         __syncthreads();
-#endif
     }
     mma_and_copies<BF, 3, ISSUE, BF2, 0, (HAS_NEXT ? 0 : -1), (HAS_NEXT && !BF1)>(t.f1, t, stage + 2, sn, t.f0);
     if constexpr (HAS_NEXT && !BF1) t.sc = t.scn;
@@ -448,10 +405,6 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     const int wm = w >> 1, wn = w & 1;
 
     tile_state_t t;
-#ifdef ADAHOP_DBG_TIMING
-    t.dbg_dma = t.dbg_bar = 0;
-    const uint64_t dbg_start = __builtin_readcyclecounter();
-#endif
     // ---- copy engine: wave w moves rows [64w, 64w+64) of both slabs, 8 rows per instruction.
     // Lane i of instruction g writes LDS row 8g + i/8, chunk position i%8, which must hold logical
     // chunk (i%8) ^ ((row/2) & 7) = (i%8) ^ (4*(g&1) + i/16).
@@ -462,13 +415,8 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
         t.pitch = (uint32_t)(K >> 1);
         t.gpitch = (uint32_t)kpad * 2;
         const int64_t pitch = t.pitch, gpitch = t.gpitch;
-#ifdef ADAHOP_DBG_CONTIG_DMA
-        t.ga = uniform_ptr(a_codes + ((int64_t)(blockIdx.x % 16) * 4 + w) * (1 << 19));
-        t.gb = uniform_ptr(a_codes + ((int64_t)(blockIdx.x % 16) * 4 + w) * (1 << 19) + (1 << 18));
-#else
         t.ga = uniform_ptr(a_codes + (m0 + w * 64) * (int64_t)pitch);
         t.gb = uniform_ptr(b_codes + (n0 + w * 64) * (int64_t)pitch);
-#endif
         t.gga = uniform_ptr(reinterpret_cast<const uint8_t *>(Ag) + (m0 + w * 64) * (int64_t)gpitch);
         t.ggb = uniform_ptr(reinterpret_cast<const uint8_t *>(Bg) + (n0 + w * 64) * (int64_t)gpitch);
         // scales (stage-major): waves 0,1 move the two 1 KiB halves of the A slab's scales, waves 2,3 of B's
@@ -522,9 +470,6 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     read_frags(smem, t, 0, t.f0);
     if constexpr (!OEK) read_scales(smem, t, t.sc);
 
-#ifdef ADAHOP_DBG_TIMING
-    const uint64_t dbg_loop_start = __builtin_readcyclecounter();
-#endif
     int stage = 0;
     if constexpr (OEK) {
         for (; stage + 2 < t.nbf; ++stage) run_stage<true, true, true, true, true>(t, smem, stage);
@@ -539,63 +484,18 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     run_stage<false, false, false, true, false>(t, smem, stage);
     run_stage<false, false, false, false, false>(t, smem, stage + 1);
 
-#ifdef ADAHOP_DBG_TIMING
-    const uint64_t dbg_loop_end = __builtin_readcyclecounter();
-#endif
-#ifndef ADAHOP_DBG_NO_STORE
-#ifdef ADAHOP_DBG_STORE_SMALL
-    const int64_t m0s = (int64_t)((blockIdx.x & 255) / tiles_n) * TM, n0s = (int64_t)((blockIdx.x & 255) % tiles_n) * TN;
-    float *crow = C + (m0s + wm * 128 + h * 4) * ldc + n0s + wn * 128 + l32;
-#else
     float *crow = C + (m0 + wm * 128 + h * 4) * ldc + n0 + wn * 128 + l32;
-#endif
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-#ifndef ADAHOP_DBG_PLAIN_STORE
                 __builtin_nontemporal_store(t.acc[i][j][r], &crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32]);
-#else
-                crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32] = t.acc[i][j][r];
-#endif
-#else
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sum += t.acc[i][j][r];
-    if (sum == 123.456f) C[0] = sum;
-#endif
-#ifdef ADAHOP_DBG_TIMING
-    const uint64_t dbg_end = __builtin_readcyclecounter();
-    if (lane == 0) {
-        atomicAdd(&g_dbg[0], (unsigned long long)(dbg_end - dbg_start));
-        atomicAdd(&g_dbg[1], (unsigned long long)t.dbg_dma);
-        atomicAdd(&g_dbg[2], (unsigned long long)t.dbg_bar);
-        atomicAdd(&g_dbg[3], (unsigned long long)(dbg_end - dbg_loop_end));
-        atomicAdd(&g_dbg[4], 1ull);
-        atomicAdd(&g_dbg[5], (unsigned long long)(dbg_loop_end - dbg_loop_start));
-    }
-#endif
 }
 
 } // namespace
 
-#ifdef ADAHOP_DBG_TIMING
-extern "C" void adahop_dbg_read(unsigned long long *out, int reset)
-{
-    (void)hipDeviceSynchronize();
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg), sizeof(g_dbg));
-    if (reset) {
-        unsigned long long z[8] = {0};
-        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_dbg), z, sizeof(z));
-    }
-}
-#endif
 
 size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
@@ -641,10 +541,7 @@ int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, cons
     int rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
     const int tiles_m = (int)(Mi / TM), tiles_n = (int)(Ni / TN);
-#ifndef ADAHOP_GROUP_M
-#define ADAHOP_GROUP_M 8
-#endif
-    const int group_m = tiles_m < ADAHOP_GROUP_M ? tiles_m : ADAHOP_GROUP_M;
+    const int group_m = tiles_m < 8 ? tiles_m : 8;
     const dim3 grid((unsigned)(tiles_m * tiles_n));
     if (kpad > 0)
         hipLaunchKernelGGL((k_gemm_mx_tile256<true>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes, b_sm,
