@@ -114,6 +114,13 @@ int adahop_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, cons
                    const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *workspace,
                    size_t workspace_bytes, void *stream);
 
+/* The same product with C rounded to bf16 (round to nearest even from the fp32 accumulators; the
+ * paper's kernels also emit bf16): C is bf16 [M, ldc], 2-byte aligned.  The tiled kernel needs
+ * ldc % 8 == 0 and C 16-byte aligned; otherwise the bounds-checked kernel runs. */
+int adahop_gemm_mx_bf16out(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                           const uint8_t *b_codes, const uint8_t *b_scales, uint16_t *C, int64_t ldc,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * The whole path (App. F: FOID -> IHT + quantise -> MXFP4 product + BF16 outlier product -> sum).
  * A is [M, K], B is [N, K] (operand sense), C is fp32 [M, N] with leading dimension ldc.
@@ -143,6 +150,41 @@ size_t adahop_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, adahop_strat
 int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, int64_t ldc,
                 adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Quantise-once operand reuse and bf16 output (the paper's layers share operands between products:
+ * one activation feeds several projections, a weight is constant over the micro-batches of a step;
+ * App. F runs IHT + quantisation per operand, so its result can be kept).
+ *
+ * adahop_pack_operand: the residual -> IHT -> MXFP4 step of the whole path for ONE operand, into
+ * caller-owned canonical codes [outer, K/2] / scales [outer, K/32].  is_b: 0 if x will be the A
+ * operand, 1 if B.  strategy / iht_block as in adahop_gemm.  The residual of x depends on the
+ * extracted indices only for (OE_ROW, A), (OE_COL, B) and (OE_K, either); then idx int32 [k] (device,
+ * distinct, in range) names them and mask_ws is device scratch of `outer` (row / column kinds) or K
+ * (OE_K) bytes, 8-byte aligned; otherwise k, idx and mask_ws are ignored.
+ *
+ * adahop_gemm_ex: adahop_gemm with options.  opts may be NULL (then identical to adahop_gemm).
+ *   a_codes / a_scales (b_...): if non-NULL, A (B) is taken as packed by adahop_pack_operand with the
+ *     same strategy, iht_block, k and indices, and is not quantised again; the bf16 operand is still
+ *     required (FOID and the BF16 outlier product read it).  If the residual of a packed operand
+ *     depends on the indices (see above) and k > 0, use_given_idx must be set: INVALID_ARG otherwise.
+ *     The workspace regions of an operand packed by the caller are left untouched.
+ *   c_bf16: 0: C is float [M, ldc]; 1: C is bf16 [M, ldc] (2-byte aligned), every element the fp32
+ *     result rounded to nearest even once (the K-channel product is added before the rounding, the
+ *     row / column product overwrites its rows / columns).
+ * Workspace size and layout are those of adahop_gemm.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    const uint8_t *a_codes, *a_scales;
+    const uint8_t *b_codes, *b_scales;
+    int c_bf16;
+} adahop_gemm_opts_t;
+
+int adahop_pack_operand(const adahop_operand_t *x, int is_b, adahop_strategy_t strategy, int iht_block, int k,
+                        const int32_t *idx, uint8_t *mask_ws, uint8_t *codes, uint8_t *scales, void *stream);
+int adahop_gemm_ex(const adahop_operand_t *A, const adahop_operand_t *B, void *C, int64_t ldc,
+                   adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
+                   const adahop_gemm_opts_t *opts, void *workspace, size_t workspace_bytes, void *stream);
 
 /* The BF16 outlier product alone (second term of Eq. 7 / Eq. 8 / the K-channel form), for callers
  * that keep quantised operands across products and for tests.

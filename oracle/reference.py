@@ -215,6 +215,29 @@ def adahop_gemm(a_bits, a_k_contig, b_bits, b_k_contig, strategy, iht_block, k=0
     return dict(C=Cm, a_codes=a_codes, a_scales=a_scales, b_codes=b_codes, b_scales=b_scales, idx=sel)
 
 
+def round_to_bf16(x):
+    """bf16 bit patterns (uint16) of a float64 array: each value rounded ONCE to the nearest number with an
+    8-bit significand (exponent range of fp32, gradual underflow), ties to the even significand.
+
+    The paper's kernels emit C in BF16 (App. F, last item); the library's optional bf16 output is compared
+    with this rounding of the double-precision result.  Written from the definition of the format, not
+    through an fp32 intermediate (which would round twice)."""
+    x = np.asarray(x, dtype=np.float64)
+    mag = np.abs(x)
+    _, e = np.frexp(mag)                               # mag = m 2^e with m in [0.5, 1)
+    e = np.maximum(e, -125)                            # below 2^-126 the spacing stays that of the smallest normal
+    quantum = np.ldexp(1.0, e - 8)                     # spacing of 8-bit significands in [2^(e-1), 2^e)
+    val = np.rint(mag / quantum) * quantum             # np.rint rounds half to even; the division is exact
+    val = np.where(val >= np.ldexp(1.0, 128), np.inf, val)
+    f32 = np.copysign(val, x).astype(np.float32)       # exact: val has at most 8 significant bits
+    return (f32.view(np.uint32) >> 16).astype(np.uint16)
+
+
+def bf16_to_double(bits):
+    """Values of bf16 bit patterns (uint16 array) as float64 (exact)."""
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
 # ------------------------------------------------------------------------------------------------
 # Outlier-pattern detection and strategy table (paper Sec. 4.1, 4.2, App. A)
 # ------------------------------------------------------------------------------------------------

@@ -18,7 +18,7 @@ ADAHOP_OK, ADAHOP_E_INVALID_ARG, ADAHOP_E_WORKSPACE, ADAHOP_E_HIP = 0, -1, -2, -
 ADAHOP_PATTERN_NONE, ADAHOP_PATTERN_OUTER, ADAHOP_PATTERN_K = range(3)
 
 EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_gemm_mx",
-           "adahop_gemm_mx_workspace_bytes",
+           "adahop_gemm_mx_bf16out", "adahop_gemm_mx_workspace_bytes", "adahop_pack_operand", "adahop_gemm_ex",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
            "adahop_oe_gemm_bf16", "adahop_detect_pattern_workspace_bytes", "adahop_detect_pattern",
            "adahop_select_strategy", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
@@ -36,6 +36,11 @@ class AdahopError(RuntimeError):
 
 class adahop_operand_t(C.Structure):
     _fields_ = [("data", C.c_void_p), ("outer", C.c_int64), ("K", C.c_int64), ("ld", C.c_int64), ("k_contig", C.c_int)]
+
+
+class adahop_gemm_opts_t(C.Structure):
+    _fields_ = [("a_codes", C.c_void_p), ("a_scales", C.c_void_p), ("b_codes", C.c_void_p), ("b_scales", C.c_void_p),
+                ("c_bf16", C.c_int)]
 
 
 class adahop_ws_layout_t(C.Structure):
@@ -60,6 +65,9 @@ def lib():
         L.adahop_iht_quantize.argtypes = [OP, I, P, P, P, P, P]
         L.adahop_foid_topk.argtypes = [OP, I, I, P, P, P, P]
         L.adahop_gemm_mx.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P, SZ, P]
+        L.adahop_gemm_mx_bf16out.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P, SZ, P]
+        L.adahop_pack_operand.argtypes = [OP, I, I, I, I, P, P, P, P, P]
+        L.adahop_gemm_ex.argtypes = [OP, OP, P, I64, I, I, I, P, I, C.POINTER(adahop_gemm_opts_t), P, SZ, P]
         L.adahop_gemm_mx_workspace_bytes.argtypes = [I64, I64, I64]
         L.adahop_gemm_mx_workspace_bytes.restype = SZ
         L.adahop_gemm_workspace_layout.argtypes = [I64, I64, I64, I, I, C.POINTER(adahop_ws_layout_t)]
@@ -157,15 +165,18 @@ def adahop_gemm_mx_workspace_bytes(M, N, K):
     return int(lib().adahop_gemm_mx_workspace_bytes(M, N, K))
 
 
-def adahop_gemm_mx(a_codes, a_scales, b_codes, b_scales, Cout=None, workspace=None, stream=None):
+def adahop_gemm_mx(a_codes, a_scales, b_codes, b_scales, Cout=None, workspace=None, stream=None, c_bf16=False):
+    """C = dequant(A) dequant(B)^T; Cout float32, or bfloat16 with c_bf16 (or a bfloat16 Cout)."""
     M, N, K = a_codes.shape[0], b_codes.shape[0], a_codes.shape[1] * 2
     assert b_codes.shape[1] * 2 == K
     if Cout is None:
-        Cout = torch.empty((M, N), dtype=torch.float32, device=a_codes.device)
+        Cout = torch.empty((M, N), dtype=torch.bfloat16 if c_bf16 else torch.float32, device=a_codes.device)
     if workspace is None:
         workspace = _u8((adahop_gemm_mx_workspace_bytes(M, N, K),), a_codes.device)
-    _check(lib().adahop_gemm_mx(M, N, K, _ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), _ptr(Cout),
-                                Cout.stride(0), _ptr(workspace), workspace.numel(), _stream(stream)), "adahop_gemm_mx")
+    fn, name = ((lib().adahop_gemm_mx_bf16out, "adahop_gemm_mx_bf16out") if Cout.element_size() == 2
+                else (lib().adahop_gemm_mx, "adahop_gemm_mx"))
+    _check(fn(M, N, K, _ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), _ptr(Cout), Cout.stride(0),
+              _ptr(workspace), workspace.numel(), _stream(stream)), name)
     return Cout
 
 
@@ -179,22 +190,45 @@ def adahop_gemm_workspace_bytes(M, N, K, strategy, k):
     return int(lib().adahop_gemm_workspace_bytes(M, N, K, strategy, k))
 
 
-def adahop_gemm(A, B, strategy, iht_block, k=0, idx=None, Cout=None, workspace=None, stream=None):
+def adahop_pack_operand(x, is_b, strategy, iht_block, k=0, idx=None, codes=None, scales=None, stream=None):
+    """Residual -> IHT -> MXFP4 of one operand as the whole path would do it; returns (codes, scales)."""
+    dev = x.tensor.device
+    codes = _u8((x.outer, x.K // 2), dev) if codes is None else codes
+    scales = _u8((x.outer, x.K // 32), dev) if scales is None else scales
+    mask_ws = _u8((max(x.outer, x.K),), dev) if k else None
+    _check(lib().adahop_pack_operand(C.byref(x.c()), int(bool(is_b)), strategy, iht_block, k, _ptr(idx), _ptr(mask_ws),
+                                     _ptr(codes), _ptr(scales), _stream(stream)), "adahop_pack_operand")
+    return codes, scales
+
+
+def adahop_gemm(A, B, strategy, iht_block, k=0, idx=None, Cout=None, workspace=None, stream=None,
+                a_packed=None, b_packed=None, c_bf16=False):
     """Whole path.  Returns dict(C, idx, workspace, layout, a_codes, a_scales, b_codes, b_scales, mask)
-    where the codes / scales / mask entries are views into the workspace."""
+    where the codes / scales / mask entries are views into the workspace.  a_packed / b_packed: (codes,
+    scales) from adahop_pack_operand; c_bf16 (or a bfloat16 Cout): bf16 output.  Any of the three routes
+    the call through adahop_gemm_ex."""
     dev = A.tensor.device
     M, N, K = A.outer, B.outer, A.K
     L = adahop_gemm_workspace_layout(M, N, K, strategy, k)
     if workspace is None:
         workspace = _u8((L.total,), dev)
     if Cout is None:
-        Cout = torch.empty((M, N), dtype=torch.float32, device=dev)
+        Cout = torch.empty((M, N), dtype=torch.bfloat16 if c_bf16 else torch.float32, device=dev)
+    c_bf16 = Cout.element_size() == 2
     use_given = idx is not None
     if idx is None:
         idx = torch.empty(max(k, 1), dtype=torch.int32, device=dev)
-    _check(lib().adahop_gemm(C.byref(A.c()), C.byref(B.c()), _ptr(Cout), Cout.stride(0), strategy, iht_block, k,
-                             _ptr(idx), int(use_given), _ptr(workspace), workspace.numel(), _stream(stream)),
-           "adahop_gemm")
+    if a_packed is None and b_packed is None and not c_bf16:
+        _check(lib().adahop_gemm(C.byref(A.c()), C.byref(B.c()), _ptr(Cout), Cout.stride(0), strategy, iht_block, k,
+                                 _ptr(idx), int(use_given), _ptr(workspace), workspace.numel(), _stream(stream)),
+               "adahop_gemm")
+    else:
+        ac, asc = a_packed if a_packed is not None else (None, None)
+        bc, bsc = b_packed if b_packed is not None else (None, None)
+        opts = adahop_gemm_opts_t(_ptr(ac), _ptr(asc), _ptr(bc), _ptr(bsc), int(c_bf16))
+        _check(lib().adahop_gemm_ex(C.byref(A.c()), C.byref(B.c()), _ptr(Cout), Cout.stride(0), strategy, iht_block, k,
+                                    _ptr(idx), int(use_given), C.byref(opts), _ptr(workspace), workspace.numel(),
+                                    _stream(stream)), "adahop_gemm_ex")
     dim = {ADAHOP_IHT_OE_ROW: M, ADAHOP_IHT_OE_COL: N, ADAHOP_IHT_OE_K: K}.get(strategy, 0)
     view = lambda off, n, shape: workspace[off:off + n].view(shape)
     return dict(C=Cout, idx=idx[:k], workspace=workspace, layout=L,

@@ -95,19 +95,34 @@ size_t adahop_gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
     return gemm_mx_workspace_bytes(M, N, K);
 }
 
-int adahop_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
-                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *workspace,
-                   size_t workspace_bytes, void *stream)
+static int gemm_mx_checked(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                           const uint8_t *b_codes, const uint8_t *b_scales, void *C, int64_t ldc, int c_bf16,
+                           void *workspace, size_t workspace_bytes, void *stream)
 {
     if (M < 1 || N < 1 || K < 32 || K % 32 != 0 || M > MAX_OUTER || N > MAX_OUTER || K > MAX_K)
         return ADAHOP_E_INVALID_ARG;
     if (!a_codes || !a_scales || !b_codes || !b_scales || !C || ldc < N) return ADAHOP_E_INVALID_ARG;
-    if (!aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(C, 4)) return ADAHOP_E_INVALID_ARG;
+    if (!aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(C, c_bf16 ? 2 : 4)) return ADAHOP_E_INVALID_ARG;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < gemm_mx_workspace_bytes(M, N, K))
         return ADAHOP_E_WORKSPACE;
-    return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0, workspace,
+    return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, nullptr, nullptr, 0, workspace,
                           static_cast<hipStream_t>(stream));
 }
+
+int adahop_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    return gemm_mx_checked(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, 0, workspace, workspace_bytes, stream);
+}
+
+int adahop_gemm_mx_bf16out(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                           const uint8_t *b_codes, const uint8_t *b_scales, uint16_t *C, int64_t ldc, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    return gemm_mx_checked(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, 1, workspace, workspace_bytes, stream);
+}
+
 
 int adahop_gemm_workspace_layout(int64_t M, int64_t N, int64_t K, adahop_strategy_t strategy, int k,
                                  adahop_ws_layout_t *out)
@@ -153,13 +168,14 @@ size_t adahop_oe_gather_bytes(int64_t M, int64_t N, int64_t K, adahop_strategy_t
     return align_up((size_t)M * kpad_of(k) * 2, 256) + align_up((size_t)N * kpad_of(k) * 2, 256);
 }
 
-static int validate_pair(const adahop_operand_t *A, const adahop_operand_t *B, const float *C, int64_t ldc)
+static int validate_pair(const adahop_operand_t *A, const adahop_operand_t *B, const void *C, int64_t ldc,
+                         size_t c_align = 4)
 {
     int rc = validate_operand(A);
     if (rc != ADAHOP_OK) return rc;
     rc = validate_operand(B);
     if (rc != ADAHOP_OK) return rc;
-    if (A->K != B->K || !C || ldc < B->outer || !aligned(C, 4)) return ADAHOP_E_INVALID_ARG;
+    if (A->K != B->K || !C || ldc < B->outer || !aligned(C, c_align)) return ADAHOP_E_INVALID_ARG;
     return ADAHOP_OK;
 }
 
@@ -176,7 +192,7 @@ int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, ad
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t need = adahop_oe_gather_bytes(A->outer, B->outer, A->K, kind, k);
     if (!gather_ws || !aligned(gather_ws, 256) || gather_bytes < need) return ADAHOP_E_WORKSPACE;
-    if (kind != ADAHOP_IHT_OE_K) return launch_oe_rowcol(*A, *B, kind, idx, k, C, ldc, gather_ws, st);
+    if (kind != ADAHOP_IHT_OE_K) return launch_oe_rowcol(*A, *B, kind, idx, k, C, ldc, 0, gather_ws, st);
     const int kpad = kpad_of(k);
     uint16_t *Ag = static_cast<uint16_t *>(gather_ws);
     uint16_t *Bg = reinterpret_cast<uint16_t *>(static_cast<char *>(gather_ws) + align_up((size_t)A->outer * kpad * 2, 256));
@@ -220,11 +236,45 @@ int adahop_select_strategy(adahop_pattern_t pattern_a, adahop_pattern_t pattern_
     return ADAHOP_IHT;
 }
 
-int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, int64_t ldc,
-                adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
-                void *workspace, size_t workspace_bytes, void *stream)
+// Which mask the residual of an operand needs under a strategy: 0 none, 1 over its outer index, 2 over K.
+static int residual_mask_kind(adahop_strategy_t s, bool is_b)
 {
-    int rc = validate_pair(A, B, C, ldc);
+    if (s == ADAHOP_IHT_OE_K) return 2;
+    if (s == ADAHOP_IHT_OE_ROW && !is_b) return 1;
+    if (s == ADAHOP_IHT_OE_COL && is_b) return 1;
+    return 0;
+}
+
+int adahop_pack_operand(const adahop_operand_t *x, int is_b, adahop_strategy_t strategy, int iht_block, int k,
+                        const int32_t *idx, uint8_t *mask_ws, uint8_t *codes, uint8_t *scales, void *stream)
+{
+    int rc = validate_operand(x);
+    if (rc != ADAHOP_OK) return rc;
+    if (strategy < ADAHOP_NONE || strategy > ADAHOP_IHT_OE_K) return ADAHOP_E_INVALID_ARG;
+    const int b = strategy == ADAHOP_NONE ? 0 : iht_block;
+    if (!valid_iht_block(b) || (b > 0 && x->K % b != 0)) return ADAHOP_E_INVALID_ARG;
+    if (strategy != ADAHOP_NONE && b == 0) return ADAHOP_E_INVALID_ARG;
+    if (!codes || !scales || !aligned(codes, 16)) return ADAHOP_E_INVALID_ARG;
+    const int kind = residual_mask_kind(strategy, is_b != 0);
+    const int64_t dim = kind == 1 ? x->outer : x->K;
+    const bool masked = kind != 0 && k != 0;
+    if (masked && (k < 0 || k > dim || !idx || !mask_ws || !aligned(mask_ws, 8))) return ADAHOP_E_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (masked) {
+        rc = launch_mask_from_idx(idx, k, mask_ws, dim, st);
+        if (rc != ADAHOP_OK) return rc;
+    }
+    return launch_iht_quantize(*x, b, masked && kind == 1 ? mask_ws : nullptr, masked && kind == 2 ? mask_ws : nullptr,
+                               codes, scales, st);
+}
+
+static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B, void *C, int64_t ldc,
+                           adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
+                           const adahop_gemm_opts_t *opts, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int c_bf16 = opts ? opts->c_bf16 : 0;
+    if (c_bf16 != 0 && c_bf16 != 1) return ADAHOP_E_INVALID_ARG;
+    int rc = validate_pair(A, B, C, ldc, c_bf16 ? 2 : 4);
     if (rc != ADAHOP_OK) return rc;
     const int64_t M = A->outer, N = B->outer, K = A->K;
     int64_t dim = 0;
@@ -235,6 +285,13 @@ int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, 
     if (k < 0 || (dim > 0 && k > dim)) return ADAHOP_E_INVALID_ARG;
     const bool oe = dim > 0 && k > 0;
     if (oe && !idx_inout) return ADAHOP_E_INVALID_ARG;
+    // operands packed by the caller: both arrays or neither, and a residual that depends on the extracted
+    // indices can only be trusted when the caller also supplies those indices
+    const bool a_given = opts && (opts->a_codes || opts->a_scales), b_given = opts && (opts->b_codes || opts->b_scales);
+    if (a_given && (!opts->a_codes || !opts->a_scales || !aligned(opts->a_codes, 16))) return ADAHOP_E_INVALID_ARG;
+    if (b_given && (!opts->b_codes || !opts->b_scales || !aligned(opts->b_codes, 16))) return ADAHOP_E_INVALID_ARG;
+    const int a_kind = oe ? residual_mask_kind(strategy, false) : 0, b_kind = oe ? residual_mask_kind(strategy, true) : 0;
+    if (!use_given_idx && ((a_given && a_kind) || (b_given && b_kind))) return ADAHOP_E_INVALID_ARG;
     adahop_ws_layout_t L;
     rc = adahop_gemm_workspace_layout(M, N, K, strategy, k, &L);
     if (rc != ADAHOP_OK) return rc;
@@ -242,15 +299,14 @@ int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, 
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    uint8_t *a_codes = reinterpret_cast<uint8_t *>(ws + L.a_codes), *a_scales = reinterpret_cast<uint8_t *>(ws + L.a_scales);
-    uint8_t *b_codes = reinterpret_cast<uint8_t *>(ws + L.b_codes), *b_scales = reinterpret_cast<uint8_t *>(ws + L.b_scales);
     uint8_t *mask = reinterpret_cast<uint8_t *>(ws + L.mask);
     float *scores = reinterpret_cast<float *>(ws + L.scores);
 
     // 1. which rows / columns / K-channels leave the MXFP4 path (App. F item 1)
     if (oe) {
+        const bool mask_used = (!a_given && a_kind) || (!b_given && b_kind);
         if (use_given_idx) {
-            rc = launch_mask_from_idx(idx_inout, k, mask, dim, st);
+            rc = mask_used ? launch_mask_from_idx(idx_inout, k, mask, dim, st) : ADAHOP_OK;
         } else if (strategy == ADAHOP_IHT_OE_ROW) {
             rc = launch_foid_topk(*A, 0, k, idx_inout, mask, scores, st);
         } else if (strategy == ADAHOP_IHT_OE_COL) {
@@ -260,14 +316,21 @@ int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, 
         }
         if (rc != ADAHOP_OK) return rc;
     }
-    // 2. residual -> transform -> MXFP4 (App. F item 2)
-    const uint8_t *a_zo = (oe && strategy == ADAHOP_IHT_OE_ROW) ? mask : nullptr;
-    const uint8_t *b_zo = (oe && strategy == ADAHOP_IHT_OE_COL) ? mask : nullptr;
-    const uint8_t *zk = (oe && strategy == ADAHOP_IHT_OE_K) ? mask : nullptr;
-    rc = launch_iht_quantize(*A, b, a_zo, zk, a_codes, a_scales, st);
-    if (rc != ADAHOP_OK) return rc;
-    rc = launch_iht_quantize(*B, b, b_zo, zk, b_codes, b_scales, st);
-    if (rc != ADAHOP_OK) return rc;
+    // 2. residual -> transform -> MXFP4 (App. F item 2), for the operands the caller has not packed
+    const uint8_t *a_codes = a_given ? opts->a_codes : reinterpret_cast<uint8_t *>(ws + L.a_codes);
+    const uint8_t *a_scales = a_given ? opts->a_scales : reinterpret_cast<uint8_t *>(ws + L.a_scales);
+    const uint8_t *b_codes = b_given ? opts->b_codes : reinterpret_cast<uint8_t *>(ws + L.b_codes);
+    const uint8_t *b_scales = b_given ? opts->b_scales : reinterpret_cast<uint8_t *>(ws + L.b_scales);
+    if (!a_given) {
+        rc = launch_iht_quantize(*A, b, a_kind == 1 ? mask : nullptr, a_kind == 2 ? mask : nullptr,
+                                 reinterpret_cast<uint8_t *>(ws + L.a_codes), reinterpret_cast<uint8_t *>(ws + L.a_scales), st);
+        if (rc != ADAHOP_OK) return rc;
+    }
+    if (!b_given) {
+        rc = launch_iht_quantize(*B, b, b_kind == 1 ? mask : nullptr, b_kind == 2 ? mask : nullptr,
+                                 reinterpret_cast<uint8_t *>(ws + L.b_codes), reinterpret_cast<uint8_t *>(ws + L.b_scales), st);
+        if (rc != ADAHOP_OK) return rc;
+    }
     // 3. MXFP4 product, with the K-channel BF16 product fused in front; 4. row / column BF16 product
     if (oe && strategy == ADAHOP_IHT_OE_K) {
         const int kpad = kpad_of(k);
@@ -276,12 +339,28 @@ int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, 
         if (rc != ADAHOP_OK) return rc;
         rc = launch_gather_k(*B, idx_inout, k, kpad, Bg, st);
         if (rc != ADAHOP_OK) return rc;
-        return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, Ag, Bg, kpad, ws + L.gemm, st);
+        return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, Ag, Bg, kpad, ws + L.gemm, st);
     }
-    rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, nullptr, nullptr, 0, ws + L.gemm, st);
+    rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, nullptr, nullptr, 0, ws + L.gemm, st);
     if (rc != ADAHOP_OK) return rc;
-    if (oe) rc = launch_oe_rowcol(*A, *B, strategy, idx_inout, k, C, ldc, ws + L.gather_a, st);
+    if (oe) rc = launch_oe_rowcol(*A, *B, strategy, idx_inout, k, C, ldc, c_bf16, ws + L.gather_a, st);
     return rc;
+}
+
+int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, int64_t ldc,
+                adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
+                void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemm_whole_path(A, B, C, ldc, strategy, iht_block, k, idx_inout, use_given_idx, nullptr, workspace,
+                           workspace_bytes, stream);
+}
+
+int adahop_gemm_ex(const adahop_operand_t *A, const adahop_operand_t *B, void *C, int64_t ldc,
+                   adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
+                   const adahop_gemm_opts_t *opts, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemm_whole_path(A, B, C, ldc, strategy, iht_block, k, idx_inout, use_given_idx, opts, workspace,
+                           workspace_bytes, stream);
 }
 
 } // extern "C"

@@ -33,14 +33,15 @@ int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, u
 int launch_mask_from_idx(const int32_t *idx, int k, uint8_t *mask, int64_t dim, hipStream_t st);
 // OE-K operands for the fused prologue: Ag [M, kpad], Bg [N, kpad] bf16, K-contiguous, zero padded.
 int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
-                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc,
+                   const uint8_t *b_codes, const uint8_t *b_scales, void *C, int64_t ldc, int c_bf16,
                    const uint16_t *Ag, const uint16_t *Bg, int kpad, void *workspace, hipStream_t st);
 size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kpad, uint16_t *out, hipStream_t st);
+// C is float[M, ldc], or bf16[M, ldc] when c_bf16 is set (here and in launch_oe_rowcol).
 // Row / column outlier product; workspace of oe_rowcol_workspace_bytes() bytes, 256-byte aligned.
 size_t oe_rowcol_workspace_bytes(int64_t M, int64_t N, int64_t K, int kind, int k);
 int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int kind, const int32_t *idx, int k,
-                     float *C, int64_t ldc, void *workspace, hipStream_t st);
+                     void *C, int64_t ldc, int c_bf16, void *workspace, hipStream_t st);
 int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint16_t *Bg, int kpad, float *C,
                            int64_t ldc, hipStream_t st);
 

@@ -34,17 +34,30 @@ __device__ __forceinline__ v16f mfma_bf16(uint4 a, uint4 b, v16f c)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
 }
 
+// fp32 -> bf16 bits, round to nearest even (finite values and infinities).
+__device__ __forceinline__ uint32_t bf16_bits(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Output element types of C: float, or bf16 held as its 16 bits.
+__device__ __forceinline__ void store_c(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_c(uint16_t *p, float v) { *p = (uint16_t)bf16_bits(v); }
+__device__ __forceinline__ float load_c(const float *p) { return *p; }
+__device__ __forceinline__ float load_c(const uint16_t *p) { return bf16_one(*p); }
+
 // ------------------------------------------------------------------------------------------------
 // Generic kernel: any M, N, any K % 32 == 0.  Workgroup tile 128x128, four waves as 2x2, each wave
 // 64x64 (2x2 matrix-core tiles), operands read straight from global memory with bounds checks.
 // It is the reference for the layout assumptions above and the fallback for ragged shapes.
 // ------------------------------------------------------------------------------------------------
-template <bool ACCUMULATE>
+template <bool ACCUMULATE, typename OUT>
 __global__ __launch_bounds__(256) void k_gemm_mx_generic(int64_t M, int64_t N, int64_t K,
                                                          const uint8_t *__restrict__ a_codes,
                                                          const uint8_t *__restrict__ a_scales,
                                                          const uint8_t *__restrict__ b_codes,
-                                                         const uint8_t *__restrict__ b_scales, float *__restrict__ C,
+                                                         const uint8_t *__restrict__ b_scales, OUT *__restrict__ C,
                                                          int64_t ldc, const uint16_t *__restrict__ Ag,
                                                          const uint16_t *__restrict__ Bg, int kpad)
 {
@@ -106,11 +119,11 @@ __global__ __launch_bounds__(256) void k_gemm_mx_generic(int64_t M, int64_t N, i
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = m0 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
                 if (row < M && col < N) {
-                    float *p = C + row * ldc + col;
+                    OUT *p = C + row * ldc + col;
                     if constexpr (ACCUMULATE)
-                        *p = *p + acc[i][j][r];
+                        store_c(p, load_c(p) + acc[i][j][r]);
                     else
-                        *p = acc[i][j][r];
+                        store_c(p, acc[i][j][r]);
                 }
             }
         }
@@ -376,12 +389,12 @@ __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, 
 // The stage loop runs over the gathered bf16 K-channels first (OEK), then over the FP4 stages, on
 // one pipeline: `stage` counts over both.  Host side guarantees K >= 512 (two FP4 stages), so that
 // every bf16 stage has two successors and the last two stages are FP4 stages.
-template <bool OEK>
+template <bool OEK, typename OUT>
 __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_t *__restrict__ a_codes,
                                                          const uint8_t *__restrict__ a_scales_sm,
                                                          const uint8_t *__restrict__ b_codes,
                                                          const uint8_t *__restrict__ b_scales_sm, int64_t M, int64_t N,
-                                                         float *__restrict__ C, int64_t ldc,
+                                                         OUT *__restrict__ C, int64_t ldc,
                                                          const uint16_t *__restrict__ Ag,
                                                          const uint16_t *__restrict__ Bg, int kpad, int tiles_m,
                                                          int tiles_n, int group_m)
@@ -484,14 +497,60 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     run_stage<false, false, false, true, false>(t, smem, stage);
     run_stage<false, false, false, false, false>(t, smem, stage + 1);
 
-    float *crow = C + (m0 + wm * 128 + h * 4) * ldc + n0 + wn * 128 + l32;
+    if constexpr (sizeof(OUT) == 4) {
+        float *crow = C + (m0 + wm * 128 + h * 4) * ldc + n0 + wn * 128 + l32;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                __builtin_nontemporal_store(t.acc[i][j][r], &crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32]);
+                for (int r = 0; r < 16; ++r)
+                    __builtin_nontemporal_store(t.acc[i][j][r],
+                                                &crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32]);
+    } else {
+        // bf16 C, staged through LDS so that global memory sees whole 256-byte row segments.  A lane holds one
+        // column: it converts two consecutive accumulator rows into one packed pair, trades pairs with its
+        // neighbour and keeps, as one dword, two adjacent columns of one row (even lane: the low halves = rows
+        // 0, 2 of each four; odd lane: the high halves = rows 1, 3).
+        // Each wave stages its 128x128 block in two halves of 64 rows in a private region (pitch 272 bytes),
+        // then reads rows back 16 bytes per lane.  Host side guarantees ldc % 8 == 0 and a 16-byte aligned C.
+        constexpr int CP = 272;
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        __syncthreads(); // every wave is done with the operand slabs
+        uint8_t *stage = smem + w * (64 * CP);
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        const int odd = lane & 1;
+        // byte selector over {neighbour's pair (bytes 4-7), own pair (bytes 0-3)}
+        const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+        OUT *cbase = C + (m0 + wm * 128) * ldc + n0 + wn * 128;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2) {
+                        const v16f &a = t.acc[half * 2 + ii][j];
+                        const f2 pair = {a[r], a[r + 1]};
+                        const uint32_t p = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf2)); // RNE
+                        const uint32_t q = __builtin_amdgcn_update_dpp(0, p, 0xB1, 0xF, 0xF, true); // lane ^ 1's pair
+                        const int row = ii * 32 + (r >> 2) * 8 + h * 4 + (r & 3) + odd;
+                        *reinterpret_cast<uint32_t *>(stage + row * CP + (j * 32 + (l32 & ~1)) * 2) =
+                            __builtin_amdgcn_perm(q, p, sel);
+                    }
+            __syncthreads();
+#pragma unroll 4
+            for (int q = 0; q < 16; ++q) {
+                const int row = q * 4 + (lane >> 4);
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + row * CP + (lane & 15) * 16);
+                __builtin_nontemporal_store(
+                    v, reinterpret_cast<u32x4 *>(cbase + (int64_t)(half * 64 + row) * ldc + (lane & 15) * 8));
+            }
+            if (half == 0) __syncthreads();
+        }
+    }
 }
 
 } // namespace
@@ -502,30 +561,36 @@ size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
     return align_up((size_t)M * (K / 32), 256) + align_up((size_t)N * (K / 32), 256);
 }
 
-int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
-                   const uint8_t *b_codes, const uint8_t *b_scales, float *C, int64_t ldc, const uint16_t *Ag,
-                   const uint16_t *Bg, int kpad, void *workspace, hipStream_t st)
+namespace {
+
+template <typename OUT>
+int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                     const uint8_t *b_codes, const uint8_t *b_scales, OUT *C, int64_t ldc, const uint16_t *Ag,
+                     const uint16_t *Bg, int kpad, void *workspace, hipStream_t st)
 {
     if (M == 0 || N == 0) return ADAHOP_OK;
     auto generic = [&](int64_t m, int64_t n, const uint8_t *ac, const uint8_t *as, const uint8_t *bc, const uint8_t *bs,
-                       float *c, const uint16_t *ag, const uint16_t *bg) {
+                       OUT *c, const uint16_t *ag, const uint16_t *bg) {
         dim3 grid((unsigned)ceil_div(n, 128), (unsigned)ceil_div(m, 128));
-        hipLaunchKernelGGL((k_gemm_mx_generic<false>), grid, dim3(256), 0, st, m, n, K, ac, as, bc, bs, c, ldc, ag, bg, kpad);
+        hipLaunchKernelGGL((k_gemm_mx_generic<false, OUT>), grid, dim3(256), 0, st, m, n, K, ac, as, bc, bs, c, ldc, ag, bg,
+                           kpad);
         return check_launch();
     };
     // The tiled kernel takes the whole 256x256 tiles; ragged edges (and shapes it cannot take at all) go to
-    // the bounds-checked kernel.
-    const bool fast_k = K % 256 == 0 && K >= 512 && kpad % 64 == 0 && aligned(a_scales, 8) && aligned(b_scales, 8);
+    // the bounds-checked kernel.  Its bf16 epilogue stores 16 bytes per lane.
+    const bool fast_c = sizeof(OUT) == 4 || (ldc % 8 == 0 && aligned(C, 16));
+    const bool fast_k =
+        fast_c && K % 256 == 0 && K >= 512 && kpad % 64 == 0 && aligned(a_scales, 8) && aligned(b_scales, 8);
     const int64_t Mi = fast_k ? M / TM * TM : 0, Ni = fast_k ? N / TN * TN : 0;
     if (Mi == 0 || Ni == 0 || (Mi / TM) * (Ni / TN) >= (1 << 30))
         return generic(M, N, a_codes, a_scales, b_codes, b_scales, C, Ag, Bg);
 
-    static bool configured = false;
+    static bool configured = false; // per output type
     if (!configured) {
-        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false>),
+        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false, OUT>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
         if (rc != ADAHOP_OK) return rc;
-        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true>),
+        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true, OUT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
         if (rc != ADAHOP_OK) return rc;
         configured = true;
@@ -544,10 +609,10 @@ int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, cons
     const int group_m = tiles_m < 8 ? tiles_m : 8;
     const dim3 grid((unsigned)(tiles_m * tiles_n));
     if (kpad > 0)
-        hipLaunchKernelGGL((k_gemm_mx_tile256<true>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes, b_sm,
-                           Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
+        hipLaunchKernelGGL((k_gemm_mx_tile256<true, OUT>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
+                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
     else
-        hipLaunchKernelGGL((k_gemm_mx_tile256<false>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
+        hipLaunchKernelGGL((k_gemm_mx_tile256<false, OUT>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
                            b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
     rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
@@ -562,12 +627,25 @@ int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, cons
     return rc;
 }
 
+} // namespace
+
+int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
+                   const uint8_t *b_codes, const uint8_t *b_scales, void *C, int64_t ldc, int c_bf16, const uint16_t *Ag,
+                   const uint16_t *Bg, int kpad, void *workspace, hipStream_t st)
+{
+    if (c_bf16)
+        return launch_gemm_mx_t(M, N, K, a_codes, a_scales, b_codes, b_scales, static_cast<uint16_t *>(C), ldc, Ag, Bg,
+                                kpad, workspace, st);
+    return launch_gemm_mx_t(M, N, K, a_codes, a_scales, b_codes, b_scales, static_cast<float *>(C), ldc, Ag, Bg, kpad,
+                            workspace, st);
+}
+
 int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint16_t *Bg, int kpad, float *C,
                            int64_t ldc, hipStream_t st)
 {
     if (M == 0 || N == 0 || kpad == 0) return ADAHOP_OK;
     dim3 grid((unsigned)ceil_div(N, 128), (unsigned)ceil_div(M, 128));
-    hipLaunchKernelGGL((k_gemm_mx_generic<true>), grid, dim3(256), 0, st, M, N, (int64_t)0, nullptr, nullptr, nullptr,
+    hipLaunchKernelGGL((k_gemm_mx_generic<true, float>), grid, dim3(256), 0, st, M, N, (int64_t)0, nullptr, nullptr, nullptr,
                        nullptr, C, ldc, Ag, Bg, kpad);
     return check_launch();
 }

@@ -9,6 +9,8 @@
 // these places of C and the sum of Eq. 7 / 8 is a plain overwrite.
 #include "common.h"
 
+#include <type_traits>
+
 namespace adahop {
 
 namespace {
@@ -150,9 +152,10 @@ __global__ __launch_bounds__(256, 2) void k_oe_skinny(const uint16_t *__restrict
 }
 
 // C[idx[t], l] (ROWS) or C[l, idx[t]] = sum over the K slices of P[s][t][l], in slice order.
-template <bool ROWS>
+// C holds float, or bf16 as its 16 bits (rounded to nearest even from the fp32 sum).
+template <bool ROWS, typename OUT>
 __global__ __launch_bounds__(256) void k_oe_reduce(const float *__restrict__ P, int nslice, int64_t rows_all, int64_t Lo,
-                                                   const int32_t *__restrict__ idx, int k, float *__restrict__ C, int64_t ldc)
+                                                   const int32_t *__restrict__ idx, int k, OUT *__restrict__ C, int64_t ldc)
 {
     const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (g >= (int64_t)k * Lo) return;
@@ -160,10 +163,17 @@ __global__ __launch_bounds__(256) void k_oe_reduce(const float *__restrict__ P, 
     float s = 0.0f;
     for (int i = 0; i < nslice; ++i) s += P[((int64_t)i * rows_all + t) * Lo + l];
     const int64_t o = idx[t];
+    OUT v;
+    if constexpr (sizeof(OUT) == 4) {
+        v = s;
+    } else {
+        const uint32_t u = __float_as_uint(s);
+        v = (OUT)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    }
     if (ROWS)
-        C[o * ldc + l] = s;
+        C[o * ldc + l] = v;
     else
-        C[l * ldc + o] = s;
+        C[l * ldc + o] = v;
 }
 
 struct skinny_plan_t {
@@ -282,7 +292,7 @@ size_t oe_rowcol_workspace_bytes(int64_t M, int64_t N, int64_t K, int kind, int 
 }
 
 int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int kind, const int32_t *idx, int k,
-                     float *C, int64_t ldc, void *workspace, hipStream_t st)
+                     void *C, int64_t ldc, int c_bf16, void *workspace, hipStream_t st)
 {
     const int64_t M = A.outer, N = B.outer, K = A.K;
     if (k == 0 || M == 0 || N == 0) return ADAHOP_OK;
@@ -311,10 +321,19 @@ int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int k
     if (rc != ADAHOP_OK) return rc;
 
     const unsigned rblocks = (unsigned)ceil_div((int64_t)k * Lo, 256);
-    if (rows)
-        hipLaunchKernelGGL((k_oe_reduce<true>), dim3(rblocks), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx, k, C, ldc);
+    auto reduce = [&](auto *c) {
+        typedef typename std::remove_pointer<decltype(c)>::type out_t;
+        if (rows)
+            hipLaunchKernelGGL((k_oe_reduce<true, out_t>), dim3(rblocks), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx,
+                               k, c, ldc);
+        else
+            hipLaunchKernelGGL((k_oe_reduce<false, out_t>), dim3(rblocks), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx,
+                               k, c, ldc);
+    };
+    if (c_bf16)
+        reduce(static_cast<uint16_t *>(C));
     else
-        hipLaunchKernelGGL((k_oe_reduce<false>), dim3(rblocks), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx, k, C, ldc);
+        reduce(static_cast<float *>(C));
     return check_launch();
 }
 

@@ -107,6 +107,63 @@ def test_gemm_argument_and_workspace_checks():
     assert L.adahop_gemm_workspace_bytes(64, 32, 100, ah.ADAHOP_IHT, 0) == 0
 
 
+def test_gemm_mx_bf16out_rejects_bad_arguments():
+    L = ah.lib()
+    need = L.adahop_gemm_mx_workspace_bytes(64, 64, 128)
+    ok = [64, 64, 128, FAKE, FAKE, FAKE, FAKE, FAKE + 2, 64, FAKE, need, None]   # bf16 C: 2-byte alignment is enough
+    for pos, val in ((0, 0), (2, 48), (7, None), (7, FAKE + 1), (8, 63)):
+        a = list(ok)
+        a[pos] = val
+        assert L.adahop_gemm_mx_bf16out(*a) == ah.ADAHOP_E_INVALID_ARG, (pos, val)
+    a = list(ok)
+    a[10] = need - 1
+    assert L.adahop_gemm_mx_bf16out(*a) == ah.ADAHOP_E_WORKSPACE
+
+
+def test_pack_operand_argument_checks():
+    L = ah.lib()
+    x = op(64, 256)
+    f = lambda **kw: L.adahop_pack_operand(C.byref(kw.get("x", x)), kw.get("is_b", 0), kw.get("s", ah.ADAHOP_IHT),
+                                           kw.get("b", 64), kw.get("k", 0), kw.get("idx", None), kw.get("mask", None),
+                                           kw.get("codes", FAKE), kw.get("scales", FAKE), None)
+    assert f(x=op(K=100)) == ah.ADAHOP_E_INVALID_ARG
+    assert f(s=9) == ah.ADAHOP_E_INVALID_ARG
+    assert f(b=48) == ah.ADAHOP_E_INVALID_ARG
+    assert f(b=0) == ah.ADAHOP_E_INVALID_ARG
+    assert f(codes=None) == ah.ADAHOP_E_INVALID_ARG
+    assert f(codes=FAKE + 8) == ah.ADAHOP_E_INVALID_ARG
+    # the residual of A depends on the indices under OE_ROW and OE_K, that of B under OE_COL and OE_K
+    for s, is_b, dim in ((ah.ADAHOP_IHT_OE_ROW, 0, 64), (ah.ADAHOP_IHT_OE_COL, 1, 64), (ah.ADAHOP_IHT_OE_K, 0, 256),
+                         (ah.ADAHOP_IHT_OE_K, 1, 256)):
+        assert f(s=s, is_b=is_b, k=4, idx=None, mask=FAKE) == ah.ADAHOP_E_INVALID_ARG
+        assert f(s=s, is_b=is_b, k=4, idx=FAKE, mask=None) == ah.ADAHOP_E_INVALID_ARG
+        assert f(s=s, is_b=is_b, k=4, idx=FAKE, mask=FAKE + 4) == ah.ADAHOP_E_INVALID_ARG
+        assert f(s=s, is_b=is_b, k=dim + 1, idx=FAKE, mask=FAKE) == ah.ADAHOP_E_INVALID_ARG
+        assert f(s=s, is_b=is_b, k=-1, idx=FAKE, mask=FAKE) == ah.ADAHOP_E_INVALID_ARG
+
+
+def test_gemm_ex_argument_checks():
+    L = ah.lib()
+    A, B = op(64, 256), op(32, 256)
+    need = L.adahop_gemm_workspace_bytes(64, 32, 256, ah.ADAHOP_IHT_OE_K, 8)
+
+    def call(opts, s=ah.ADAHOP_IHT, k=0, given=0, c=FAKE, ldc=32, wsb=need):
+        o = None if opts is None else C.byref(ah.adahop_gemm_opts_t(*opts))
+        return L.adahop_gemm_ex(C.byref(A), C.byref(B), c, ldc, s, 64, k, FAKE, given, o, FAKE, wsb, None)
+
+    assert call(None, ldc=31) == ah.ADAHOP_E_INVALID_ARG                          # same checks as adahop_gemm
+    assert call((None, None, None, None, 2)) == ah.ADAHOP_E_INVALID_ARG           # c_bf16 is 0 or 1
+    assert call((None, None, None, None, 0), c=FAKE + 2) == ah.ADAHOP_E_INVALID_ARG   # float C: 4-byte aligned
+    assert call((FAKE, None, None, None, 0)) == ah.ADAHOP_E_INVALID_ARG           # codes without scales
+    assert call((None, None, None, FAKE, 0)) == ah.ADAHOP_E_INVALID_ARG
+    assert call((FAKE + 8, FAKE, None, None, 0)) == ah.ADAHOP_E_INVALID_ARG       # codes 16-byte aligned
+    # a packed operand whose residual depends on the indices needs the caller's indices
+    assert call((FAKE, FAKE, None, None, 0), s=ah.ADAHOP_IHT_OE_ROW, k=4) == ah.ADAHOP_E_INVALID_ARG
+    assert call((None, None, FAKE, FAKE, 0), s=ah.ADAHOP_IHT_OE_COL, k=4) == ah.ADAHOP_E_INVALID_ARG
+    assert call((None, None, FAKE, FAKE, 0), s=ah.ADAHOP_IHT_OE_K, k=4) == ah.ADAHOP_E_INVALID_ARG
+    assert call((FAKE, FAKE, FAKE, FAKE, 1), s=ah.ADAHOP_IHT_OE_K, k=8, given=1, wsb=need - 1) == ah.ADAHOP_E_WORKSPACE
+
+
 def test_oe_gemm_argument_checks():
     L = ah.lib()
     A, B = op(64, 256), op(32, 256)

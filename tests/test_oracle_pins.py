@@ -530,3 +530,33 @@ def test_pattern_iid_gives_unit_normalised_cv_and_planted_outliers_are_found():
     assert p == orc.PATTERN_OUTER
     p, _ = orc.detect_pattern(inputs.matrix(512, 1024, 1.0, 79, col_outliers=(8, 50.0, 50.0)), True)
     assert p == orc.PATTERN_K
+
+
+# ----------------------------------------------------------------------------- bf16 rounding of C
+
+def test_round_to_bf16_matches_the_library_conversion_on_fp32_values():
+    """Pin: for values that already are fp32 numbers a single rounding to bf16 is what torch's CPU conversion
+    does (an independent library routine); covers normals, bf16-subnormals, both signs, overflow."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(123)
+    x = (rng.standard_normal(400000) * np.exp(rng.uniform(-88.0, 88.0, 400000))).astype(np.float32)
+    x = np.concatenate([x, np.float32([0.0, -0.0, 3.4e38, -3.4e38, 1e-40, -1e-40, 2.0 ** -133, 2.0 ** -134])])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(orc.round_to_bf16(x.astype(np.float64)), want)
+    assert np.array_equal(orc.bf16_to_double(want[np.isfinite(x)]),
+                          torch.from_numpy(want[np.isfinite(x)].view(np.int16)).view(torch.bfloat16).double().numpy())
+
+
+def test_round_to_bf16_ties_and_single_rounding():
+    """Pin from the format's definition: the midpoint of two neighbouring bf16 numbers goes to the one with the
+    even significand, for every positive finite pair; a double just above a midpoint goes up although an fp32
+    intermediate would land on the midpoint and go down."""
+    b = np.arange(0, 0x7f7f, dtype=np.uint32)
+    lo = (b << 16).view(np.float32).astype(np.float64)
+    hi = ((b + 1) << 16).view(np.float32).astype(np.float64)
+    want = np.where(b % 2 == 0, b, b + 1).astype(np.uint16)
+    assert np.array_equal(orc.round_to_bf16((lo + hi) / 2), want)
+    assert np.array_equal(orc.round_to_bf16(-(lo + hi) / 2), want | 0x8000)
+    assert orc.round_to_bf16(np.array([1 + 2.0 ** -8]))[0] == 0x3f80
+    assert orc.round_to_bf16(np.array([1 + 2.0 ** -8 + 2.0 ** -40]))[0] == 0x3f81
+    assert orc.round_to_bf16(np.array([1 + 3 * 2.0 ** -8]))[0] == 0x3f82
