@@ -13,6 +13,8 @@
  *   - Outlier Extraction: residual + extracted part, OE-Left / OE-Right       (paper Eq. 7-8,
  *     App. E "OE formulation"); the K-channel form is the same split applied to K indices
  *   - FOID: variance over the first 64 elements, top-r by variance           (App. F item 1)
+ *   - Outer Hadamard Transform, the comparison strategy: block transform along the OUTER
+ *     index of each operand before quantisation, inverse rotations of C afterwards  (paper Eq. 6)
  *   - MXFP4: OCP Microscaling v1.0 -- E2M1 elements, one E8M0 scale per 32 elements along K,
  *     scale = 2^(floor(log2 amax) - 2), round-to-nearest-even, saturate to +-6.  The paper only
  *     names the format; these rules are the published OCP ones.
@@ -254,6 +256,43 @@ void orc_iht_quantize(const uint16_t *data, int64_t outer, int64_t K, int64_t ld
         }
         free(row);
     }
+}
+
+/* ------------------------------------------------------------------ OHT (Eq. 6), operand side */
+
+/* The fp32 values that get quantised under the Outer Hadamard Transform: H_m A for the A operand,
+ * (B H_n)^T = H_n B^T for B given as [N, K] -- in both cases the block transform runs along the
+ * OUTER index: for every K index, every block of b consecutive outer indices is multiplied by the
+ * normalised Sylvester matrix (same butterflies, same rounding order as the inner transform).
+ * outer % b == 0.  out is [outer, K] row-major. */
+void orc_oht_transform(const uint16_t *data, int64_t outer, int64_t K, int64_t ld, int k_contig, int b, float *out)
+{
+#pragma omp parallel
+    {
+        float *col = (float *)malloc((size_t)b * sizeof *col);
+#pragma omp for schedule(static)
+        for (int64_t kk = 0; kk < K; ++kk) {
+            for (int64_t o0 = 0; o0 < outer; o0 += b) {
+                for (int i = 0; i < b; ++i) col[i] = op_at(data, ld, k_contig, o0 + i, kk);
+                orc_fwht(col, b);
+                for (int i = 0; i < b; ++i) out[(o0 + i) * K + kk] = col[i];
+            }
+        }
+        free(col);
+    }
+}
+
+/* OHT-transformed operand -> MXFP4, MX blocks along K as everywhere (codes [outer, K/2], scales [outer, K/32]). */
+void orc_oht_quantize(const uint16_t *data, int64_t outer, int64_t K, int64_t ld, int k_contig, int b,
+                      uint8_t *codes, uint8_t *scales)
+{
+    float *t = (float *)malloc((size_t)outer * (size_t)K * sizeof *t);
+    orc_oht_transform(data, outer, K, ld, k_contig, b, t);
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < outer; ++o)
+        for (int64_t blk = 0; blk < K / 32; ++blk)
+            orc_mx_quantize_block(t + o * K + 32 * blk, codes + o * (K / 2) + 16 * blk, scales + o * (K / 32) + blk);
+    free(t);
 }
 
 /* ------------------------------------------------------------------ GEMMs in double */

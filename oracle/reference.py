@@ -215,6 +215,57 @@ def adahop_gemm(a_bits, a_k_contig, b_bits, b_k_contig, strategy, iht_block, k=0
     return dict(C=Cm, a_codes=a_codes, a_scales=a_scales, b_codes=b_codes, b_scales=b_scales, idx=sel)
 
 
+# ------------------------------------------------------------------------------------------------
+# Outer Hadamard Transform (paper Eq. 6): the comparison strategy
+# ------------------------------------------------------------------------------------------------
+def hadamard_matrix(b):
+    """Normalised Sylvester Hadamard matrix H_b (float64), by the doubling recursion H_2n = [[H, H], [H, -H]]."""
+    H = np.ones((1, 1))
+    while H.shape[0] < b:
+        H = np.block([[H, H], [H, -H]])
+    assert H.shape[0] == b, "b must be a power of two"
+    return H / np.sqrt(float(b))
+
+
+def oht_transform(bits, k_contig, block):
+    """fp32 values that enter the quantiser under OHT: block transform along the OUTER index (H_m A; H_n B^T)."""
+    bits, outer, K, ld = _operand(bits, k_contig)
+    assert outer % block == 0
+    out = np.empty((outer, K), dtype=np.float32)
+    lib().orc_oht_transform(_p(bits), _i64(outer), _i64(K), _i64(ld), C.c_int(int(k_contig)), C.c_int(block), _p(out))
+    return out
+
+
+def oht_quantize(bits, k_contig, block):
+    bits, outer, K, ld = _operand(bits, k_contig)
+    assert K % 32 == 0 and outer % block == 0
+    codes = np.empty((outer, K // 2), dtype=np.uint8)
+    scales = np.empty((outer, K // 32), dtype=np.uint8)
+    lib().orc_oht_quantize(_p(bits), _i64(outer), _i64(K), _i64(ld), C.c_int(int(k_contig)), C.c_int(block),
+                           _p(codes), _p(scales))
+    return codes, scales
+
+
+def oht_inverse(Cq, block_m, block_n):
+    """H_m^T Cq H_n^T with block-diagonal H (Eq. 6, the rotations after the product), in double, written as the
+    two matrix products they are."""
+    M, N = Cq.shape
+    assert M % block_m == 0 and N % block_n == 0
+    Hm = np.kron(np.eye(M // block_m), hadamard_matrix(block_m))
+    Hn = np.kron(np.eye(N // block_n), hadamard_matrix(block_n))
+    return Hm.T @ np.asarray(Cq, dtype=np.float64) @ Hn.T
+
+
+def oht_gemm(a_bits, a_k_contig, b_bits, b_k_contig, block):
+    """C_OHT = H_m^T ( Q(H_m A) Q(B H_n) ) H_n^T (Eq. 6) with block-diagonal transforms of size `block` on both
+    outer dimensions.  Returns dict(C, a_codes, a_scales, b_codes, b_scales)."""
+    a_codes, a_scales = oht_quantize(a_bits, a_k_contig, block)
+    b_codes, b_scales = oht_quantize(b_bits, b_k_contig, block)
+    Cq = mx_gemm(a_codes, a_scales, b_codes, b_scales)
+    return dict(C=oht_inverse(Cq, block, block), Cq=Cq, a_codes=a_codes, a_scales=a_scales, b_codes=b_codes,
+                b_scales=b_scales)
+
+
 def round_to_bf16(x):
     """bf16 bit patterns (uint16) of a float64 array: each value rounded ONCE to the nearest number with an
     8-bit significand (exponent range of fp32, gradual underflow), ties to the even significand.

@@ -560,3 +560,107 @@ def test_round_to_bf16_ties_and_single_rounding():
     assert orc.round_to_bf16(np.array([1 + 2.0 ** -8]))[0] == 0x3f80
     assert orc.round_to_bf16(np.array([1 + 2.0 ** -8 + 2.0 ** -40]))[0] == 0x3f81
     assert orc.round_to_bf16(np.array([1 + 3 * 2.0 ** -8]))[0] == 0x3f82
+
+
+# ----------------------------------------------------------------------------- Outer Hadamard Transform (Eq. 6)
+
+@pytest.mark.parametrize("b", [32, 64, 128])
+def test_oht_hadamard_matrix_is_the_library_sylvester_matrix(b):
+    """Pin: scipy's Hadamard construction (a library routine) and exact orthogonality in integers."""
+    import scipy.linalg
+    H = orc.hadamard_matrix(b)
+    assert np.array_equal(np.rint(H * np.sqrt(b)).astype(np.int64), scipy.linalg.hadamard(b))
+    assert np.array_equal(sylvester(b) @ sylvester(b).T, b * np.eye(b, dtype=np.int64))
+    assert np.allclose(H @ H.T, np.eye(b), atol=1e-14)
+
+
+@pytest.mark.parametrize("b", [32, 64, 128])
+def test_oht_transform_is_left_multiplication_by_block_hadamard(b):
+    """H_m A mixes along the OUTER index (Lemma on mixing directions): compare with the explicit double
+    product (I kron H_b) X built from scipy's matrix, and check that the storage order does not matter."""
+    import scipy.linalg
+    rng = np.random.default_rng(b)
+    x = rng.standard_normal((2 * b, 96)).astype(np.float32)
+    bits = bf16_bits(x)
+    got = orc.oht_transform(bits, True, b)
+    Hb = scipy.linalg.hadamard(b) / np.sqrt(b)
+    want = np.kron(np.eye(2), Hb) @ bits_to_f64(bits)
+    assert np.abs(got - want).max() <= 4e-7 * np.log2(b) * np.abs(want).max()
+    assert np.array_equal(orc.oht_transform(np.ascontiguousarray(bits.T), False, b), got)
+    # not the inner transform: a matrix that is constant along K and varies along outer must change
+    ramp = bf16_bits(np.repeat(np.arange(2 * b, dtype=np.float32)[:, None], 32, axis=1))
+    assert not np.array_equal(orc.oht_transform(ramp, True, b), bits_to_f64(ramp).astype(np.float32))
+    assert np.array_equal(orc.transform(ramp, True, 32)[:, 1:], np.zeros((2 * b, 31), np.float32))
+
+
+def test_oht_spreads_one_outlier_row_over_its_block_exactly():
+    """Closed form for b = 64 (normalisation 1/8, exact): A zero except row r = u  =>  every row o of r's block
+    becomes H[o, r] u / 8, rows of other blocks stay zero."""
+    b, r = 64, 70
+    u = bits_to_f64(bf16_bits(np.random.default_rng(1).standard_normal(64).astype(np.float32) * 40))
+    x = np.zeros((3 * b, 64), dtype=np.float32)
+    x[r] = u
+    got = orc.oht_transform(bf16_bits(x), True, b).astype(np.float64)
+    H = sylvester(b)
+    want = np.zeros_like(got)
+    want[b:2 * b] = H[:, r - b][:, None] * u[None, :] / 8.0
+    assert np.array_equal(got, want)
+
+
+def test_oht_identity_without_quantisation():
+    """Eq. 6 with Q = identity: H_m^T (H_m A)(B H_n) H_n^T = A B (fp32 butterflies on the operand side)."""
+    rng = np.random.default_rng(7)
+    a = bf16_bits(rng.standard_normal((128, 160)).astype(np.float32))
+    bt = bf16_bits((rng.standard_normal((64, 160)) * 0.02).astype(np.float32))
+    for b in (32, 64):
+        Ta = orc.oht_transform(a, True, b).astype(np.float64)
+        Tb = orc.oht_transform(np.ascontiguousarray(bt.T), False, b).astype(np.float64)
+        C = orc.oht_inverse(Ta @ Tb.T, b, b)
+        exact = bits_to_f64(a) @ bits_to_f64(bt).T
+        assert np.linalg.norm(C - exact) <= 1e-5 * np.linalg.norm(exact)
+    # the inverse is a two-sided rotation: one side alone does not restore the product
+    one_sided = np.kron(np.eye(128 // 64), orc.hadamard_matrix(64)).T @ (Ta @ Tb.T)
+    assert np.linalg.norm(one_sided - exact) > 0.1 * np.linalg.norm(exact)
+
+
+def test_oht_inverse_against_direct_sums():
+    """Brute force on a tiny case: C[i, j] = sum_p sum_q H[p, i] Cq[p, q] H[q, j] within each block pair."""
+    rng = np.random.default_rng(9)
+    Cq = rng.standard_normal((64, 32))
+    H = sylvester(32) / np.sqrt(32.0)
+    want = np.zeros_like(Cq)
+    for bi in range(2):
+        blk = Cq[32 * bi:32 * bi + 32]
+        for i in range(32):
+            for j in range(32):
+                want[32 * bi + i, j] = sum(H[p, i] * blk[p, q] * H[q, j] for p in range(32) for q in range(32))
+    assert np.allclose(orc.oht_inverse(Cq, 32, 32), want, atol=1e-12)
+
+
+def test_oht_quantize_closed_form_and_whole_strategy(golden_dir):
+    """Columns of a 64-row block equal to c * (column i of the +-1 Sylvester matrix) transform to 8 c at row i and
+    0 elsewhere (b = 64: integer butterflies, exact normalisation), so the packed operand is known in closed form:
+    row i of the block holds 8 c along K, every other row is all-zero codes with scale code 0.  Then the whole
+    strategy on such operands is exact: C_OHT = A B."""
+    table = e2m1_table(golden_dir)
+    b, K = 64, 64
+    H = sylvester(b)
+    cs = np.array([0.5, 0.25, 0.125, 0.0625] * (K // 4))           # 8c in {4, 2, 1, 0.5}: E2M1 values, amax 4
+    hot = [5, 40]                                                  # hot row of block 0 / block 1
+    x = np.zeros((2 * b, K), dtype=np.float32)
+    for blk, i in enumerate(hot):
+        x[blk * b:(blk + 1) * b] = H[:, i][:, None] * cs[None, :]
+    bits = bf16_bits(x)
+    codes, scales = orc.oht_quantize(bits, True, b)
+    dq = dequant(codes, scales, table)
+    want = np.zeros((2 * b, K))
+    for blk, i in enumerate(hot):
+        want[blk * b + i] = 8.0 * cs
+    assert np.array_equal(dq, want)
+    hot_rows = [blk * b + i for blk, i in enumerate(hot)]
+    assert np.all(scales[hot_rows] == 127) and np.all(np.delete(scales, hot_rows, axis=0) == 0)
+    assert np.all(np.delete(codes, hot_rows, axis=0) == 0)
+    # whole strategy: both operands of this kind -> every quantisation is exact -> Eq. 6 returns A B
+    out = orc.oht_gemm(bits, True, bits[:b], True, b)
+    exact = bits_to_f64(bits) @ bits_to_f64(bits[:b]).T
+    assert np.allclose(out["C"], exact, rtol=0, atol=1e-12 * np.abs(exact).max())
