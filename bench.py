@@ -226,6 +226,21 @@ def main():
             extras["b_operand_packed_once"] = {"gemms": sorted(packed_b), "step_ms": r_ms,
                                                "step_tflops": total_flops / r_ms / 1e9}
         del packed_b, c16
+        # the comparison strategy of Eq. 6 on the largest product: outer transforms (block 128) + rotations of C
+        if big.M % 128 == 0 and big.N % 128 == 0:
+            def run_oht():
+                ah.adahop_gemm(big.A, big.B, inputs.OHT, 128, Cout=big.C, workspace=ws)
+            t_oht = time_ms(torch, run_oht, 5)
+            t_inv = time_ms(torch, lambda: ah.adahop_oht_inverse(big.C, 128), 5)
+            qa = torch.empty((big.A.outer, big.K // 2), dtype=torch.uint8, device="cuda")
+            qs = torch.empty((big.A.outer, big.K // 32), dtype=torch.uint8, device="cuda")
+            t_q = time_ms(torch, lambda: ah.adahop_oht_quantize(big.A, 128, qa, qs), 5)
+            extras["oht_comparison"] = {"shape": [big.M, big.N, big.K], "block": 128, "pipeline_ms": t_oht,
+                                        "tflops": big.flops / t_oht / 1e9, "inverse_rotations_ms": t_inv,
+                                        "inverse_GBps": 8.0 * big.M * big.N / (t_inv * 1e-3) / 1e9,
+                                        "quantize_a_ms": t_q,
+                                        "quantize_a_GBps": 2.53125 * big.A.outer * big.K / (t_q * 1e-3) / 1e9}
+            del qa, qs
         # what the matrix cores sustain with no memory traffic at all (register-only loop, 256 workgroups)
         sink = torch.zeros(1, dtype=torch.float32, device="cuda")
         probe = {}

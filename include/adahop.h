@@ -44,7 +44,8 @@ typedef enum {
     ADAHOP_IHT = 1,        /* C = Q(A H) Q(H^T B)                             (Eq. 5)            */
     ADAHOP_IHT_OE_ROW = 2, /* OE-Left : top-k rows of A in BF16              (Eq. 7)            */
     ADAHOP_IHT_OE_COL = 3, /* OE-Right: top-k columns of B in BF16           (Eq. 8)            */
-    ADAHOP_IHT_OE_K = 4    /* top-k K-channels (of A) in BF16, removed from both residuals       */
+    ADAHOP_IHT_OE_K = 4,   /* top-k K-channels (of A) in BF16, removed from both residuals       */
+    ADAHOP_OHT = 5         /* C = H^T ( Q(H A) Q(B H) ) H^T, outer transforms (Eq. 6): comparison */
 } adahop_strategy_t;
 
 /* A bf16 matrix operand, logical shape [outer, K].
@@ -150,6 +151,22 @@ size_t adahop_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, adahop_strat
 int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, int64_t ldc,
                 adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Outer Hadamard Transform (paper Eq. 6), the strategy the paper compares against:
+ *     C_OHT = H_m^T ( Q(H_m A) Q(B H_n) ) H_n^T
+ * with block-diagonal normalised Sylvester matrices of size oht_block in {32, 64, 128} on both outer
+ * dimensions (same butterfly order and rounding as the inner transform).
+ *   adahop_oht_quantize: operand x, logical [outer, K], outer % oht_block == 0: every block of oht_block
+ *     consecutive OUTER indices is transformed for every K index (H_m A for A; H_n B^T for B given as
+ *     [N, K]), then rows are quantised along K to canonical codes [outer, K/2] / scales [outer, K/32].
+ *   adahop_oht_inverse: C (float [M, ldc], M % oht_block == 0, N % oht_block == 0) <- H^T C H^T in place.
+ * adahop_gemm / adahop_gemm_ex with strategy ADAHOP_OHT run both operands through adahop_oht_quantize,
+ * the MXFP4 product and adahop_oht_inverse; iht_block is then the OHT block, k is ignored, C must be
+ * float (c_bf16 = 0) and M, N multiples of the block: INVALID_ARG otherwise.
+ * ------------------------------------------------------------------------------------------- */
+int adahop_oht_quantize(const adahop_operand_t *x, int oht_block, uint8_t *codes, uint8_t *scales, void *stream);
+int adahop_oht_inverse(float *C, int64_t M, int64_t N, int64_t ldc, int oht_block, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Quantise-once operand reuse and bf16 output (the paper's layers share operands between products:

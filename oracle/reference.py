@@ -18,7 +18,7 @@ import numpy as np
 
 from . import build as _build
 
-NONE, IHT, IHT_OE_ROW, IHT_OE_COL, IHT_OE_K = range(5)
+NONE, IHT, IHT_OE_ROW, IHT_OE_COL, IHT_OE_K, OHT = range(6)
 
 _lib = None
 

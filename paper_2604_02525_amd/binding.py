@@ -13,12 +13,13 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libadahop.so")
 
-ADAHOP_NONE, ADAHOP_IHT, ADAHOP_IHT_OE_ROW, ADAHOP_IHT_OE_COL, ADAHOP_IHT_OE_K = range(5)
+ADAHOP_NONE, ADAHOP_IHT, ADAHOP_IHT_OE_ROW, ADAHOP_IHT_OE_COL, ADAHOP_IHT_OE_K, ADAHOP_OHT = range(6)
 ADAHOP_OK, ADAHOP_E_INVALID_ARG, ADAHOP_E_WORKSPACE, ADAHOP_E_HIP = 0, -1, -2, -3
 ADAHOP_PATTERN_NONE, ADAHOP_PATTERN_OUTER, ADAHOP_PATTERN_K = range(3)
 
 EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_gemm_mx",
            "adahop_gemm_mx_bf16out", "adahop_gemm_mx_workspace_bytes", "adahop_pack_operand", "adahop_gemm_ex",
+           "adahop_oht_quantize", "adahop_oht_inverse",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
            "adahop_oe_gemm_bf16", "adahop_detect_pattern_workspace_bytes", "adahop_detect_pattern",
            "adahop_select_strategy", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
@@ -68,6 +69,8 @@ def lib():
         L.adahop_gemm_mx_bf16out.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P, SZ, P]
         L.adahop_pack_operand.argtypes = [OP, I, I, I, I, P, P, P, P, P]
         L.adahop_gemm_ex.argtypes = [OP, OP, P, I64, I, I, I, P, I, C.POINTER(adahop_gemm_opts_t), P, SZ, P]
+        L.adahop_oht_quantize.argtypes = [OP, I, P, P, P]
+        L.adahop_oht_inverse.argtypes = [P, I64, I64, I64, I, P]
         L.adahop_gemm_mx_workspace_bytes.argtypes = [I64, I64, I64]
         L.adahop_gemm_mx_workspace_bytes.restype = SZ
         L.adahop_gemm_workspace_layout.argtypes = [I64, I64, I64, I, I, C.POINTER(adahop_ws_layout_t)]
@@ -188,6 +191,24 @@ def adahop_gemm_workspace_layout(M, N, K, strategy, k):
 
 def adahop_gemm_workspace_bytes(M, N, K, strategy, k):
     return int(lib().adahop_gemm_workspace_bytes(M, N, K, strategy, k))
+
+
+def adahop_oht_quantize(x, oht_block, codes=None, scales=None, stream=None):
+    """Block Hadamard transform along the OUTER index, then MXFP4 along K (operand side of paper Eq. 6)."""
+    dev = x.tensor.device
+    codes = _u8((x.outer, x.K // 2), dev) if codes is None else codes
+    scales = _u8((x.outer, x.K // 32), dev) if scales is None else scales
+    _check(lib().adahop_oht_quantize(C.byref(x.c()), oht_block, _ptr(codes), _ptr(scales), _stream(stream)),
+           "adahop_oht_quantize")
+    return codes, scales
+
+
+def adahop_oht_inverse(Cmat, oht_block, stream=None):
+    """Cmat (float32 [M, N], row stride ld) <- H^T Cmat H^T in place (the rotations after the product, Eq. 6)."""
+    assert Cmat.dtype == torch.float32 and Cmat.dim() == 2 and Cmat.stride(1) == 1
+    _check(lib().adahop_oht_inverse(_ptr(Cmat), Cmat.shape[0], Cmat.shape[1], Cmat.stride(0), oht_block,
+                                    _stream(stream)), "adahop_oht_inverse")
+    return Cmat
 
 
 def adahop_pack_operand(x, is_b, strategy, iht_block, k=0, idx=None, codes=None, scales=None, stream=None):

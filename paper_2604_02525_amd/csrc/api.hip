@@ -32,6 +32,7 @@ static int extracted_dim(adahop_strategy_t s, int64_t M, int64_t N, int64_t K, i
 {
     switch (s) {
     case ADAHOP_NONE:
+    case ADAHOP_OHT:
     case ADAHOP_IHT: *dim = 0; return ADAHOP_OK;
     case ADAHOP_IHT_OE_ROW: *dim = M; return ADAHOP_OK;
     case ADAHOP_IHT_OE_COL: *dim = N; return ADAHOP_OK;
@@ -250,11 +251,15 @@ int adahop_pack_operand(const adahop_operand_t *x, int is_b, adahop_strategy_t s
 {
     int rc = validate_operand(x);
     if (rc != ADAHOP_OK) return rc;
-    if (strategy < ADAHOP_NONE || strategy > ADAHOP_IHT_OE_K) return ADAHOP_E_INVALID_ARG;
+    if (strategy < ADAHOP_NONE || strategy > ADAHOP_OHT) return ADAHOP_E_INVALID_ARG;
+    if (!codes || !scales || !aligned(codes, 16)) return ADAHOP_E_INVALID_ARG;
+    if (strategy == ADAHOP_OHT) {
+        if (!valid_oht_block(iht_block) || x->outer % iht_block != 0) return ADAHOP_E_INVALID_ARG;
+        return launch_oht_quantize(*x, iht_block, codes, scales, static_cast<hipStream_t>(stream));
+    }
     const int b = strategy == ADAHOP_NONE ? 0 : iht_block;
     if (!valid_iht_block(b) || (b > 0 && x->K % b != 0)) return ADAHOP_E_INVALID_ARG;
     if (strategy != ADAHOP_NONE && b == 0) return ADAHOP_E_INVALID_ARG;
-    if (!codes || !scales || !aligned(codes, 16)) return ADAHOP_E_INVALID_ARG;
     const int kind = residual_mask_kind(strategy, is_b != 0);
     const int64_t dim = kind == 1 ? x->outer : x->K;
     const bool masked = kind != 0 && k != 0;
@@ -268,6 +273,22 @@ int adahop_pack_operand(const adahop_operand_t *x, int is_b, adahop_strategy_t s
                                codes, scales, st);
 }
 
+int adahop_oht_quantize(const adahop_operand_t *x, int oht_block, uint8_t *codes, uint8_t *scales, void *stream)
+{
+    int rc = validate_operand(x);
+    if (rc != ADAHOP_OK) return rc;
+    if (!valid_oht_block(oht_block) || x->outer % oht_block != 0) return ADAHOP_E_INVALID_ARG;
+    if (!codes || !scales || !aligned(codes, 16)) return ADAHOP_E_INVALID_ARG;
+    return launch_oht_quantize(*x, oht_block, codes, scales, static_cast<hipStream_t>(stream));
+}
+
+int adahop_oht_inverse(float *C, int64_t M, int64_t N, int64_t ldc, int oht_block, void *stream)
+{
+    if (!C || !aligned(C, 4) || M < 1 || N < 1 || M > MAX_OUTER || N > MAX_OUTER || ldc < N) return ADAHOP_E_INVALID_ARG;
+    if (!valid_oht_block(oht_block) || M % oht_block != 0 || N % oht_block != 0) return ADAHOP_E_INVALID_ARG;
+    return launch_oht_inverse(C, M, N, ldc, oht_block, static_cast<hipStream_t>(stream));
+}
+
 static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B, void *C, int64_t ldc,
                            adahop_strategy_t strategy, int iht_block, int k, int32_t *idx_inout, int use_given_idx,
                            const adahop_gemm_opts_t *opts, void *workspace, size_t workspace_bytes, void *stream)
@@ -279,9 +300,14 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
     const int64_t M = A->outer, N = B->outer, K = A->K;
     int64_t dim = 0;
     if (extracted_dim(strategy, M, N, K, &dim) != ADAHOP_OK) return ADAHOP_E_INVALID_ARG;
+    const bool oht = strategy == ADAHOP_OHT;
     const int b = strategy == ADAHOP_NONE ? 0 : iht_block;
-    if (!valid_iht_block(b) || (b > 0 && K % b != 0)) return ADAHOP_E_INVALID_ARG;
-    if (strategy != ADAHOP_NONE && b == 0) return ADAHOP_E_INVALID_ARG;
+    if (oht) {
+        if (!valid_oht_block(b) || M % b != 0 || N % b != 0 || c_bf16) return ADAHOP_E_INVALID_ARG;
+    } else {
+        if (!valid_iht_block(b) || (b > 0 && K % b != 0)) return ADAHOP_E_INVALID_ARG;
+        if (strategy != ADAHOP_NONE && b == 0) return ADAHOP_E_INVALID_ARG;
+    }
     if (k < 0 || (dim > 0 && k > dim)) return ADAHOP_E_INVALID_ARG;
     const bool oe = dim > 0 && k > 0;
     if (oe && !idx_inout) return ADAHOP_E_INVALID_ARG;
@@ -322,13 +348,15 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
     const uint8_t *b_codes = b_given ? opts->b_codes : reinterpret_cast<uint8_t *>(ws + L.b_codes);
     const uint8_t *b_scales = b_given ? opts->b_scales : reinterpret_cast<uint8_t *>(ws + L.b_scales);
     if (!a_given) {
-        rc = launch_iht_quantize(*A, b, a_kind == 1 ? mask : nullptr, a_kind == 2 ? mask : nullptr,
-                                 reinterpret_cast<uint8_t *>(ws + L.a_codes), reinterpret_cast<uint8_t *>(ws + L.a_scales), st);
+        uint8_t *c = reinterpret_cast<uint8_t *>(ws + L.a_codes), *s = reinterpret_cast<uint8_t *>(ws + L.a_scales);
+        rc = oht ? launch_oht_quantize(*A, b, c, s, st)
+                 : launch_iht_quantize(*A, b, a_kind == 1 ? mask : nullptr, a_kind == 2 ? mask : nullptr, c, s, st);
         if (rc != ADAHOP_OK) return rc;
     }
     if (!b_given) {
-        rc = launch_iht_quantize(*B, b, b_kind == 1 ? mask : nullptr, b_kind == 2 ? mask : nullptr,
-                                 reinterpret_cast<uint8_t *>(ws + L.b_codes), reinterpret_cast<uint8_t *>(ws + L.b_scales), st);
+        uint8_t *c = reinterpret_cast<uint8_t *>(ws + L.b_codes), *s = reinterpret_cast<uint8_t *>(ws + L.b_scales);
+        rc = oht ? launch_oht_quantize(*B, b, c, s, st)
+                 : launch_iht_quantize(*B, b, b_kind == 1 ? mask : nullptr, b_kind == 2 ? mask : nullptr, c, s, st);
         if (rc != ADAHOP_OK) return rc;
     }
     // 3. MXFP4 product, with the K-channel BF16 product fused in front; 4. row / column BF16 product
@@ -343,6 +371,7 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
     }
     rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, nullptr, nullptr, 0, ws + L.gemm, st);
     if (rc != ADAHOP_OK) return rc;
+    if (oht) return launch_oht_inverse(static_cast<float *>(C), M, N, ldc, b, st); // the rotations after the product (Eq. 6)
     if (oe) rc = launch_oe_rowcol(*A, *B, strategy, idx_inout, k, C, ldc, c_bf16, ws + L.gather_a, st);
     return rc;
 }

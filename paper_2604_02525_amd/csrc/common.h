@@ -45,6 +45,11 @@ int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int k
 int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint16_t *Bg, int kpad, float *C,
                            int64_t ldc, hipStream_t st);
 
+// Outer Hadamard Transform strategy (paper Eq. 6): operand side and the rotations of C after the product.
+bool valid_oht_block(int b);
+int launch_oht_quantize(const adahop_operand_t &x, int b, uint8_t *codes, uint8_t *scales, hipStream_t st);
+int launch_oht_inverse(float *C, int64_t M, int64_t N, int64_t ldc, int b, hipStream_t st);
+
 size_t pattern_workspace_bytes(const adahop_operand_t &x);
 int launch_detect_pattern(const adahop_operand_t &x, double tau, double eps, int32_t *pattern_out, double *stats_out,
                           void *workspace, hipStream_t st);

@@ -20,8 +20,9 @@ import math
 import numpy as np
 import torch
 
-NONE, IHT, IHT_OE_ROW, IHT_OE_COL, IHT_OE_K = range(5)
-STRATEGY_NAMES = {NONE: "none", IHT: "iht", IHT_OE_ROW: "iht+oe-row", IHT_OE_COL: "iht+oe-col", IHT_OE_K: "iht+oe-k"}
+NONE, IHT, IHT_OE_ROW, IHT_OE_COL, IHT_OE_K, OHT = range(6)
+STRATEGY_NAMES = {NONE: "none", IHT: "iht", IHT_OE_ROW: "iht+oe-row", IHT_OE_COL: "iht+oe-col", IHT_OE_K: "iht+oe-k",
+                  OHT: "oht"}
 
 
 @dataclass

@@ -164,6 +164,35 @@ def test_gemm_ex_argument_checks():
     assert call((FAKE, FAKE, FAKE, FAKE, 1), s=ah.ADAHOP_IHT_OE_K, k=8, given=1, wsb=need - 1) == ah.ADAHOP_E_WORKSPACE
 
 
+def test_oht_argument_checks():
+    L = ah.lib()
+    x = op(64, 128)
+    for b in (0, 16, 48, 256):
+        assert L.adahop_oht_quantize(C.byref(x), b, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_oht_quantize(C.byref(op(96, 128)), 64, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG   # 96 % 64
+    assert L.adahop_oht_quantize(C.byref(x), 32, None, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_oht_quantize(C.byref(x), 32, FAKE + 8, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_oht_quantize(C.byref(op(K=100)), 32, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    inv = lambda c=FAKE, M=64, N=64, ldc=64, b=32: L.adahop_oht_inverse(c, M, N, ldc, b, None)
+    assert inv(c=None) == ah.ADAHOP_E_INVALID_ARG
+    assert inv(c=FAKE + 2) == ah.ADAHOP_E_INVALID_ARG
+    assert inv(M=48) == ah.ADAHOP_E_INVALID_ARG
+    assert inv(N=80) == ah.ADAHOP_E_INVALID_ARG
+    assert inv(ldc=63) == ah.ADAHOP_E_INVALID_ARG
+    assert inv(b=256) == ah.ADAHOP_E_INVALID_ARG
+    assert inv(M=0) == ah.ADAHOP_E_INVALID_ARG
+    # whole path: block, divisibility of M and N, float C only
+    A, B = op(64, 256), op(96, 256)
+    need = L.adahop_gemm_workspace_bytes(64, 96, 256, ah.ADAHOP_OHT, 0)
+    assert need > 0
+    g = lambda b, opts=None: L.adahop_gemm_ex(C.byref(A), C.byref(B), FAKE, 96, ah.ADAHOP_OHT, b, 0, None, 0,
+                                              None if opts is None else C.byref(ah.adahop_gemm_opts_t(*opts)), FAKE, need,
+                                              None)
+    assert g(64) == ah.ADAHOP_E_INVALID_ARG            # 96 % 64
+    assert g(256) == ah.ADAHOP_E_INVALID_ARG
+    assert g(32, (None, None, None, None, 1)) == ah.ADAHOP_E_INVALID_ARG
+
+
 def test_oe_gemm_argument_checks():
     L = ah.lib()
     A, B = op(64, 256), op(32, 256)
