@@ -15,6 +15,10 @@
  *   - FOID: variance over the first 64 elements, top-r by variance           (App. F item 1)
  *   - Outer Hadamard Transform, the comparison strategy: block transform along the OUTER
  *     index of each operand before quantisation, inverse rotations of C afterwards  (paper Eq. 6)
+ *   - optional stochastic rounding of the elements (the paper cites it as prior work for unbiased
+ *     gradient quantisation, Sec. 2.1-2.2): between the two neighbouring E2M1 values with probability
+ *     proportional to the distance, random bits from Philox4x32-10 keyed by a seed and counted by the
+ *     element's (row, K) position
  *   - MXFP4: OCP Microscaling v1.0 -- E2M1 elements, one E8M0 scale per 32 elements along K,
  *     scale = 2^(floor(log2 amax) - 2), round-to-nearest-even, saturate to +-6.  The paper only
  *     names the format; these rules are the published OCP ones.
@@ -208,6 +212,60 @@ void orc_mx_quantize_block(const float *v, uint8_t *codes, uint8_t *scale)
     *scale = s;
 }
 
+/* ------------------------------------------------------------------ stochastic rounding (optional) */
+
+/* Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3",
+ * SC'11): a keyed bijection of 128-bit counters, used as a counter-based generator. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0, out[1] = c1, out[2] = c2, out[3] = c3;
+}
+
+/* The 16 random bits of element (o, kk) of an operand under `seed`: Philox key = (low, high) half of the
+ * seed, counter = (o, kk / 8, 0, 0); the 8 elements of that group take the eight 16-bit halves of the four
+ * output words in order (element kk % 8 = j: word j / 2, low half if j is even). */
+uint32_t orc_sr_bits(uint64_t seed, int64_t o, int64_t kk)
+{
+    uint32_t ctr[4] = {(uint32_t)o, (uint32_t)(kk / 8), 0u, 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    orc_philox4x32_10(ctr, key, w);
+    int j = (int)(kk % 8);
+    return (w[j / 2] >> (16 * (j % 2))) & 0xffffu;
+}
+
+/* Stochastic rounding of q to E2M1 with the 16-bit uniform number r16: |q| >= 6 saturates; otherwise with
+ * lo <= |q| < hi the neighbouring representable magnitudes, the result is hi with probability
+ * (|q| - lo) / (hi - lo) -- taken as "r16 / 65536 < that fraction" -- else lo.  Sign bit as in the
+ * deterministic encoder.  A representable |q| is never moved. */
+uint8_t orc_e2m1_encode_sr(float q, uint32_t r16)
+{
+    uint32_t u;
+    memcpy(&u, &q, sizeof u);
+    uint8_t sign = (uint8_t)((u >> 31) << 3);
+    float a = fabsf(q);
+    if (a >= 6.0f) return (uint8_t)(sign | 7);
+    int lo = 0;
+    while (lo < 6 && (float)E2M1_VALUE[lo + 1] <= a) ++lo;
+    float vlo = (float)E2M1_VALUE[lo], vhi = (float)E2M1_VALUE[lo + 1];
+    float frac = (a - vlo) / (vhi - vlo);
+    float draw = (float)r16 / 65536.0f;
+    return (uint8_t)(sign | (uint8_t)(draw < frac ? lo + 1 : lo));
+}
+
 /* ------------------------------------------------------------------ mask -> IHT -> quantise */
 
 /* The fp32 values that get quantised: row o of the operand with masked entries set to zero
@@ -256,6 +314,35 @@ void orc_iht_quantize(const uint16_t *data, int64_t outer, int64_t K, int64_t ld
         }
         free(row);
     }
+}
+
+/* As orc_iht_quantize, with the elements rounded stochastically (scales as before: amax rule). */
+void orc_iht_quantize_sr(const uint16_t *data, int64_t outer, int64_t K, int64_t ld, int k_contig,
+                         int iht_block, const uint8_t *zero_outer, const uint8_t *zero_k, uint64_t seed,
+                         uint8_t *codes, uint8_t *scales)
+{
+    float *t = (float *)malloc((size_t)outer * (size_t)K * sizeof *t);
+    orc_transform(data, outer, K, ld, k_contig, iht_block, zero_outer, zero_k, t);
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t blk = 0; blk < K / 32; ++blk) {
+            const float *v = t + o * K + 32 * blk;
+            float amax = 0.0f;
+            for (int i = 0; i < 32; ++i) {
+                float a = fabsf(v[i]);
+                if (a > amax) amax = a;
+            }
+            uint8_t s = orc_e8m0_from_amax(amax);
+            float X = ldexpf(1.0f, (int)s - 127);
+            for (int i = 0; i < 32; i += 2) {
+                uint8_t lo = orc_e2m1_encode_sr(v[i] / X, orc_sr_bits(seed, o, 32 * blk + i));
+                uint8_t hi = orc_e2m1_encode_sr(v[i + 1] / X, orc_sr_bits(seed, o, 32 * blk + i + 1));
+                codes[o * (K / 2) + 16 * blk + i / 2] = (uint8_t)(lo | (hi << 4));
+            }
+            scales[o * (K / 32) + blk] = s;
+        }
+    }
+    free(t);
 }
 
 /* ------------------------------------------------------------------ OHT (Eq. 6), operand side */

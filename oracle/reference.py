@@ -32,6 +32,10 @@ def lib():
         _lib.orc_e2m1_encode.restype = C.c_uint8
         _lib.orc_e2m1_encode.argtypes = [C.c_float]
         _lib.orc_num_threads.restype = C.c_int
+        _lib.orc_e2m1_encode_sr.restype = C.c_uint8
+        _lib.orc_e2m1_encode_sr.argtypes = [C.c_float, C.c_uint32]
+        _lib.orc_sr_bits.restype = C.c_uint32
+        _lib.orc_sr_bits.argtypes = [C.c_uint64, C.c_int64, C.c_int64]
     return _lib
 
 
@@ -111,12 +115,36 @@ def transform(bits, k_contig, iht_block, zero_outer=None, zero_k=None):
     return out
 
 
-def iht_quantize(bits, k_contig, iht_block, zero_outer=None, zero_k=None):
+def philox4x32_10(ctr, key):
+    """One Philox4x32-10 block: ctr 4 x uint32, key 2 x uint32 -> 4 x uint32."""
+    c = (C.c_uint32 * 4)(*[int(x) for x in ctr])
+    k = (C.c_uint32 * 2)(*[int(x) for x in key])
+    out = (C.c_uint32 * 4)()
+    lib().orc_philox4x32_10(c, k, out)
+    return [int(x) for x in out]
+
+
+def sr_bits(seed, o, kk):
+    """The 16 random bits that stochastic rounding uses for element (o, kk) under `seed`."""
+    return int(lib().orc_sr_bits(C.c_uint64(int(seed)), _i64(o), _i64(kk)))
+
+
+def e2m1_encode_sr(q, r16):
+    return int(lib().orc_e2m1_encode_sr(C.c_float(q), C.c_uint32(int(r16))))
+
+
+def iht_quantize(bits, k_contig, iht_block, zero_outer=None, zero_k=None, sr_seed=None):
+    """Residual masking -> block transform -> MXFP4.  sr_seed: round the elements stochastically (Philox
+    stream of that seed) instead of to nearest even."""
     bits, outer, K, ld = _operand(bits, k_contig)
     assert K % 32 == 0 and (iht_block == 0 or K % iht_block == 0)
     zo, zk = _mask(zero_outer, outer), _mask(zero_k, K)
     codes = np.empty((outer, K // 2), dtype=np.uint8)
     scales = np.empty((outer, K // 32), dtype=np.uint8)
+    if sr_seed is not None:
+        lib().orc_iht_quantize_sr(_p(bits), _i64(outer), _i64(K), _i64(ld), C.c_int(int(k_contig)),
+                                  C.c_int(iht_block), _p(zo), _p(zk), C.c_uint64(int(sr_seed)), _p(codes), _p(scales))
+        return codes, scales
     lib().orc_iht_quantize(_p(bits), _i64(outer), _i64(K), _i64(ld), C.c_int(int(k_contig)), C.c_int(iht_block),
                            _p(zo), _p(zk), _p(codes), _p(scales))
     return codes, scales
@@ -166,11 +194,13 @@ def exact_gemm(a_bits, a_k_contig, b_bits, b_k_contig, rows=None, cols=None):
     return bf16_gemm(a_bits, a_k_contig, b_bits, b_k_contig, rows=rows, cols=cols)
 
 
-def adahop_gemm(a_bits, a_k_contig, b_bits, b_k_contig, strategy, iht_block, k=0, idx=None, rows=None, cols=None):
+def adahop_gemm(a_bits, a_k_contig, b_bits, b_k_contig, strategy, iht_block, k=0, idx=None, rows=None, cols=None,
+                sr_seed_a=None, sr_seed_b=None):
     """The whole per-GEMM path.  A is logical [M, K], B is logical [N, K] (i.e. B^T), C is [M, N].
 
     rows / cols: optional index samples; C is returned on rows x cols only.
     idx: optional externally chosen extraction indices (else FOID picks them).
+    sr_seed_a / sr_seed_b: stochastic rounding of that operand's elements with this seed.
     Returns dict(C, a_codes, a_scales, b_codes, b_scales, idx).
     """
     a_bits, M, K, _ = _operand(a_bits, a_k_contig)
@@ -198,8 +228,8 @@ def adahop_gemm(a_bits, a_k_contig, b_bits, b_k_contig, strategy, iht_block, k=0
             b_zo = mask
         else:
             zk = mask
-    a_codes, a_scales = iht_quantize(a_bits, a_k_contig, b_iht, a_zo, zk)
-    b_codes, b_scales = iht_quantize(b_bits, b_k_contig, b_iht, b_zo, zk)
+    a_codes, a_scales = iht_quantize(a_bits, a_k_contig, b_iht, a_zo, zk, sr_seed=sr_seed_a)
+    b_codes, b_scales = iht_quantize(b_bits, b_k_contig, b_iht, b_zo, zk, sr_seed=sr_seed_b)
     Cm = mx_gemm(a_codes, a_scales, b_codes, b_scales, rows_a, cols_a)
     if sel.size:
         if strategy == IHT_OE_ROW:        # C[S, :] += A[S, :] B   (Eq. 7)

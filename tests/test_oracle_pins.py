@@ -664,3 +664,97 @@ def test_oht_quantize_closed_form_and_whole_strategy(golden_dir):
     out = orc.oht_gemm(bits, True, bits[:b], True, b)
     exact = bits_to_f64(bits) @ bits_to_f64(bits[:b]).T
     assert np.allclose(out["C"], exact, rtol=0, atol=1e-12 * np.abs(exact).max())
+
+
+# ----------------------------------------------------------------------------- stochastic rounding (optional)
+
+def test_philox_known_answers(golden_dir):
+    rows = load_table(os.path.join(golden_dir, "philox4x32_10_kat.txt"))
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        assert orc.philox4x32_10(w[0:4], w[4:6]) == w[6:10]
+
+
+def test_sr_bits_layout_and_uniformity():
+    """Element (o, kk) takes half j = kk % 8 of the block with counter (o, kk / 8, 0, 0), key = the seed's halves;
+    the 16-bit draws are uniform (mean, 16-bucket chi-square) and differ between seeds, rows and K indices."""
+    seed = 0x0123456789abcdef
+    for o, kk in ((0, 0), (5, 17), (1000, 8191), (3, 8)):
+        w = orc.philox4x32_10([o, kk // 8, 0, 0], [seed & 0xffffffff, seed >> 32])
+        j = kk % 8
+        assert orc.sr_bits(seed, o, kk) == (w[j // 2] >> (16 * (j % 2))) & 0xffff
+    draws = np.array([orc.sr_bits(7, o, kk) for o in range(40) for kk in range(512)])
+    assert abs(draws.mean() - 32767.5) < 4 * 65536 / np.sqrt(12 * draws.size)
+    counts = np.bincount(draws >> 12, minlength=16)
+    chi2 = ((counts - draws.size / 16) ** 2 / (draws.size / 16)).sum()
+    assert chi2 < 45.0                                   # 15 degrees of freedom: P(chi2 > 45) < 1e-4
+    other = np.array([orc.sr_bits(8, o, kk) for o in range(40) for kk in range(512)])
+    assert np.mean(draws == other) < 0.001
+    assert len({orc.sr_bits(7, 0, kk) for kk in range(64)}) > 60
+
+
+def test_sr_encoder_probability_is_the_distance_fraction(golden_dir):
+    """Brute force over all 65536 draws: the number of draws that round q up equals ceil(frac * 65536) with frac
+    the position of |q| between its E2M1 neighbours; representable values never move; |q| >= 6 saturates;
+    the result is always one of the two neighbours and keeps the sign."""
+    table = e2m1_table(golden_dir)
+    grid = [table[c] for c in range(8)]
+    all_draws = np.arange(65536)
+    for q in (0.1, 0.25, 0.49, 0.5, 0.7, 1.3, 1.75, 2.0, 2.2, 3.9, 4.5, 5.999, 1e-6, 2.0 ** -20):
+        for sign in (1.0, -1.0):
+            lo = max(i for i in range(8) if grid[i] <= q)
+            frac = (np.float32(q) - np.float32(grid[lo])) / np.float32(grid[lo + 1] - grid[lo])
+            codes = np.array([orc.e2m1_encode_sr(sign * q, int(r)) for r in all_draws[::1 if q in (0.7, 4.5) else 97]])
+            mags = codes & 7
+            assert set(mags.tolist()) <= {lo, lo + 1}
+            assert np.all((codes >> 3) == (0 if sign > 0 else 1))
+            if q in (0.7, 4.5):
+                assert int(np.sum(mags == lo + 1)) == int(np.ceil(float(frac) * 65536))
+            if frac == 0:
+                assert np.all(mags == lo)
+    for q in (6.0, 6.5, 7.99, 1e9):
+        assert orc.e2m1_encode_sr(q, 0) == 7 and orc.e2m1_encode_sr(-q, 65535) == 15
+
+
+def test_sr_quantiser_is_unbiased_where_round_to_nearest_is_not(golden_dir):
+    """Mean over seeds of the dequantised SR result converges to the transformed value (no saturation in this
+    input); round-to-nearest keeps a systematic offset on the same data.  Scales do not depend on the rounding."""
+    table = e2m1_table(golden_dir)
+    x = np.full((4, 64), 2.6, dtype=np.float32)
+    x[:, 0] = 4.0                                        # block amax 4 -> scale 1: 2.6 sits between 2 and 3
+    x[:, 32] = 4.0
+    bits = bf16_bits(x)
+    truth = bits_to_f64(bits)
+    rne_codes, rne_scales = orc.iht_quantize(bits, True, 0)
+    rne = dequant(rne_codes, rne_scales, table)
+    acc = np.zeros_like(truth)
+    n = 400
+    for seed in range(n):
+        c, s = orc.iht_quantize(bits, True, 0, sr_seed=seed)
+        assert np.array_equal(s, rne_scales)
+        d = dequant(c, s, table)
+        assert np.all((d == 2.0) | (d == 3.0) | (d == 4.0))
+        acc += d
+    mean = acc / n
+    # per element the estimator has variance p(1-p) <= 1/4; averaged over 4*62 elements and n seeds
+    assert abs((mean - truth)[truth < 4].mean()) < 4 * 0.5 / np.sqrt(n * 4 * 62)
+    assert abs((rne - truth)[truth < 4].mean()) > 0.3    # nearest: every 2.6 (bf16: 2.59375) becomes 3
+
+
+def test_sr_product_converges_to_the_unquantised_transformed_product():
+    """E[Q_sr(A H) Q_sr(H^T B)] = (A H)(H^T B) = A B when nothing saturates: the error of the seed-averaged
+    product falls like 1 / sqrt(n), well below the single-draw and the round-to-nearest errors."""
+    rng = np.random.default_rng(3)
+    a = bf16_bits(rng.uniform(-1, 1, (48, 128)).astype(np.float32))
+    b = bf16_bits(rng.uniform(-1, 1, (40, 128)).astype(np.float32))
+    exact = orc.exact_gemm(a, True, b, True)
+    err = lambda c: np.linalg.norm(c - exact) / np.linalg.norm(exact)
+    single = orc.adahop_gemm(a, True, b, True, orc.IHT, 32, sr_seed_a=1, sr_seed_b=2)["C"]
+    acc = np.zeros_like(exact)
+    n = 64
+    for i in range(n):
+        acc += orc.adahop_gemm(a, True, b, True, orc.IHT, 32, sr_seed_a=2 * i + 1, sr_seed_b=2 * i + 2)["C"]
+    e1, en = err(single), err(acc / n)
+    assert en < 2.0 * e1 / np.sqrt(n) + 0.02 * e1        # saturation in (6, 8) X blocks leaves a small floor
+    assert en < 0.5 * err(orc.adahop_gemm(a, True, b, True, orc.IHT, 32)["C"])
