@@ -256,6 +256,8 @@ def main():
         q_ms = time_ms(torch, lambda: ah.adahop_iht_quantize(qx, big.g.iht_block, None, None, codes, scales), 10)
         extras["iht_quantize"] = {"outer": qx.outer, "K": qx.K, "k_contig": qx.k_contig, "ms": q_ms,
                                   "GBps": 2.53125 * qx.outer * qx.K / (q_ms * 1e-3) / 1e9, "peak_GBps": 8000.0}
+        q_sr = time_ms(torch, lambda: ah.adahop_iht_quantize(qx, big.g.iht_block, None, None, codes, scales, sr_seed=1), 10)
+        extras["iht_quantize_stochastic_rounding"] = {"ms": q_sr, "GBps": 2.53125 * qx.outer * qx.K / (q_sr * 1e-3) / 1e9}
         out["extras"] = extras
 
     if args.copy_calibration:

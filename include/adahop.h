@@ -153,6 +153,19 @@ int adahop_gemm(const adahop_operand_t *A, const adahop_operand_t *B, float *C, 
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * adahop_iht_quantize with stochastic rounding of the elements -- an option for gradient operands (the
+ * paper cites it as prior work for unbiased MXFP4 gradient estimates, Sec. 2.1-2.2; AdaHOP itself rounds
+ * to nearest).  Scales as before (amax rule).  An element q = v / 2^(s-127) with |q| >= 6 saturates;
+ * otherwise, lo <= |q| < hi being its neighbouring E2M1 magnitudes, it becomes hi if
+ * r / 65536 < (|q| - lo) / (hi - lo) and lo otherwise (a representable |q| never moves; sign kept), with r
+ * the 16-bit draw of that element: Philox4x32-10, key = (low, high) 32 bits of seed, counter =
+ * (outer index, K index / 8, 0, 0), element K index % 8 = j taking the low (j even) or high (j odd) half
+ * of output word j / 2.  The result depends on (seed, position) only: not on layout, launch shape or k.
+ * ------------------------------------------------------------------------------------------- */
+int adahop_iht_quantize_sr(const adahop_operand_t *x, int iht_block, const uint8_t *zero_outer,
+                           const uint8_t *zero_k, uint64_t seed, uint8_t *codes, uint8_t *scales, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Outer Hadamard Transform (paper Eq. 6), the strategy the paper compares against:
  *     C_OHT = H_m^T ( Q(H_m A) Q(B H_n) ) H_n^T
  * with block-diagonal normalised Sylvester matrices of size oht_block in {32, 64, 128} on both outer
@@ -189,12 +202,16 @@ int adahop_oht_inverse(float *C, int64_t M, int64_t N, int64_t ldc, int oht_bloc
  *   c_bf16: 0: C is float [M, ldc]; 1: C is bf16 [M, ldc] (2-byte aligned), every element the fp32
  *     result rounded to nearest even once (the K-channel product is added before the rounding, the
  *     row / column product overwrites its rows / columns).
+ *   sr_a / sr_b with sr_seed_a / sr_seed_b: the elements of that operand are rounded stochastically as
+ *     by adahop_iht_quantize_sr (ignored for an operand packed by the caller and under ADAHOP_OHT).
  * Workspace size and layout are those of adahop_gemm.
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
     const uint8_t *a_codes, *a_scales;
     const uint8_t *b_codes, *b_scales;
     int c_bf16;
+    int sr_a, sr_b;                 /* nonzero: quantise that operand with stochastic rounding (below) */
+    uint64_t sr_seed_a, sr_seed_b;  /* seeds of the two streams                                       */
 } adahop_gemm_opts_t;
 
 int adahop_pack_operand(const adahop_operand_t *x, int is_b, adahop_strategy_t strategy, int iht_block, int k,

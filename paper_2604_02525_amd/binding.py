@@ -19,7 +19,7 @@ ADAHOP_PATTERN_NONE, ADAHOP_PATTERN_OUTER, ADAHOP_PATTERN_K = range(3)
 
 EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_gemm_mx",
            "adahop_gemm_mx_bf16out", "adahop_gemm_mx_workspace_bytes", "adahop_pack_operand", "adahop_gemm_ex",
-           "adahop_oht_quantize", "adahop_oht_inverse",
+           "adahop_oht_quantize", "adahop_oht_inverse", "adahop_iht_quantize_sr",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
            "adahop_oe_gemm_bf16", "adahop_detect_pattern_workspace_bytes", "adahop_detect_pattern",
            "adahop_select_strategy", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
@@ -41,7 +41,8 @@ class adahop_operand_t(C.Structure):
 
 class adahop_gemm_opts_t(C.Structure):
     _fields_ = [("a_codes", C.c_void_p), ("a_scales", C.c_void_p), ("b_codes", C.c_void_p), ("b_scales", C.c_void_p),
-                ("c_bf16", C.c_int)]
+                ("c_bf16", C.c_int), ("sr_a", C.c_int), ("sr_b", C.c_int), ("sr_seed_a", C.c_uint64),
+                ("sr_seed_b", C.c_uint64)]
 
 
 class adahop_ws_layout_t(C.Structure):
@@ -64,6 +65,7 @@ def lib():
         OP = C.POINTER(adahop_operand_t)
         L.adahop_quantize_mx.argtypes = [OP, P, P, P]
         L.adahop_iht_quantize.argtypes = [OP, I, P, P, P, P, P]
+        L.adahop_iht_quantize_sr.argtypes = [OP, I, P, P, C.c_uint64, P, P, P]
         L.adahop_foid_topk.argtypes = [OP, I, I, P, P, P, P]
         L.adahop_gemm_mx.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P, SZ, P]
         L.adahop_gemm_mx_bf16out.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P, SZ, P]
@@ -136,10 +138,16 @@ def _u8(shape, device):
     return torch.empty(shape, dtype=torch.uint8, device=device)
 
 
-def adahop_iht_quantize(x, iht_block, zero_outer=None, zero_k=None, codes=None, scales=None, stream=None):
+def adahop_iht_quantize(x, iht_block, zero_outer=None, zero_k=None, codes=None, scales=None, stream=None,
+                        sr_seed=None):
+    """sr_seed: round the elements stochastically under that seed (adahop_iht_quantize_sr)."""
     dev = x.tensor.device
     codes = _u8((x.outer, x.K // 2), dev) if codes is None else codes
     scales = _u8((x.outer, x.K // 32), dev) if scales is None else scales
+    if sr_seed is not None:
+        _check(lib().adahop_iht_quantize_sr(C.byref(x.c()), iht_block, _ptr(zero_outer), _ptr(zero_k), int(sr_seed),
+                                            _ptr(codes), _ptr(scales), _stream(stream)), "adahop_iht_quantize_sr")
+        return codes, scales
     _check(lib().adahop_iht_quantize(C.byref(x.c()), iht_block, _ptr(zero_outer), _ptr(zero_k), _ptr(codes),
                                      _ptr(scales), _stream(stream)), "adahop_iht_quantize")
     return codes, scales
@@ -223,11 +231,11 @@ def adahop_pack_operand(x, is_b, strategy, iht_block, k=0, idx=None, codes=None,
 
 
 def adahop_gemm(A, B, strategy, iht_block, k=0, idx=None, Cout=None, workspace=None, stream=None,
-                a_packed=None, b_packed=None, c_bf16=False):
+                a_packed=None, b_packed=None, c_bf16=False, sr_seed_a=None, sr_seed_b=None):
     """Whole path.  Returns dict(C, idx, workspace, layout, a_codes, a_scales, b_codes, b_scales, mask)
     where the codes / scales / mask entries are views into the workspace.  a_packed / b_packed: (codes,
-    scales) from adahop_pack_operand; c_bf16 (or a bfloat16 Cout): bf16 output.  Any of the three routes
-    the call through adahop_gemm_ex."""
+    scales) from adahop_pack_operand; c_bf16 (or a bfloat16 Cout): bf16 output; sr_seed_a / sr_seed_b:
+    stochastic rounding of that operand.  Any of these routes the call through adahop_gemm_ex."""
     dev = A.tensor.device
     M, N, K = A.outer, B.outer, A.K
     L = adahop_gemm_workspace_layout(M, N, K, strategy, k)
@@ -239,14 +247,15 @@ def adahop_gemm(A, B, strategy, iht_block, k=0, idx=None, Cout=None, workspace=N
     use_given = idx is not None
     if idx is None:
         idx = torch.empty(max(k, 1), dtype=torch.int32, device=dev)
-    if a_packed is None and b_packed is None and not c_bf16:
+    if a_packed is None and b_packed is None and not c_bf16 and sr_seed_a is None and sr_seed_b is None:
         _check(lib().adahop_gemm(C.byref(A.c()), C.byref(B.c()), _ptr(Cout), Cout.stride(0), strategy, iht_block, k,
                                  _ptr(idx), int(use_given), _ptr(workspace), workspace.numel(), _stream(stream)),
                "adahop_gemm")
     else:
         ac, asc = a_packed if a_packed is not None else (None, None)
         bc, bsc = b_packed if b_packed is not None else (None, None)
-        opts = adahop_gemm_opts_t(_ptr(ac), _ptr(asc), _ptr(bc), _ptr(bsc), int(c_bf16))
+        opts = adahop_gemm_opts_t(_ptr(ac), _ptr(asc), _ptr(bc), _ptr(bsc), int(c_bf16), int(sr_seed_a is not None),
+                                  int(sr_seed_b is not None), int(sr_seed_a or 0), int(sr_seed_b or 0))
         _check(lib().adahop_gemm_ex(C.byref(A.c()), C.byref(B.c()), _ptr(Cout), Cout.stride(0), strategy, iht_block, k,
                                     _ptr(idx), int(use_given), C.byref(opts), _ptr(workspace), workspace.numel(),
                                     _stream(stream)), "adahop_gemm_ex")

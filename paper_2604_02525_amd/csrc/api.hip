@@ -62,15 +62,29 @@ const char *adahop_status_string(int status)
     }
 }
 
-int adahop_iht_quantize(const adahop_operand_t *x, int iht_block, const uint8_t *zero_outer, const uint8_t *zero_k,
-                        uint8_t *codes, uint8_t *scales, void *stream)
+static int iht_quantize_checked(const adahop_operand_t *x, int iht_block, const uint8_t *zero_outer,
+                                const uint8_t *zero_k, uint8_t *codes, uint8_t *scales, void *stream,
+                                const uint64_t *sr_seed)
 {
     int rc = validate_operand(x);
     if (rc != ADAHOP_OK) return rc;
     if (!codes || !scales || !valid_iht_block(iht_block)) return ADAHOP_E_INVALID_ARG;
     if (iht_block > 0 && x->K % iht_block != 0) return ADAHOP_E_INVALID_ARG;
     if (!aligned(codes, 16) || (zero_k && !aligned(zero_k, 8))) return ADAHOP_E_INVALID_ARG;
-    return launch_iht_quantize(*x, iht_block, zero_outer, zero_k, codes, scales, static_cast<hipStream_t>(stream));
+    return launch_iht_quantize(*x, iht_block, zero_outer, zero_k, codes, scales, static_cast<hipStream_t>(stream),
+                               sr_seed);
+}
+
+int adahop_iht_quantize(const adahop_operand_t *x, int iht_block, const uint8_t *zero_outer, const uint8_t *zero_k,
+                        uint8_t *codes, uint8_t *scales, void *stream)
+{
+    return iht_quantize_checked(x, iht_block, zero_outer, zero_k, codes, scales, stream, nullptr);
+}
+
+int adahop_iht_quantize_sr(const adahop_operand_t *x, int iht_block, const uint8_t *zero_outer,
+                           const uint8_t *zero_k, uint64_t seed, uint8_t *codes, uint8_t *scales, void *stream)
+{
+    return iht_quantize_checked(x, iht_block, zero_outer, zero_k, codes, scales, stream, &seed);
 }
 
 int adahop_quantize_mx(const adahop_operand_t *x, uint8_t *codes, uint8_t *scales, void *stream)
@@ -350,13 +364,15 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
     if (!a_given) {
         uint8_t *c = reinterpret_cast<uint8_t *>(ws + L.a_codes), *s = reinterpret_cast<uint8_t *>(ws + L.a_scales);
         rc = oht ? launch_oht_quantize(*A, b, c, s, st)
-                 : launch_iht_quantize(*A, b, a_kind == 1 ? mask : nullptr, a_kind == 2 ? mask : nullptr, c, s, st);
+                 : launch_iht_quantize(*A, b, a_kind == 1 ? mask : nullptr, a_kind == 2 ? mask : nullptr, c, s, st,
+                                       opts && opts->sr_a ? &opts->sr_seed_a : nullptr);
         if (rc != ADAHOP_OK) return rc;
     }
     if (!b_given) {
         uint8_t *c = reinterpret_cast<uint8_t *>(ws + L.b_codes), *s = reinterpret_cast<uint8_t *>(ws + L.b_scales);
         rc = oht ? launch_oht_quantize(*B, b, c, s, st)
-                 : launch_iht_quantize(*B, b, b_kind == 1 ? mask : nullptr, b_kind == 2 ? mask : nullptr, c, s, st);
+                 : launch_iht_quantize(*B, b, b_kind == 1 ? mask : nullptr, b_kind == 2 ? mask : nullptr, c, s, st,
+                                       opts && opts->sr_b ? &opts->sr_seed_b : nullptr);
         if (rc != ADAHOP_OK) return rc;
     }
     // 3. MXFP4 product, with the K-channel BF16 product fused in front; 4. row / column BF16 product

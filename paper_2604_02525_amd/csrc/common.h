@@ -26,8 +26,10 @@ int validate_operand(const adahop_operand_t *x);
 bool valid_iht_block(int b);
 
 // Launchers (one per kernel family); each validates nothing and returns a status.
+// sr_seed: NULL = round to nearest even; else the elements are rounded stochastically under that seed.
 int launch_iht_quantize(const adahop_operand_t &x, int iht_block, const uint8_t *zero_outer,
-                        const uint8_t *zero_k, uint8_t *codes, uint8_t *scales, hipStream_t st);
+                        const uint8_t *zero_k, uint8_t *codes, uint8_t *scales, hipStream_t st,
+                        const uint64_t *sr_seed = nullptr);
 int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, uint8_t *mask, float *scores,
                      hipStream_t st);
 int launch_mask_from_idx(const int32_t *idx, int k, uint8_t *mask, int64_t dim, hipStream_t st);

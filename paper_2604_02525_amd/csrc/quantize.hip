@@ -42,6 +42,57 @@ __device__ __forceinline__ uint32_t e2m1_code(float v, int s)
     return m | ((__float_as_uint(v) >> 28) & 8u);
 }
 
+// ---- optional stochastic rounding of the elements (the paper cites it as prior work for unbiased
+// gradient quantisation).  Random bits: Philox4x32 with 10 rounds (Salmon et al., SC'11), key = the two
+// halves of the caller's seed, counter = (row, K index / 8, 0, 0): one block serves the 8 consecutive
+// K-elements of a group, element j taking half j (word j / 2, low half for even j).
+struct sr_key_t {
+    uint32_t k0, k1;
+};
+
+__device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, sr_key_t key)
+{
+    uint32_t c2 = 0, c3 = 0, k0 = key.k0, k1 = key.k1;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return make_uint4(c0, c1, c2, c3);
+}
+
+// E2M1 code of v / 2^(s-127) rounded stochastically with the 16-bit draw r16: up to the next magnitude
+// iff r16 / 65536 < (|q| - lo) / (hi - lo); |q| >= 6 saturates; sign as in e2m1_code.
+__device__ __forceinline__ uint32_t e2m1_code_sr(float v, int s, uint32_t r16)
+{
+    const float a = fabsf(ldexpf(v, 127 - s));
+    const uint32_t idx = (uint32_t)(a >= 0.5f) + (uint32_t)(a >= 1.0f) + (uint32_t)(a >= 1.5f) + (uint32_t)(a >= 2.0f) +
+                         (uint32_t)(a >= 3.0f) + (uint32_t)(a >= 4.0f);
+    const float lo = idx < 4 ? 0.5f * (float)idx : (float)(idx - 2);       // 0, .5, 1, 1.5, 2, 3, 4
+    const float inv_step = idx < 4 ? 2.0f : (idx < 6 ? 1.0f : 0.5f);       // steps .5, 1, 2: exact scaling
+    const float frac = (a - lo) * inv_step;
+    const uint32_t up = (float)r16 * 0x1p-16f < frac ? 1u : 0u;
+    const uint32_t m = a >= 6.0f ? 7u : idx + up;
+    return m | ((__float_as_uint(v) >> 28) & 8u);
+}
+
+// Packed codes of 8 consecutive K-elements (first in the low nibble) starting at K index kk of row `row`.
+__device__ __forceinline__ uint32_t pack8_sr(const float (&w)[8], int s, sr_key_t key, int64_t row, int64_t kk)
+{
+    const uint4 r = philox4x32_10((uint32_t)row, (uint32_t)(kk >> 3), key);
+    const uint32_t word[4] = {r.x, r.y, r.z, r.w};
+    uint32_t packed = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) packed |= e2m1_code_sr(w[i], s, (word[i >> 1] >> (16 * (i & 1))) & 0xffffu) << (4 * i);
+    return packed;
+}
+
 template <int B> __device__ __forceinline__ float hadamard_norm();
 template <> __device__ __forceinline__ float hadamard_norm<32>() { return 0x1.6a09e6p-3f; }
 template <> __device__ __forceinline__ float hadamard_norm<64>() { return 0.125f; }
@@ -78,11 +129,12 @@ template <int XM, int B> __device__ __forceinline__ void lane_stage(float (&v)[8
 // one transform block.  FLAT = 0: blockIdx.x is the row, blockIdx.y*256+tid the 8-element chunk.
 // FLAT = 1 (short rows): chunks of all rows are numbered consecutively.
 // ------------------------------------------------------------------------------------------------
-template <int B, int FLAT>
+template <int B, int FLAT, bool SR>
 __global__ __launch_bounds__(256) void k_quant_kc(const uint16_t *__restrict__ x, int64_t outer, int64_t K,
                                                   int64_t ld, const uint8_t *__restrict__ zero_outer,
                                                   const uint8_t *__restrict__ zero_k,
-                                                  uint8_t *__restrict__ codes, uint8_t *__restrict__ scales)
+                                                  uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
+                                                  sr_key_t key)
 {
     const uint32_t cpr = (uint32_t)(K >> 3);
     int64_t row;
@@ -145,8 +197,12 @@ __global__ __launch_bounds__(256) void k_quant_kc(const uint16_t *__restrict__ x
     const int s = e8m0_of_amax(amax);
 
     uint32_t packed = 0;
+    if constexpr (SR) {
+        packed = pack8_sr(v, s, key, row, kk);
+    } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) packed |= e2m1_code(v[i], s) << (4 * i);
+        for (int i = 0; i < 8; ++i) packed |= e2m1_code(v[i], s) << (4 * i);
+    }
 
     if (active) {
         *reinterpret_cast<uint32_t *>(codes + row * (K >> 1) + (kk >> 1)) = packed;
@@ -163,13 +219,13 @@ template <int B> struct ks_cfg {
     static constexpr int NW = (NCH > 4) ? NCH : 4;     // waves per workgroup
 };
 
-template <int B>
+template <int B, bool SR>
 __global__ __launch_bounds__(ks_cfg<B>::NW * 64) void k_quant_ks(const uint16_t *__restrict__ x, int64_t outer,
                                                                   int64_t K, int64_t ld,
                                                                   const uint8_t *__restrict__ zero_outer,
                                                                   const uint8_t *__restrict__ zero_k,
                                                                   uint8_t *__restrict__ codes,
-                                                                  uint8_t *__restrict__ scales)
+                                                                  uint8_t *__restrict__ scales, sr_key_t key)
 {
     constexpr int NCH = ks_cfg<B>::NCH;
     constexpr int NW = ks_cfg<B>::NW;
@@ -249,10 +305,24 @@ __global__ __launch_bounds__(ks_cfg<B>::NW * 64) void k_quant_ks(const uint16_t 
     }
     const int sx = e8m0_of_amax(ax), sy = e8m0_of_amax(ay);
     uint32_t px[4] = {0, 0, 0, 0}, py[4] = {0, 0, 0, 0};
+    if constexpr (SR) {
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-        px[i >> 3] |= e2m1_code(v[i].x, sx) << (4 * (i & 7));
-        py[i >> 3] |= e2m1_code(v[i].y, sy) << (4 * (i & 7));
+        for (int g = 0; g < 4; ++g) {
+            float wx[8], wy[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                wx[i] = v[8 * g + i].x;
+                wy[i] = v[8 * g + i].y;
+            }
+            px[g] = pack8_sr(wx, sx, key, o, blk * 32 + 8 * g);
+            py[g] = pack8_sr(wy, sy, key, o + 1, blk * 32 + 8 * g);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            px[i >> 3] |= e2m1_code(v[i].x, sx) << (4 * (i & 7));
+            py[i >> 3] |= e2m1_code(v[i].y, sy) << (4 * (i & 7));
+        }
     }
     if (valid) {
         *reinterpret_cast<uint4 *>(codes + o * (K >> 1) + blk * 16) = make_uint4(px[0], px[1], px[2], px[3]);
@@ -349,9 +419,11 @@ template <int STAGE> __device__ __forceinline__ void cross_stage(float (&w0)[8],
 
 // Transform (B > 0) and quantise the lane's two groups; returns the packed codes of each group and
 // the scale code of the MX block each group belongs to (identical on the 4 lanes of the block).
-template <int B>
+// SR: elements rounded stochastically; the groups start at K indices kk0 and kk1 of row `row`.
+template <int B, bool SR>
 __device__ __forceinline__ void transform_quantize16(float (&w0)[8], float (&w1)[8], const lane_plan_t &p,
-                                                     uint32_t &codes0, uint32_t &codes1, int &s0, int &s1)
+                                                     uint32_t &codes0, uint32_t &codes1, int &s0, int &s1,
+                                                     sr_key_t key, int64_t row, int64_t kk0, int64_t kk1)
 {
     if constexpr (B > 0) {
 #pragma unroll
@@ -399,6 +471,11 @@ __device__ __forceinline__ void transform_quantize16(float (&w0)[8], float (&w1)
     m1 = fmaxf(m1, dpp_get<0x4E>(m1));
     s0 = e8m0_of_amax(m0);
     s1 = e8m0_of_amax(m1);
+    if constexpr (SR) {
+        codes0 = pack8_sr(w0, s0, key, row, kk0);
+        codes1 = pack8_sr(w1, s1, key, row, kk1);
+        return;
+    }
     const float x0 = __uint_as_float((uint32_t)s0 << 23), x1 = __uint_as_float((uint32_t)s1 << 23);
     codes0 = 0;
     codes1 = 0;
@@ -434,11 +511,12 @@ __device__ __forceinline__ void store_codes_scales(uint8_t *codes, uint8_t *scal
 }
 
 // K-contiguous operand: 16 lanes per 256 K-elements of a row.  FLAT as in k_quant_kc.
-template <int B, int FLAT>
+template <int B, int FLAT, bool SR>
 __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__ x, int64_t outer, int64_t K,
                                                     int64_t ld, const uint8_t *__restrict__ zero_outer,
                                                     const uint8_t *__restrict__ zero_k,
-                                                    uint8_t *__restrict__ codes, uint8_t *__restrict__ scales)
+                                                    uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
+                                                    sr_key_t key)
 {
     const uint32_t upr = (uint32_t)(K >> 8); // 256-element units per row
     int64_t row;
@@ -474,7 +552,7 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
     }
     uint32_t c0, c1;
     int s0, s1;
-    transform_quantize16<B>(w0, w1, plan, c0, c1, s0, s1);
+    transform_quantize16<B, SR>(w0, w1, plan, c0, c1, s0, s1, key, row, kk, kk + 128);
     if (active) store_codes_scales(codes, scales, row, K, k0, plan.chunk, c0, c1, s0, s1);
 }
 
@@ -485,11 +563,12 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
 // row pitch of 66 elements keeps those reads down to 2-way bank conflicts.
 constexpr int KS_COLS = 64, KS_PITCH = 66;
 
-template <int B>
+template <int B, bool SR>
 __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__ x, int64_t outer, int64_t K,
                                                     int64_t ld, const uint8_t *__restrict__ zero_outer,
                                                     const uint8_t *__restrict__ zero_k,
-                                                    uint8_t *__restrict__ codes, uint8_t *__restrict__ scales)
+                                                    uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
+                                                    sr_key_t key)
 {
     __shared__ uint16_t tile[256 * KS_PITCH];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -537,72 +616,74 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
         }
         uint32_t c0, c1;
         int s0, s1;
-        transform_quantize16<B>(w0, w1, plan, c0, c1, s0, s1);
+        transform_quantize16<B, SR>(w0, w1, plan, c0, c1, s0, s1, key, o, k0 + kc, k0 + kc + 128);
         if (active) store_codes_scales(codes, scales, o, K, k0, plan.chunk, c0, c1, s0, s1);
     }
 }
 
-template <int B>
+template <int B, bool SR>
 int launch_kc(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
-              hipStream_t st)
+              sr_key_t key, hipStream_t st)
 {
     const uint16_t *d = static_cast<const uint16_t *>(x.data);
     if (x.K % 256 == 0) {
         const int64_t tpr = x.K / 16; // threads per row
         if (tpr >= 128) {
             dim3 grid((unsigned)x.outer, (unsigned)ceil_div(tpr, 256));
-            hipLaunchKernelGGL((k_quant_kc16<B, 0>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes, scales);
+            hipLaunchKernelGGL((k_quant_kc16<B, 0, SR>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes,
+                               scales, key);
         } else {
             dim3 grid((unsigned)ceil_div(x.outer * tpr, 256));
-            hipLaunchKernelGGL((k_quant_kc16<B, 1>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes, scales);
+            hipLaunchKernelGGL((k_quant_kc16<B, 1, SR>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes,
+                               scales, key);
         }
         return check_launch();
     }
     const int64_t cpr = x.K / 8;
     if (cpr >= 128) {
         dim3 grid((unsigned)x.outer, (unsigned)ceil_div(cpr, 256));
-        hipLaunchKernelGGL((k_quant_kc<B, 0>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes, scales);
+        hipLaunchKernelGGL((k_quant_kc<B, 0, SR>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes, scales,
+                           key);
     } else {
         dim3 grid((unsigned)ceil_div(x.outer * cpr, 256));
-        hipLaunchKernelGGL((k_quant_kc<B, 1>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes, scales);
+        hipLaunchKernelGGL((k_quant_kc<B, 1, SR>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes, scales,
+                           key);
     }
     return check_launch();
 }
 
-template <int B>
+template <int B, bool SR>
 int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
-              hipStream_t st)
+              sr_key_t key, hipStream_t st)
 {
     if (x.K % 256 == 0 && x.K / 256 <= 65535) {
         dim3 grid((unsigned)ceil_div(x.outer, KS_COLS), (unsigned)(x.K / 256));
-        hipLaunchKernelGGL((k_quant_ks16<B>), grid, dim3(256), 0, st, static_cast<const uint16_t *>(x.data), x.outer,
-                           x.K, x.ld, zo, zk, codes, scales);
+        hipLaunchKernelGGL((k_quant_ks16<B, SR>), grid, dim3(256), 0, st, static_cast<const uint16_t *>(x.data), x.outer,
+                           x.K, x.ld, zo, zk, codes, scales, key);
         return check_launch();
     }
     constexpr int NW = ks_cfg<B>::NW;
     constexpr int NCH = ks_cfg<B>::NCH;
     const size_t lds = NCH > 1 ? (size_t)NW * 32 * 64 * sizeof(float2) : 0;
     if (lds > 48 * 1024) {
-        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_quant_ks<B>),
+        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_quant_ks<B, SR>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         if (rc != ADAHOP_OK) return rc;
     }
     dim3 grid((unsigned)ceil_div(x.outer, 128), (unsigned)ceil_div(x.K / 32, NW));
-    hipLaunchKernelGGL((k_quant_ks<B>), grid, dim3(NW * 64), lds, st, static_cast<const uint16_t *>(x.data),
-                       x.outer, x.K, x.ld, zo, zk, codes, scales);
+    hipLaunchKernelGGL((k_quant_ks<B, SR>), grid, dim3(NW * 64), lds, st, static_cast<const uint16_t *>(x.data),
+                       x.outer, x.K, x.ld, zo, zk, codes, scales, key);
     return check_launch();
 }
 
-} // namespace
-
-int launch_iht_quantize(const adahop_operand_t &x, int b, const uint8_t *zo, const uint8_t *zk, uint8_t *codes,
-                        uint8_t *scales, hipStream_t st)
+template <bool SR>
+int dispatch_block(const adahop_operand_t &x, int b, const uint8_t *zo, const uint8_t *zk, uint8_t *codes,
+                   uint8_t *scales, sr_key_t key, hipStream_t st)
 {
-    if (x.outer == 0 || x.K == 0) return ADAHOP_OK;
-#define ADAHOP_DISPATCH(BB)                                                              \
-    case BB:                                                                             \
-        return x.k_contig ? launch_kc<BB>(x, zo, zk, codes, scales, st)                  \
-                          : launch_ks<BB>(x, zo, zk, codes, scales, st);
+#define ADAHOP_DISPATCH(BB)                                                                  \
+    case BB:                                                                                 \
+        return x.k_contig ? launch_kc<BB, SR>(x, zo, zk, codes, scales, key, st)             \
+                          : launch_ks<BB, SR>(x, zo, zk, codes, scales, key, st);
     switch (b) {
         ADAHOP_DISPATCH(0)
         ADAHOP_DISPATCH(32)
@@ -613,6 +694,20 @@ int launch_iht_quantize(const adahop_operand_t &x, int b, const uint8_t *zo, con
         return ADAHOP_E_INVALID_ARG;
     }
 #undef ADAHOP_DISPATCH
+}
+
+} // namespace
+
+// sr_seed: NULL for round-to-nearest-even, else the seed of the stochastic rounding of the elements.
+int launch_iht_quantize(const adahop_operand_t &x, int b, const uint8_t *zo, const uint8_t *zk, uint8_t *codes,
+                        uint8_t *scales, hipStream_t st, const uint64_t *sr_seed)
+{
+    if (x.outer == 0 || x.K == 0) return ADAHOP_OK;
+    if (sr_seed) {
+        const sr_key_t key = {(uint32_t)*sr_seed, (uint32_t)(*sr_seed >> 32)};
+        return dispatch_block<true>(x, b, zo, zk, codes, scales, key, st);
+    }
+    return dispatch_block<false>(x, b, zo, zk, codes, scales, sr_key_t{0, 0}, st);
 }
 
 } // namespace adahop

@@ -44,6 +44,19 @@ def test_quantize_rejects_bad_operands(bad):
     assert L.adahop_iht_quantize(C.byref(x), 32, None, None, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
 
 
+def test_iht_quantize_sr_rejects_what_the_deterministic_entry_rejects():
+    L = ah.lib()
+    x = op(K=192)
+    f = lambda xx, b, zk, codes: L.adahop_iht_quantize_sr(None if xx is None else C.byref(xx), b, None, zk, 12345, codes,
+                                                           FAKE, None)
+    assert f(x, 48, None, FAKE) == ah.ADAHOP_E_INVALID_ARG
+    assert f(x, 128, None, FAKE) == ah.ADAHOP_E_INVALID_ARG        # 192 % 128
+    assert f(x, 64, FAKE + 4, FAKE) == ah.ADAHOP_E_INVALID_ARG     # mask alignment
+    assert f(x, 64, None, None) == ah.ADAHOP_E_INVALID_ARG
+    assert f(None, 64, None, FAKE) == ah.ADAHOP_E_INVALID_ARG
+    assert f(op(K=100), 0, None, FAKE) == ah.ADAHOP_E_INVALID_ARG
+
+
 def test_iht_quantize_rejects_bad_blocks_and_pointers():
     L = ah.lib()
     x = op(K=192)
