@@ -107,7 +107,7 @@ int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_ou
  * codes / scales in the canonical layout above; codes 16-byte aligned, K % 32 == 0.
  * workspace: device scratch of at least adahop_gemm_mx_workspace_bytes(M, N, K) bytes, 256-byte
  * aligned (the kernel keeps a re-ordered copy of the scales there); contents undefined on return.
- * With K % 256 == 0 and K >= 512 the whole 256x256 tiles of C take the tiled, LDS-pipelined kernel
+ * With K % 256 == 0 and K >= 768 the whole 256x256 tiles of C take the tiled, LDS-pipelined kernel
  * and only the ragged edges a slower bounds-checked kernel; any other K takes the latter throughout.
  * ------------------------------------------------------------------------------------------- */
 size_t adahop_gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);

@@ -264,24 +264,24 @@ __device__ __forceinline__ void read_scales(const uint8_t *buf, const tile_state
 }
 
 // Matrix-core instructions q0 .. q1-1 (of 16: instruction q is tile row q / 4, column q % 4) of step S.
-template <bool BF, int S> __device__ __forceinline__ void mma_some(const frags_t &f, tile_state_t &t, int q0, int q1)
+// ZC: the very first step of a tile -- the accumulator input is the constant 0, which starts the tile
+// without 256 register writes per lane to clear the accumulators.
+template <bool BF, int S, bool ZC>
+__device__ __forceinline__ void mma_some(const frags_t &f, tile_state_t &t, int q0, int q1)
 {
+    const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int q = q0; q < q1; ++q) {
         const int i = q >> 2, j = q & 3;
+        const v16f c = ZC ? zero : t.acc[i][j];
         if constexpr (BF) {
-            t.acc[i][j] = mfma_bf16(f.a[i], f.b[j], t.acc[i][j]);
+            t.acc[i][j] = mfma_bf16(f.a[i], f.b[j], c);
         } else {
             v8i av = {(int)f.a[i].x, (int)f.a[i].y, (int)f.a[i].z, (int)f.a[i].w, 0, 0, 0, 0};
             v8i bv = {(int)f.b[j].x, (int)f.b[j].y, (int)f.b[j].z, (int)f.b[j].w, 0, 0, 0, 0};
-            t.acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, t.acc[i][j], 4, 4, S, t.sc.a[i], S, t.sc.b[j]);
+            t.acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, c, 4, 4, S, t.sc.a[i], S, t.sc.b[j]);
         }
     }
-}
-
-template <bool BF, int S> __device__ __forceinline__ void mma_step(const frags_t &f, tile_state_t &t)
-{
-    mma_some<BF, S>(f, t, 0, 16);
 }
 
 // Copies d0 .. d1-1 of the 17 copies of one stage: copy 2g + o (g < 8) is row group g of slab o
@@ -333,14 +333,14 @@ template <bool TBF, int K> __device__ __forceinline__ void issue_slot(const tile
 //     the first instructions, and after them the scales of that buffer (RSC).
 // A wave issues in order, so a burst of LDS or copy instructions keeps it from feeding the matrix
 // cores; single instructions fit into the shadow of the matrix-core instruction before them.
-template <bool BF, int S, bool COND, bool TBF, int SLOT0, int RS, bool RSC, int U = 0>
+template <bool BF, int S, bool COND, bool TBF, int SLOT0, int RS, bool RSC, bool ZC = false, int U = 0>
 __device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t, int which, const uint8_t *rbuf, frags_t &rf)
 {
     constexpr int PER = 16 / SPS;                 // matrix-core instructions per unit
     constexpr int RUNITS = SPS < 8 ? SPS : 8;     // units that carry fragment reads
     constexpr int RPU = 8 / RUNITS;               // fragment reads per such unit
     if constexpr (U < SPS) {
-        mma_some<BF, S>(f, t, U * PER, (U + 1) * PER);
+        mma_some<BF, S, ZC>(f, t, U * PER, (U + 1) * PER);
         ADAHOP_PIN();
         if constexpr (RS >= 0 && U < RUNITS) {
 #pragma unroll
@@ -355,7 +355,7 @@ __device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t
             issue_slot<TBF, SLOT0 + U>(t, which);
             ADAHOP_PIN();
         }
-        mma_and_copies<BF, S, COND, TBF, SLOT0, RS, RSC, U + 1>(f, t, which, rbuf, rf);
+        mma_and_copies<BF, S, COND, TBF, SLOT0, RS, RSC, ZC, U + 1>(f, t, which, rbuf, rf);
     }
 }
 
@@ -368,14 +368,15 @@ __device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t
 //             (one barrier), then read its first fragments while the last step runs.
 //   ISSUE:    stage + 2 exists -- its copies go into the buffer just released, starting between the
 //             instructions of the last step.
+//   ZC:       first stage of the tile: its first step starts the accumulators from 0.
 // The body has no branches, so the order written here is the order that runs.
-template <bool BF, bool BF1, bool BF2, bool HAS_NEXT, bool ISSUE>
+template <bool BF, bool BF1, bool BF2, bool HAS_NEXT, bool ISSUE, bool ZC = false>
 __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, int stage)
 {
     const uint8_t *st = smem + (stage & 1) * STAGE_BYTES;
     const uint8_t *sn = smem + ((stage + 1) & 1) * STAGE_BYTES;
     // step j computes on the fragments read during step j - 1 and reads those of step j + 1
-    mma_and_copies<BF, 0, HAS_NEXT, BF1, SPS, 1, false>(t.f0, t, stage + 1, st, t.f1);
+    mma_and_copies<BF, 0, HAS_NEXT, BF1, SPS, 1, false, ZC>(t.f0, t, stage + 1, st, t.f1);
     mma_and_copies<BF, 1, HAS_NEXT, BF1, 2 * SPS, 2, false>(t.f1, t, stage + 1, st, t.f0);
     mma_and_copies<BF, 2, false, false, 0, 3, false>(t.f0, t, 0, st, t.f1);
     if constexpr (HAS_NEXT) {
@@ -388,7 +389,8 @@ __device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, 
 
 // The stage loop runs over the gathered bf16 K-channels first (OEK), then over the FP4 stages, on
 // one pipeline: `stage` counts over both.  Host side guarantees K >= 512 (two FP4 stages), so that
-// every bf16 stage has two successors and the last two stages are FP4 stages.
+// every bf16 stage has two successors and the last two stages are FP4 stages, and at least three
+// stages in all (K >= 768 when there are no bf16 stages).
 template <bool OEK, typename OUT>
 __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_t *__restrict__ a_codes,
                                                          const uint8_t *__restrict__ a_scales_sm,
@@ -455,12 +457,6 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     }
 
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) t.acc[i][j][r] = 0.0f;
-#pragma unroll
     for (int i = 0; i < 4; ++i) t.sc.a[i] = t.sc.b[i] = t.scn.a[i] = t.scn.b[i] = 0;
 
     // prologue: stage 0 copied and landed, the first slots of stage 1 under way (the rest of stage 1
@@ -483,19 +479,34 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     read_frags(smem, t, 0, t.f0);
     if constexpr (!OEK) read_scales(smem, t, t.sc);
 
-    int stage = 0;
+    // The first stage of the tile starts the accumulators (ZC); which kinds of stage follow it decides
+    // its variant, as for every later stage.
+    int stage = 1;
     if constexpr (OEK) {
-        for (; stage + 2 < t.nbf; ++stage) run_stage<true, true, true, true, true>(t, smem, stage);
-        if (stage + 1 < t.nbf) {
-            run_stage<true, true, false, true, true>(t, smem, stage);
+        if (t.nbf >= 3)
+            run_stage<true, true, true, true, true, true>(t, smem, 0);
+        else if (t.nbf == 2)
+            run_stage<true, true, false, true, true, true>(t, smem, 0);
+        else
+            run_stage<true, false, false, true, true, true>(t, smem, 0);
+        if (t.nbf >= 2) {
+            for (; stage + 2 < t.nbf; ++stage) run_stage<true, true, true, true, true>(t, smem, stage);
+            if (stage + 1 < t.nbf) {
+                run_stage<true, true, false, true, true>(t, smem, stage);
+                ++stage;
+            }
+            run_stage<true, false, false, true, true>(t, smem, stage);
             ++stage;
         }
-        run_stage<true, false, false, true, true>(t, smem, stage);
-        ++stage;
+        for (; stage + 2 < nstage; ++stage) run_stage<false, false, false, true, true>(t, smem, stage);
+        run_stage<false, false, false, true, false>(t, smem, stage);
+        run_stage<false, false, false, false, false>(t, smem, stage + 1);
+    } else { // host side guarantees at least three FP4 stages here
+        run_stage<false, false, false, true, true, true>(t, smem, 0);
+        for (; stage + 2 < nstage; ++stage) run_stage<false, false, false, true, true>(t, smem, stage);
+        run_stage<false, false, false, true, false>(t, smem, stage);
+        run_stage<false, false, false, false, false>(t, smem, stage + 1);
     }
-    for (; stage + 2 < nstage; ++stage) run_stage<false, false, false, true, true>(t, smem, stage);
-    run_stage<false, false, false, true, false>(t, smem, stage);
-    run_stage<false, false, false, false, false>(t, smem, stage + 1);
 
     if constexpr (sizeof(OUT) == 4) {
         float *crow = C + (m0 + wm * 128 + h * 4) * ldc + n0 + wn * 128 + l32;
@@ -579,8 +590,9 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     // The tiled kernel takes the whole 256x256 tiles; ragged edges (and shapes it cannot take at all) go to
     // the bounds-checked kernel.  Its bf16 epilogue stores 16 bytes per lane.
     const bool fast_c = sizeof(OUT) == 4 || (ldc % 8 == 0 && aligned(C, 16));
-    const bool fast_k =
-        fast_c && K % 256 == 0 && K >= 512 && kpad % 64 == 0 && aligned(a_scales, 8) && aligned(b_scales, 8);
+    // (at least three pipeline stages: 64 gathered channels or 256 K-elements each, two of them FP4 stages)
+    const bool fast_k = fast_c && K % 256 == 0 && K >= (kpad > 0 ? 512 : 768) && kpad % 64 == 0 &&
+                        aligned(a_scales, 8) && aligned(b_scales, 8);
     const int64_t Mi = fast_k ? M / TM * TM : 0, Ni = fast_k ? N / TN * TN : 0;
     if (Mi == 0 || Ni == 0 || (Mi / TM) * (Ni / TN) >= (1 << 30))
         return generic(M, N, a_codes, a_scales, b_codes, b_scales, C, Ag, Bg);
