@@ -248,6 +248,10 @@ def main():
             flop = ah.adahop_probe_mfma_rate(rnd, 256, 4000, sink)
             p_ms = time_ms(torch, lambda: ah.adahop_probe_mfma_rate(rnd, 256, 4000, sink), 3)
             probe[name] = flop / p_ms / 1e9
+        for idle in (1, 2):   # idle stretches between the instructions: the clock rises, the rate falls by less than the duty
+            flop = ah.adahop_probe_mfma_rate(1, 256, 4000, sink, idle_sleeps=idle)
+            p_ms = time_ms(torch, lambda: ah.adahop_probe_mfma_rate(1, 256, 4000, sink, idle_sleeps=idle), 3)
+            probe[f"random_operands_idle{idle}"] = flop / p_ms / 1e9
         extras["mfma_only_tflops"] = probe
         # quantiser bandwidth on the largest operand of the largest GEMM (2 + 1/2 + 1/32 bytes / element)
         qx = big.B if big.N >= big.M else big.A

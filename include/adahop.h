@@ -270,9 +270,12 @@ int adahop_select_strategy(adahop_pattern_t pattern_a, adahop_pattern_t pattern_
  * iters x 16 block-scaled FP4 matrix-core instructions (32x32x64, 131072 flop each) on register
  * operands only -- constant bits, or pseudo-random bits if random_operands != 0 -- so that a caller
  * timing the launch obtains the rate the matrix cores sustain on this machine without any memory
- * traffic: 2 * 65536 * 16 * iters * 4 * workgroups flop.  sink: one device float (never written in
- * practice).  Used by bench.py to report the power-limited ceiling beside the published peak. */
-int adahop_probe_mfma_rate(int random_operands, int workgroups, int iters, float *sink, void *stream);
+ * traffic: 2 * 65536 * 16 * iters * 4 * workgroups flop.  idle_sleeps (0..64): that many short sleeps
+ * after every 16 instructions, to see how the rate responds to idle stretches under the power limit.
+ * sink: one device float (never written in practice).  Used by bench.py to report the power-limited
+ * ceiling beside the published peak. */
+int adahop_probe_mfma_rate(int random_operands, int idle_sleeps, int workgroups, int iters, float *sink,
+                           void *stream);
 
 /* hipError_t (as int) of the most recent failed HIP call on this thread, 0 if none. */
 int adahop_last_hip_error(void);

@@ -86,7 +86,7 @@ def lib():
         L.adahop_detect_pattern_workspace_bytes.restype = SZ
         L.adahop_detect_pattern.argtypes = [OP, C.c_double, P, P, P, SZ, P]
         L.adahop_select_strategy.argtypes = [I, I, I, C.POINTER(C.c_int)]
-        L.adahop_probe_mfma_rate.argtypes = [I, I, I, P, P]
+        L.adahop_probe_mfma_rate.argtypes = [I, I, I, I, P, P]
         L.adahop_status_string.restype = C.c_char_p
         L.adahop_status_string.argtypes = [I]
         for name in EXPORTS:
@@ -282,9 +282,10 @@ def adahop_oe_gemm_bf16(A, B, kind, idx, Cout, gather_ws=None, stream=None):
     return Cout
 
 
-def adahop_probe_mfma_rate(random_operands, workgroups, iters, sink, stream=None):
+def adahop_probe_mfma_rate(random_operands, workgroups, iters, sink, stream=None, idle_sleeps=0):
     """Measurement aid: register-only matrix-core loop; returns the flop count of the launch."""
-    _check(lib().adahop_probe_mfma_rate(int(bool(random_operands)), workgroups, iters, _ptr(sink), _stream(stream)),
+    _check(lib().adahop_probe_mfma_rate(int(bool(random_operands)), int(idle_sleeps), workgroups, iters, _ptr(sink),
+                                        _stream(stream)),
            "adahop_probe_mfma_rate")
     return 2.0 * 65536 * 16 * iters * 4 * workgroups
 

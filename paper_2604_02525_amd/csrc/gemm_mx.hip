@@ -14,6 +14,8 @@
 // 8*(l/32) .. +7 of row / column l % 32.
 #include "common.h"
 
+#include <type_traits>
+
 namespace adahop {
 
 namespace {
@@ -218,7 +220,12 @@ struct scales_t {
 // order written here is what hides the LDS and copy-issue latency behind the matrix cores).
 #define ADAHOP_PIN() __builtin_amdgcn_sched_barrier(0)
 
-// Everything one wave keeps across the stages of a tile.
+// Where the copies of one tile come from: wave-uniform bases of its stage 0 (see k_gemm_mx_tile256).
+struct copy_src_t {
+    const uint8_t *ga, *gb, *gga, *ggb, *gs;
+};
+
+// Everything one wave keeps across stages and tiles.
 struct tile_state_t {
     v16f acc[4][4];
     frags_t f0, f1;
@@ -226,7 +233,8 @@ struct tile_state_t {
     // fragment reads: byte offsets inside a stage buffer
     int a_row, b_row, sa_row, sb_row, off[4];
     // copy engine (see k_gemm_mx_tile256)
-    const uint8_t *ga, *gb, *gga, *ggb, *gs; // wave-uniform bases of stage 0
+    copy_src_t cur, nxt;                     // the tile being computed and the one after it
+    int n;                                   // stages per tile
     uint32_t lrow, c_even, c_odd, vs;        // per-lane: row within an 8-row group, byte of its chunk in even / odd
                                              // groups, offset of the scale copy
     uint32_t pitch, gpitch;                  // bytes between rows of the codes / of the gathered bf16 operands
@@ -287,19 +295,21 @@ __device__ __forceinline__ void mma_some(const frags_t &f, tile_state_t &t, int 
 // Copies d0 .. d1-1 of the 17 copies of one stage: copy 2g + o (g < 8) is row group g of slab o
 // (0 = A, 1 = B), copy 16 the scales.  TBF: the stage is one of the gathered-bf16 stages, whose
 // operands have their own row pitch; such a stage has no scales and copy 16 is skipped.
-template <bool TBF, int D0, int D1> __device__ __forceinline__ void issue_copies(const tile_state_t &t, int stage)
+// `stage` is the stage's index within its tile (it decides the addresses), `buf` the LDS buffer (0 / 1).
+template <bool TBF, int D0, int D1>
+__device__ __forceinline__ void issue_copies(const tile_state_t &t, const copy_src_t &src, int stage, int buf)
 {
-    const uint32_t boff = (stage & 1) * STAGE_BYTES;
+    const uint32_t boff = buf * STAGE_BYTES;
     const int cs = stage - t.nbf;                      // index among the FP4 stages
     const uint32_t rp = TBF ? t.gpitch : t.pitch;      // row pitch of this stage's operands
-    const uint8_t *pa = TBF ? t.gga + (int64_t)stage * TKB : t.ga + (int64_t)cs * TKB;
-    const uint8_t *pb = TBF ? t.ggb + (int64_t)stage * TKB : t.gb + (int64_t)cs * TKB;
+    const uint8_t *pa = TBF ? src.gga + (int64_t)stage * TKB : src.ga + (int64_t)cs * TKB;
+    const uint8_t *pb = TBF ? src.ggb + (int64_t)stage * TKB : src.gb + (int64_t)cs * TKB;
     // row group g starts 8 g rows further: a wave-uniform term that goes into the base address
     const uint32_t v_even = t.lrow * rp + t.c_even, v_odd = t.lrow * rp + t.c_odd;
 #pragma unroll
     for (int d = D0; d < D1; ++d) {
         if (d == 16) {
-            if constexpr (!TBF) dma16(t.gs + (int64_t)cs * t.s_stride, t.vs, t.lds_s + boff);
+            if constexpr (!TBF) dma16(src.gs + (int64_t)cs * t.s_stride, t.vs, t.lds_s + boff);
         } else {
             const int g = d >> 1;
             const uint32_t vo = (g & 1) ? v_odd : v_even;
@@ -322,19 +332,22 @@ constexpr int SPREAD = 3, NSLOT = SPS * SPREAD; // the stage body wires up at mo
 static_assert(SPREAD >= 1 && SPREAD <= 3 && 16 % SPS == 0, "copy slots are placed in the last and the first two steps");
 constexpr int slot_lo(int k) { return 17 * k / NSLOT; }
 
-template <bool TBF, int K> __device__ __forceinline__ void issue_slot(const tile_state_t &t, int stage)
+template <bool TBF, int K>
+__device__ __forceinline__ void issue_slot(const tile_state_t &t, const copy_src_t &src, int stage, int buf)
 {
-    if constexpr (K < NSLOT) issue_copies<TBF, slot_lo(K), slot_lo(K + 1)>(t, stage);
+    if constexpr (K < NSLOT) issue_copies<TBF, slot_lo(K), slot_lo(K + 1)>(t, src, stage, buf);
 }
 
 // The 16 matrix-core instructions of step S on fragments f, and between them
-//   - the copy slots SLOT0 .. SLOT0 + SPS - 1 of stage `which` (COND: whether that stage exists);
+//   - the copy slots SLOT0 .. SLOT0 + SPS - 1 of stage `which` of the tile behind `src`, into LDS buffer
+//     `wbuf` (COND: whether that stage exists);
 //   - the eight fragment reads of step RS of buffer rbuf into rf (RS < 0: none), one at a time behind
 //     the first instructions, and after them the scales of that buffer (RSC).
 // A wave issues in order, so a burst of LDS or copy instructions keeps it from feeding the matrix
 // cores; single instructions fit into the shadow of the matrix-core instruction before them.
 template <bool BF, int S, bool COND, bool TBF, int SLOT0, int RS, bool RSC, bool ZC = false, int U = 0>
-__device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t, int which, const uint8_t *rbuf, frags_t &rf)
+__device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t, const copy_src_t &src, int which,
+                                               int wbuf, const uint8_t *rbuf, frags_t &rf)
 {
     constexpr int PER = 16 / SPS;                 // matrix-core instructions per unit
     constexpr int RUNITS = SPS < 8 ? SPS : 8;     // units that carry fragment reads
@@ -352,45 +365,151 @@ __device__ __forceinline__ void mma_and_copies(const frags_t &f, tile_state_t &t
             ADAHOP_PIN();
         }
         if constexpr (COND) {
-            issue_slot<TBF, SLOT0 + U>(t, which);
+            issue_slot<TBF, SLOT0 + U>(t, src, which, wbuf);
             ADAHOP_PIN();
         }
-        mma_and_copies<BF, S, COND, TBF, SLOT0, RS, RSC, ZC, U + 1>(f, t, which, rbuf, rf);
+        mma_and_copies<BF, S, COND, TBF, SLOT0, RS, RSC, ZC, U + 1>(f, t, src, which, wbuf, rbuf, rf);
     }
 }
 
-// One pipeline stage: four matrix-core steps on the fragments of buffer stage % 2.
+// One pipeline stage: four matrix-core steps on the fragments of LDS buffer f % 2, f counting the stages
+// of all tiles of the workgroup; l is the stage's index within its tile.
 //   BF:       this stage holds gathered bf16 K-channels (else FP4 codes and scales).
-//   BF1, BF2: the same for stages stage + 1 and stage + 2 (they decide what the copies fetch).
-//   HAS_NEXT: stage + 1 exists.  Its copies were begun during the previous stage (or the
+//   BF1, BF2: the same for the next stage and the one after it (they decide what the copies fetch).
+//   N1, N2:   that stage belongs to the NEXT tile of this workgroup (the pipeline runs on across tiles:
+//             the last two stages of a tile already fetch the first two of the following one).
+//   HAS_NEXT: a next stage exists.  Its copies were begun during the previous stage (or the
 //             prologue) and continue during the first steps of this one.  Before the last step,
 //             wait until it has landed and every wave has read its last fragments of this stage
 //             (one barrier), then read its first fragments while the last step runs.
-//   ISSUE:    stage + 2 exists -- its copies go into the buffer just released, starting between the
-//             instructions of the last step.
-//   ZC:       first stage of the tile: its first step starts the accumulators from 0.
+//   ISSUE:    the stage after the next exists -- its copies go into the buffer just released,
+//             starting between the instructions of the last step.
+//   ZC:       first stage of a tile: its first step starts the accumulators from 0.
 // The body has no branches, so the order written here is the order that runs.
-template <bool BF, bool BF1, bool BF2, bool HAS_NEXT, bool ISSUE, bool ZC = false>
-__device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, int stage)
+template <bool BF, bool BF1, bool BF2, bool HAS_NEXT, bool ISSUE, bool N1 = false, bool N2 = false, bool ZC = false>
+__device__ __forceinline__ void run_stage(tile_state_t &t, const uint8_t *smem, int l, int f)
 {
-    const uint8_t *st = smem + (stage & 1) * STAGE_BYTES;
-    const uint8_t *sn = smem + ((stage + 1) & 1) * STAGE_BYTES;
+    const uint8_t *st = smem + (f & 1) * STAGE_BYTES;
+    const uint8_t *sn = smem + ((f + 1) & 1) * STAGE_BYTES;
+    const copy_src_t &src1 = N1 ? t.nxt : t.cur, &src2 = N2 ? t.nxt : t.cur;
+    const int l1 = N1 ? l + 1 - t.n : l + 1, l2 = N2 ? l + 2 - t.n : l + 2;
+    const int b1 = (f + 1) & 1, b2 = f & 1;
     // step j computes on the fragments read during step j - 1 and reads those of step j + 1
-    mma_and_copies<BF, 0, HAS_NEXT, BF1, SPS, 1, false, ZC>(t.f0, t, stage + 1, st, t.f1);
-    mma_and_copies<BF, 1, HAS_NEXT, BF1, 2 * SPS, 2, false>(t.f1, t, stage + 1, st, t.f0);
-    mma_and_copies<BF, 2, false, false, 0, 3, false>(t.f0, t, 0, st, t.f1);
+    mma_and_copies<BF, 0, HAS_NEXT, BF1, SPS, 1, false, ZC>(t.f0, t, src1, l1, b1, st, t.f1);
+    mma_and_copies<BF, 1, HAS_NEXT, BF1, 2 * SPS, 2, false>(t.f1, t, src1, l1, b1, st, t.f0);
+    mma_and_copies<BF, 2, false, false, 0, 3, false>(t.f0, t, src1, 0, 0, st, t.f1);
     if constexpr (HAS_NEXT) {
         asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)" ::: "memory"); // next stage landed; my reads done
         __syncthreads();
     }
-    mma_and_copies<BF, 3, ISSUE, BF2, 0, (HAS_NEXT ? 0 : -1), (HAS_NEXT && !BF1)>(t.f1, t, stage + 2, sn, t.f0);
+    mma_and_copies<BF, 3, ISSUE, BF2, 0, (HAS_NEXT ? 0 : -1), (HAS_NEXT && !BF1)>(t.f1, t, src2, l2, b2, sn, t.f0);
     if constexpr (HAS_NEXT && !BF1) t.sc = t.scn;
 }
 
-// The stage loop runs over the gathered bf16 K-channels first (OEK), then over the FP4 stages, on
-// one pipeline: `stage` counts over both.  Host side guarantees K >= 512 (two FP4 stages), so that
-// every bf16 stage has two successors and the last two stages are FP4 stages, and at least three
-// stages in all (K >= 768 when there are no bf16 stages).
+// All stages of one tile, f0 being the running stage count at its start.  The last two stages fetch the
+// first two stages of the tile behind t.nxt.  (After its last tile a workgroup names that tile once more:
+// the fetched stages are never used, and the loop needs no second variant of its body.)
+// NBFC: 0 = no gathered bf16 stages; 1, 2 = that many; 3 = three or more.  A compile-time class, so that
+// the body of the tile loop is one straight sequence of stages (branches that each start the accumulators
+// make the register allocator spill them).
+template <int NBFC> __device__ __forceinline__ void run_tile(tile_state_t &t, const uint8_t *smem, int f0)
+{
+    const int n = t.n;
+    int l = 1;
+    if constexpr (NBFC == 0) {
+        run_stage<false, false, false, true, true, false, false, true>(t, smem, 0, f0);
+    } else if constexpr (NBFC == 1) {
+        run_stage<true, false, false, true, true, false, false, true>(t, smem, 0, f0);
+    } else if constexpr (NBFC == 2) {
+        run_stage<true, true, false, true, true, false, false, true>(t, smem, 0, f0);
+        run_stage<true, false, false, true, true>(t, smem, 1, f0 + 1);
+        l = 2;
+    } else {
+        run_stage<true, true, true, true, true, false, false, true>(t, smem, 0, f0);
+        for (; l + 2 < t.nbf; ++l) run_stage<true, true, true, true, true>(t, smem, l, f0 + l);
+        run_stage<true, true, false, true, true>(t, smem, l, f0 + l);
+        run_stage<true, false, false, true, true>(t, smem, l + 1, f0 + l + 1);
+        l += 2;
+    }
+    for (; l + 2 < n; ++l) run_stage<false, false, false, true, true>(t, smem, l, f0 + l);
+    // the two stages that reach into the next tile: its stage 0 is a bf16 stage iff there are any, its
+    // stage 1 iff there are two or more
+    run_stage<false, false, (NBFC >= 1), true, true, false, true>(t, smem, l, f0 + l);
+    run_stage<false, (NBFC >= 1), (NBFC >= 2), true, true, true, true>(t, smem, l + 1, f0 + l + 1);
+}
+
+// The accumulators of a finished tile -> C.  The two stage buffers may already hold the next tile, so the
+// bf16 path, which has to transpose through LDS, uses a small patch private to the wave beyond them; LDS
+// operations of one wave execute in order, so the patch needs no barrier.  For bf16 the host side
+// guarantees a 16-byte aligned C and ldc % 8 == 0.
+constexpr int PATCH_BYTES = 5120;                                  // per wave
+constexpr int KERNEL_LDS_BYTES = TILED_LDS_BYTES + 4 * PATCH_BYTES; // 159744 of the 163840 of a compute unit
+
+template <typename OUT>
+__device__ __forceinline__ void store_tile(tile_state_t &t, uint8_t *smem, OUT *__restrict__ C, int64_t ldc, int64_t m0,
+                                           int64_t n0, int w, int lane)
+{
+    const int l32 = lane & 31, h = lane >> 5, wm = w >> 1, wn = w & 1;
+    if constexpr (sizeof(OUT) == 4) {
+        // fp32: straight from the accumulator registers, 128-byte row segments (staging through LDS as below
+        // and storing whole rows, 16 bytes per lane, was measured and is no faster)
+        float *crow = C + (m0 + wm * 128 + h * 4) * ldc + n0 + wn * 128 + l32;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __builtin_nontemporal_store(t.acc[i][j][r],
+                                                &crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32]);
+    } else {
+        // bf16: a lane converts two consecutive accumulator rows into one packed pair, trades pairs with its
+        // neighbour and keeps, as one dword, two adjacent columns of one row (even lane: the low halves =
+        // rows 0, 2 of each four; odd lane: the high halves = rows 1, 3).  One patch = 32 rows x 64 columns
+        // (two accumulator tiles side by side: 128-byte row segments), pitch 144 bytes.
+        constexpr int BP = 144;
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        OUT *cbase = C + (m0 + wm * 128) * ldc + n0 + wn * 128;
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        uint8_t *patch = smem + TILED_LDS_BYTES + w * PATCH_BYTES;
+        const int odd = lane & 1;
+        // byte selector over {neighbour's pair (bytes 4-7), own pair (bytes 0-3)}
+        const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2) {
+                        const v16f &a = t.acc[i][jp * 2 + jj];
+                        const f2 pair = {a[r], a[r + 1]};
+                        const uint32_t p = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf2)); // RNE
+                        const uint32_t q = __builtin_amdgcn_update_dpp(0, p, 0xB1, 0xF, 0xF, true); // lane ^ 1's pair
+                        const int row = (r >> 2) * 8 + h * 4 + (r & 3) + odd;
+                        *reinterpret_cast<uint32_t *>(patch + row * BP + (jj * 32 + (l32 & ~1)) * 2) =
+                            __builtin_amdgcn_perm(q, p, sel);
+                    }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int prow = q * 8 + (lane >> 3);
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(patch + prow * BP + (lane & 7) * 16);
+                    __builtin_nontemporal_store(
+                        v, reinterpret_cast<u32x4 *>(cbase + (int64_t)(i * 32 + prow) * ldc + jp * 64 + (lane & 7) * 8));
+                }
+            }
+    }
+}
+
+// Persistent kernel: the grid has one workgroup per compute unit (or per tile, if there are fewer), and a
+// workgroup walks the tile sequence with the stride of the grid.  The stage pipeline of a tile runs over
+// the gathered bf16 K-channels first (OEK), then over the FP4 stages, and on into the next tile: while a
+// tile's accumulators are stored, the first two stages of the next one are already in LDS or on the way.
+// Host side guarantees K >= 512 (two FP4 stages), so that every bf16 stage has two successors and the
+// last two stages of a tile are FP4 stages, and at least three stages per tile (K >= 768 when there are
+// no bf16 stages).
 template <bool OEK, typename OUT>
 __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_t *__restrict__ a_codes,
                                                          const uint8_t *__restrict__ a_scales_sm,
@@ -404,46 +523,54 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-    // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with its
-    // own L2), so give every XCD a contiguous run of the tile sequence, and order that sequence in
-    // bands of group_m tile rows so that concurrently running tiles share A and B panels.
-    const int ntiles = tiles_m * tiles_n;
-    int tix = blockIdx.x;
-    if (ntiles % 8 == 0) tix = (tix & 7) * (ntiles >> 3) + (tix >> 3);
-    const int band = group_m * tiles_n;
-    const int first_m = (tix / band) * group_m;
-    const int gsz = min(group_m, tiles_m - first_m);
-    const int tm = first_m + (tix % band) % gsz;
-    const int tn = (tix % band) / gsz;
-    const int64_t m0 = (int64_t)tm * TM, n0 = (int64_t)tn * TN;
     const int wm = w >> 1, wn = w & 1;
+    const int ntiles = tiles_m * tiles_n;
+    const int grid = (int)gridDim.x;
+
+    // Position v of the walk -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each
+    // with its own L2) and the grid is a multiple of 8 whenever it is smaller than the tile count, so v % 8
+    // is the XCD of every tile of a workgroup: give each XCD a contiguous run of the tile sequence, and
+    // order that sequence in bands of group_m tile rows so that concurrently running tiles share A and B
+    // panels.
+    auto tile_origin = [&](int v, int64_t &m0, int64_t &n0) {
+        int tix = v;
+        if (ntiles % 8 == 0) tix = (v & 7) * (ntiles >> 3) + (v >> 3);
+        const int band = group_m * tiles_n;
+        const int first_m = (tix / band) * group_m;
+        const int gsz = min(group_m, tiles_m - first_m);
+        m0 = (int64_t)(first_m + (tix % band) % gsz) * TM;
+        n0 = (int64_t)((tix % band) / gsz) * TN;
+    };
 
     tile_state_t t;
     // ---- copy engine: wave w moves rows [64w, 64w+64) of both slabs, 8 rows per instruction.
     // Lane i of instruction g writes LDS row 8g + i/8, chunk position i%8, which must hold logical
     // chunk (i%8) ^ ((row/2) & 7) = (i%8) ^ (4*(g&1) + i/16).
+    t.lrow = lane >> 3;
+    t.c_even = ((lane & 7) ^ (lane >> 4)) * 16;
+    t.c_odd = t.c_even ^ 64;
+    t.pitch = (uint32_t)(K >> 1);
+    t.gpitch = (uint32_t)kpad * 2;
+    t.vs = lane * 16;
+    t.s_stride = (w < 2 ? M : N) * 8;
     {
-        t.lrow = lane >> 3;
-        t.c_even = ((lane & 7) ^ (lane >> 4)) * 16;
-        t.c_odd = t.c_even ^ 64;
-        t.pitch = (uint32_t)(K >> 1);
-        t.gpitch = (uint32_t)kpad * 2;
-        const int64_t pitch = t.pitch, gpitch = t.gpitch;
-        t.ga = uniform_ptr(a_codes + (m0 + w * 64) * (int64_t)pitch);
-        t.gb = uniform_ptr(b_codes + (n0 + w * 64) * (int64_t)pitch);
-        t.gga = uniform_ptr(reinterpret_cast<const uint8_t *>(Ag) + (m0 + w * 64) * (int64_t)gpitch);
-        t.ggb = uniform_ptr(reinterpret_cast<const uint8_t *>(Bg) + (n0 + w * 64) * (int64_t)gpitch);
-        // scales (stage-major): waves 0,1 move the two 1 KiB halves of the A slab's scales, waves 2,3 of B's
-        t.gs = uniform_ptr(w < 2 ? a_scales_sm + (m0 + w * 128) * 8 : b_scales_sm + (n0 + (w - 2) * 128) * 8);
-        t.vs = lane * 16;
-        t.s_stride = (w < 2 ? M : N) * 8;
         const uint32_t smem_base = __builtin_amdgcn_readfirstlane(lds_address(smem));
         t.lds_w = smem_base + w * 64 * TKB;
         t.lds_s = smem_base + SLAB_BYTES + w * 1024;
-        t.nbf = OEK ? (kpad >> 6) : 0;
     }
-    const int nstage = t.nbf + (int)(K >> 8);
+    t.nbf = OEK ? (kpad >> 6) : 0;
+    t.n = t.nbf + (int)(K >> 8);
+    auto tile_source = [&](int64_t m0, int64_t n0) {
+        const int64_t pitch = t.pitch, gpitch = t.gpitch;
+        copy_src_t c;
+        c.ga = uniform_ptr(a_codes + (m0 + w * 64) * pitch);
+        c.gb = uniform_ptr(b_codes + (n0 + w * 64) * pitch);
+        c.gga = uniform_ptr(reinterpret_cast<const uint8_t *>(Ag) + (m0 + w * 64) * gpitch);
+        c.ggb = uniform_ptr(reinterpret_cast<const uint8_t *>(Bg) + (n0 + w * 64) * gpitch);
+        // scales (stage-major): waves 0,1 move the two 1 KiB halves of the A slab's scales, waves 2,3 of B's
+        c.gs = uniform_ptr(w < 2 ? a_scales_sm + (m0 + w * 128) * 8 : b_scales_sm + (n0 + (w - 2) * 128) * 8);
+        return c;
+    };
 
     // ---- fragment reads: row l32 (+32 i) of the wave's slab, logical chunk 4h + s
     {
@@ -459,109 +586,55 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
 #pragma unroll
     for (int i = 0; i < 4; ++i) t.sc.a[i] = t.sc.b[i] = t.scn.a[i] = t.scn.b[i] = 0;
 
-    // prologue: stage 0 copied and landed, the first slots of stage 1 under way (the rest of stage 1
-    // follows during stage 0, as in every later stage), first fragments of stage 0 read.
-    // Host side guarantees at least two FP4 stages.
-    constexpr int PRO = slot_lo(SPS); // copies of the four slots that fall into the step before a stage
+    int v = blockIdx.x;
+    int64_t m0, n0;
+    tile_origin(v, m0, n0);
+    t.cur = tile_source(m0, n0);
+    t.nxt = t.cur;
+
+    // prologue: stage 0 of the first tile copied and landed, the first slots of its stage 1 under way
+    // (the rest of stage 1 follows during stage 0, as in every later stage), first fragments of stage 0 read.
+    constexpr int PRO = slot_lo(SPS); // copies of the slots that fall into the step before a stage
     if constexpr (OEK) {
-        issue_copies<true, 0, 17>(t, 0);
+        issue_copies<true, 0, 17>(t, t.cur, 0, 0);
         if (t.nbf > 1)
-            issue_copies<true, 0, PRO>(t, 1);
+            issue_copies<true, 0, PRO>(t, t.cur, 1, 1);
         else
-            issue_copies<false, 0, PRO>(t, 1);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PRO) : "memory");
+            issue_copies<false, 0, PRO>(t, t.cur, 1, 1);
     } else {
-        issue_copies<false, 0, 17>(t, 0);
-        issue_copies<false, 0, PRO>(t, 1);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PRO) : "memory");
+        issue_copies<false, 0, 17>(t, t.cur, 0, 0);
+        issue_copies<false, 0, PRO>(t, t.cur, 1, 1);
     }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PRO) : "memory");
     __syncthreads();
     read_frags(smem, t, 0, t.f0);
     if constexpr (!OEK) read_scales(smem, t, t.sc);
 
-    // The first stage of the tile starts the accumulators (ZC); which kinds of stage follow it decides
-    // its variant, as for every later stage.
-    int stage = 1;
-    if constexpr (OEK) {
-        if (t.nbf >= 3)
-            run_stage<true, true, true, true, true, true>(t, smem, 0);
-        else if (t.nbf == 2)
-            run_stage<true, true, false, true, true, true>(t, smem, 0);
-        else
-            run_stage<true, false, false, true, true, true>(t, smem, 0);
-        if (t.nbf >= 2) {
-            for (; stage + 2 < t.nbf; ++stage) run_stage<true, true, true, true, true>(t, smem, stage);
-            if (stage + 1 < t.nbf) {
-                run_stage<true, true, false, true, true>(t, smem, stage);
-                ++stage;
-            }
-            run_stage<true, false, false, true, true>(t, smem, stage);
-            ++stage;
+    auto walk = [&](auto nbfc) {
+        for (int f = 0;; f += t.n) {
+            const int vn = v + grid;
+            const bool more = vn < ntiles; // same for the whole workgroup
+            int64_t m0n, n0n;
+            tile_origin(more ? vn : v, m0n, n0n);
+            t.nxt = tile_source(m0n, n0n);
+            run_tile<decltype(nbfc)::value>(t, smem, f);
+            store_tile(t, smem, C, ldc, m0, n0, w, lane);
+            if (!more) break;
+            v = vn;
+            m0 = m0n;
+            n0 = n0n;
+            t.cur = t.nxt;
         }
-        for (; stage + 2 < nstage; ++stage) run_stage<false, false, false, true, true>(t, smem, stage);
-        run_stage<false, false, false, true, false>(t, smem, stage);
-        run_stage<false, false, false, false, false>(t, smem, stage + 1);
-    } else { // host side guarantees at least three FP4 stages here
-        run_stage<false, false, false, true, true, true>(t, smem, 0);
-        for (; stage + 2 < nstage; ++stage) run_stage<false, false, false, true, true>(t, smem, stage);
-        run_stage<false, false, false, true, false>(t, smem, stage);
-        run_stage<false, false, false, false, false>(t, smem, stage + 1);
-    }
-
-    if constexpr (sizeof(OUT) == 4) {
-        float *crow = C + (m0 + wm * 128 + h * 4) * ldc + n0 + wn * 128 + l32;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    __builtin_nontemporal_store(t.acc[i][j][r],
-                                                &crow[(int64_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * ldc + j * 32]);
-    } else {
-        // bf16 C, staged through LDS so that global memory sees whole 256-byte row segments.  A lane holds one
-        // column: it converts two consecutive accumulator rows into one packed pair, trades pairs with its
-        // neighbour and keeps, as one dword, two adjacent columns of one row (even lane: the low halves = rows
-        // 0, 2 of each four; odd lane: the high halves = rows 1, 3).
-        // Each wave stages its 128x128 block in two halves of 64 rows in a private region (pitch 272 bytes),
-        // then reads rows back 16 bytes per lane.  Host side guarantees ldc % 8 == 0 and a 16-byte aligned C.
-        constexpr int CP = 272;
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-        __syncthreads(); // every wave is done with the operand slabs
-        uint8_t *stage = smem + w * (64 * CP);
-        typedef float f2 __attribute__((ext_vector_type(2)));
-        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
-        const int odd = lane & 1;
-        // byte selector over {neighbour's pair (bytes 4-7), own pair (bytes 0-3)}
-        const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
-        OUT *cbase = C + (m0 + wm * 128) * ldc + n0 + wn * 128;
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-#pragma unroll
-            for (int ii = 0; ii < 2; ++ii)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; r += 2) {
-                        const v16f &a = t.acc[half * 2 + ii][j];
-                        const f2 pair = {a[r], a[r + 1]};
-                        const uint32_t p = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf2)); // RNE
-                        const uint32_t q = __builtin_amdgcn_update_dpp(0, p, 0xB1, 0xF, 0xF, true); // lane ^ 1's pair
-                        const int row = ii * 32 + (r >> 2) * 8 + h * 4 + (r & 3) + odd;
-                        *reinterpret_cast<uint32_t *>(stage + row * CP + (j * 32 + (l32 & ~1)) * 2) =
-                            __builtin_amdgcn_perm(q, p, sel);
-                    }
-            __syncthreads();
-#pragma unroll 4
-            for (int q = 0; q < 16; ++q) {
-                const int row = q * 4 + (lane >> 4);
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + row * CP + (lane & 15) * 16);
-                __builtin_nontemporal_store(
-                    v, reinterpret_cast<u32x4 *>(cbase + (int64_t)(half * 64 + row) * ldc + (lane & 15) * 8));
-            }
-            if (half == 0) __syncthreads();
-        }
-    }
+    };
+    if constexpr (!OEK)
+        walk(std::integral_constant<int, 0>{});
+    else if (t.nbf == 1)
+        walk(std::integral_constant<int, 1>{});
+    else if (t.nbf == 2)
+        walk(std::integral_constant<int, 2>{});
+    else
+        walk(std::integral_constant<int, 3>{});
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // the copies begun for a tile that does not follow
 }
 
 } // namespace
@@ -589,7 +662,7 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     };
     // The tiled kernel takes the whole 256x256 tiles; ragged edges (and shapes it cannot take at all) go to
     // the bounds-checked kernel.  Its bf16 epilogue stores 16 bytes per lane.
-    const bool fast_c = sizeof(OUT) == 4 || (ldc % 8 == 0 && aligned(C, 16));
+    const bool fast_c = sizeof(OUT) == 4 || (aligned(C, 16) && ldc % 8 == 0);
     // (at least three pipeline stages: 64 gathered channels or 256 K-elements each, two of them FP4 stages)
     const bool fast_k = fast_c && K % 256 == 0 && K >= (kpad > 0 ? 512 : 768) && kpad % 64 == 0 &&
                         aligned(a_scales, 8) && aligned(b_scales, 8);
@@ -600,12 +673,22 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     static bool configured = false; // per output type
     if (!configured) {
         int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false, OUT>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
         if (rc != ADAHOP_OK) return rc;
         rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true, OUT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, TILED_LDS_BYTES));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
         if (rc != ADAHOP_OK) return rc;
         configured = true;
+    }
+    int ncu = 0;
+    {
+        int dev = 0;
+        int rc = check_hip(hipGetDevice(&dev));
+        if (rc != ADAHOP_OK) return rc;
+        rc = check_hip(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+        if (rc != ADAHOP_OK) return rc;
+        ncu = ncu / 8 * 8; // keep a workgroup's tiles on one XCD
+        if (ncu < 8) ncu = 8;
     }
     // scales of the tiled part, stage-major, in the caller's workspace
     uint8_t *a_sm = static_cast<uint8_t *>(workspace);
@@ -619,12 +702,14 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     if (rc != ADAHOP_OK) return rc;
     const int tiles_m = (int)(Mi / TM), tiles_n = (int)(Ni / TN);
     const int group_m = tiles_m < 8 ? tiles_m : 8;
-    const dim3 grid((unsigned)(tiles_m * tiles_n));
+    // one workgroup per compute unit walks the tiles (each workgroup fills a compute unit's LDS and registers)
+    const int ntiles = tiles_m * tiles_n;
+    const dim3 grid((unsigned)(ntiles < ncu ? ntiles : ncu));
     if (kpad > 0)
-        hipLaunchKernelGGL((k_gemm_mx_tile256<true, OUT>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
+        hipLaunchKernelGGL((k_gemm_mx_tile256<true, OUT>), grid, dim3(256), KERNEL_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
                            b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
     else
-        hipLaunchKernelGGL((k_gemm_mx_tile256<false, OUT>), grid, dim3(256), TILED_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
+        hipLaunchKernelGGL((k_gemm_mx_tile256<false, OUT>), grid, dim3(256), KERNEL_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
                            b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
     rc = check_launch();
     if (rc != ADAHOP_OK) return rc;

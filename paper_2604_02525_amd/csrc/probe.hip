@@ -23,8 +23,10 @@ __device__ __forceinline__ uint32_t mix(uint32_t x)
 }
 
 // One workgroup of four waves per launch slot; every wave runs iters x 16 independent instructions
-// (a 4 x 4 arrangement of accumulators over 4 + 4 operand fragments, as in the GEMM).
-__global__ __launch_bounds__(256) void k_probe_mfma(int random_operands, int iters, float *sink)
+// (a 4 x 4 arrangement of accumulators over 4 + 4 operand fragments, as in the GEMM).  idle_sleeps > 0 puts
+// that many short sleeps after every 16 instructions: under a power limit the clock rises when the matrix
+// cores idle part of the time, so the rate falls by much less than the duty cycle.
+__global__ __launch_bounds__(256) void k_probe_mfma(int random_operands, int idle_sleeps, int iters, float *sink)
 {
     v16f acc[16];
 #pragma unroll
@@ -46,6 +48,7 @@ __global__ __launch_bounds__(256) void k_probe_mfma(int random_operands, int ite
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 acc[i * 4 + j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i * 4 + j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+        for (int g = 0; g < idle_sleeps; ++g) __builtin_amdgcn_s_sleep(8); // an idle stretch after every 16 instructions
     }
     float s = 0.0f;
 #pragma unroll
@@ -61,10 +64,12 @@ __global__ __launch_bounds__(256) void k_probe_mfma(int random_operands, int ite
 
 using namespace adahop;
 
-extern "C" int adahop_probe_mfma_rate(int random_operands, int workgroups, int iters, float *sink, void *stream)
+extern "C" int adahop_probe_mfma_rate(int random_operands, int idle_sleeps, int workgroups, int iters, float *sink,
+                                      void *stream)
 {
+    if (idle_sleeps < 0 || idle_sleeps > 64) return ADAHOP_E_INVALID_ARG;
     if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24) || !sink) return ADAHOP_E_INVALID_ARG;
     hipLaunchKernelGGL(k_probe_mfma, dim3((unsigned)workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       random_operands, iters, sink);
+                       random_operands, idle_sleeps, iters, sink);
     return check_launch();
 }
