@@ -22,7 +22,7 @@ BF16_PEAK_TFLOPS = 2516.0
 # HBM bytes per launch of the FP4 GEMM kernel, by (M, N, K): rocprofv3 FETCH_SIZE + WRITE_SIZE (KiB per
 # dispatch), each scaled by what the same counter reads for a plain 1 GiB copy (--copy-calibration);
 # the runs and the scaling are in profiles/gemm_mx_16384x28672x8192_counters.txt.
-GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 4.89e9}
+GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 5.05e9}
 
 
 def parse():
@@ -34,6 +34,9 @@ def parse():
     p.add_argument("--k-pct", type=float, default=1.0, help="extraction count as %% of the extracted dim (cfg4)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the k-sweep / BF16 / per-stage extras")
+    p.add_argument("--dominant-kernel-only", action="store_true",
+                   help="profiling aid: time only the FP4 GEMM of the largest product (the roofline object); the "
+                        "whole-step figures of the JSON line are then absent")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run one plain 1 GiB device-to-device copy (reference reading for rocprofv3's "
                         "FETCH_SIZE / WRITE_SIZE counters)")
@@ -143,19 +146,22 @@ def main():
         for p in prepared:
             run_gemm(ah, p, ws)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_per_step = max(e0.elapsed_time(e1) / args.steps, 0.0)
-    value = total_flops / (ms_per_step * 1e-3) / 1e12
+    if args.dominant_kernel_only:
+        wall_ms = ms_per_step = value = None
+    else:
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ms_per_step = max(e0.elapsed_time(e1) / args.steps, 0.0)
+        value = total_flops / (ms_per_step * 1e-3) / 1e12
 
     # Dominant kernel: the FP4 GEMM alone on the largest GEMM's quantised operands.
     big = max(prepared, key=lambda p: p.flops)
@@ -179,9 +185,10 @@ def main():
            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "mxfp4 (e2m1 x e8m0) with fp32 accumulate; bf16 outlier path", "data": "synthetic",
            "config": {"workload": desc, "gemms": [p.g.name for p in prepared], "flops_per_step": total_flops},
-           "pct_mxfp4_peak": 100.0 * value / MXFP4_PEAK_TFLOPS, "wall_ms_per_step": wall_ms, "roofline": roofline}
+           "pct_mxfp4_peak": None if value is None else 100.0 * value / MXFP4_PEAK_TFLOPS,
+           "wall_ms_per_step": wall_ms, "roofline": roofline}
 
-    if not args.no_extras:
+    if not args.no_extras and not args.dominant_kernel_only:
         extras = {}
         # per-GEMM pipeline time and the same GEMM with pure IHT (no extraction)
         per = []
@@ -272,7 +279,7 @@ def main():
         out["copy_calibration_bytes"] = src.numel() * 4
         del src, dst
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.dominant_kernel_only:
         out["cpu_baseline"] = cpu_baseline(gemms)
 
     print(json.dumps(out))
