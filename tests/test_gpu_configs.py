@@ -117,3 +117,73 @@ def test_patterns_and_strategy_selection_on_config_tensors(ah):
         if kind == "wgrad":
             assert ah.adahop_select_strategy(pats[0], pats[1], 2) == (inputs.NONE, True)
     torch.cuda.empty_cache()
+
+
+# ----------------------------------------------------------------------------- variants at full size
+
+def test_config4_bf16_output_and_packed_operands(ah):
+    """configs[4] up-projection, forward (OE-K) and dgrad (OE-row): bf16 C equals the fp32 path's C rounded once,
+    bit for bit over the whole 16384 x 28672 (x 8192) output; operands packed once give the same bits as packing
+    inside the call; a sampled block is within half a bf16 step (+ the fp32 accumulation allowance) of the oracle."""
+    from test_gpu_reuse_bf16 import bits_of, check_bf16_against_oracle
+    gemms = inputs.config4(which=("up",), strategies=(inputs.IHT_OE_K, inputs.IHT_OE_ROW, inputs.IHT), k_pct=1.0)
+    for g in gemms[:2]:
+        say("config4 variants", g.name, inputs.STRATEGY_NAMES[g.strategy], g.shape)
+        A, B = dev_op(ah, g.A), dev_op(ah, g.B)
+        plain = ah.adahop_gemm(A, B, g.strategy, g.iht_block, g.k)
+        idx = plain["idx"].clone()
+        c32 = plain["C"]
+        ref_bits = c32.to(torch.bfloat16)
+        pa = ah.adahop_pack_operand(A, 0, g.strategy, g.iht_block, g.k, idx)
+        pb = ah.adahop_pack_operand(B, 1, g.strategy, g.iht_block, g.k, idx)
+        assert torch.equal(pa[0], plain["a_codes"]) and torch.equal(pa[1], plain["a_scales"])
+        assert torch.equal(pb[0], plain["b_codes"]) and torch.equal(pb[1], plain["b_scales"])
+        del plain
+        out = ah.adahop_gemm(A, B, g.strategy, g.iht_block, g.k, idx=idx, a_packed=pa, b_packed=pb, c_bf16=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out["C"].view(torch.int16), ref_bits.view(torch.int16))
+        rows, cols = sample(g)
+        ref = orc.adahop_gemm(g.A.bits, g.A.k_contig, g.B.bits, g.B.k_contig, g.strategy, g.iht_block, g.k,
+                              rows=rows, cols=cols)
+        sub = out["C"][torch.from_numpy(rows.astype(np.int64)).cuda()][:, torch.from_numpy(cols.astype(np.int64)).cuda()]
+
+        class Sub:                      # the sampled rows of A / columns of B as operands, for the norms of the bar
+            def __init__(self, op, sel):
+                v = op.bits if op.k_contig else op.bits.T
+                self.bits, self.k_contig = np.ascontiguousarray(v[sel]), True
+        check_bf16_against_oracle(bits_of(sub.contiguous()), ref["C"], Sub(g.A, rows), Sub(g.B, cols), "sample vs oracle")
+        del out, c32, ref_bits, pa, pb
+        torch.cuda.empty_cache()
+
+
+def test_stochastic_rounding_full_size_operand(ah):
+    """The configs[4] activation (16384 x 8192, K-contiguous) and its K-strided view as a weight-gradient operand:
+    every code and scale byte against the oracle's stochastic quantiser."""
+    g = inputs.config4(which=("up",), strategies=(inputs.IHT, inputs.IHT, inputs.IHT), k_pct=0.0)[0]
+    say("SR full size", g.A.bits.shape)
+    x = dev_op(ah, g.A)
+    codes, scales = ah.adahop_iht_quantize(x, 256, sr_seed=2024)
+    torch.cuda.synchronize()
+    rc, rs = orc.iht_quantize(g.A.bits, g.A.k_contig, 256, sr_seed=2024)
+    assert np.array_equal(host(scales), rs) and np.array_equal(host(codes), rc)
+    xs = ah.Operand.from_bits(g.A.bits, False)            # the same array read as [K = 16384, outer = 8192]
+    codes, scales = ah.adahop_iht_quantize(xs, 256, sr_seed=7)
+    torch.cuda.synchronize()
+    rc, rs = orc.iht_quantize(g.A.bits, False, 256, sr_seed=7)
+    assert np.array_equal(host(scales), rs) and np.array_equal(host(codes), rc)
+
+
+def test_oht_strategy_large_shape(ah):
+    """Eq. 6 at a size where the rotations of C span many workgroups: 2048 x 3072 x 4096, block 128."""
+    M, N, K, b = 2048, 3072, 4096, 128
+    A = inputs.Operand(inputs.matrix(M, K, 1.0, 4100, row_outliers=(10, 100.0, 100.0)), True)
+    B = inputs.Operand(inputs.matrix(N, K, 0.02, 4101, row_outliers=(15, 30.0, 30.0)), True)
+    say("OHT large", (M, N, K))
+    out = ah.adahop_gemm(dev_op(ah, A), dev_op(ah, B), inputs.OHT, b)
+    torch.cuda.synchronize()
+    ref = orc.oht_gemm(A.bits, True, B.bits, True, b)
+    for name in ("a_scales", "b_scales", "a_codes", "b_codes"):
+        assert np.array_equal(host(out[name]), ref[name]), name
+    err = np.linalg.norm(host(out["C"]).astype(np.float64) - ref["C"]) / np.linalg.norm(ref["C"])
+    say(f"  vs oracle {err:.2e}")
+    assert err < 1e-3
