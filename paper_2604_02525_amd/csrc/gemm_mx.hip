@@ -14,6 +14,7 @@
 // 8*(l/32) .. +7 of row / column l % 32.
 #include "common.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace adahop {
@@ -670,25 +671,24 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     if (Mi == 0 || Ni == 0 || (Mi / TM) * (Ni / TN) >= (1 << 30))
         return generic(M, N, a_codes, a_scales, b_codes, b_scales, C, Ag, Bg);
 
-    static bool configured = false; // per output type
-    if (!configured) {
+    int dev = 0, ncu = 0;
+    int rc0 = check_hip(hipGetDevice(&dev));
+    if (rc0 != ADAHOP_OK) return rc0;
+    rc0 = check_hip(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (rc0 != ADAHOP_OK) return rc0;
+    ncu = ncu / 8 * 8; // keep a workgroup's tiles on one XCD
+    if (ncu < 8) ncu = 8;
+    // the kernels need more LDS than a launch may ask for by default: once per output type and device
+    static std::atomic<uint64_t> configured{0};
+    const uint64_t dev_bit = dev < 64 ? (uint64_t)1 << dev : 0;
+    if (!(configured.load() & dev_bit)) {
         int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false, OUT>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
         if (rc != ADAHOP_OK) return rc;
         rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true, OUT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
         if (rc != ADAHOP_OK) return rc;
-        configured = true;
-    }
-    int ncu = 0;
-    {
-        int dev = 0;
-        int rc = check_hip(hipGetDevice(&dev));
-        if (rc != ADAHOP_OK) return rc;
-        rc = check_hip(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
-        if (rc != ADAHOP_OK) return rc;
-        ncu = ncu / 8 * 8; // keep a workgroup's tiles on one XCD
-        if (ncu < 8) ncu = 8;
+        configured.fetch_or(dev_bit);
     }
     // scales of the tiled part, stage-major, in the caller's workspace
     uint8_t *a_sm = static_cast<uint8_t *>(workspace);
