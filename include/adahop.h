@@ -257,6 +257,13 @@ size_t adahop_detect_pattern_workspace_bytes(const adahop_operand_t *x);
 int adahop_detect_pattern(const adahop_operand_t *x, double tau, int32_t *pattern_out, double *stats_out,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* The calibrated pattern of a tensor from its per-step classifications (Sec. 4.1: the paper classifies every
+ * tensor at each of 30 calibration steps and keeps the majority).  patterns: HOST array of n values of
+ * adahop_pattern_t (what adahop_detect_pattern wrote, copied back by the caller).  Returns the class that
+ * occurs most often; when several classes share the top count, ADAHOP_PATTERN_NONE.  Host-side, no GPU work.
+ * Returns ADAHOP_E_INVALID_ARG (negative) for a null array, n < 1 or a value outside the enum. */
+int adahop_vote_pattern(const int32_t *patterns, int n);
+
 /* Strategy for the product of A and B from their patterns (Sec. 4.2; host-side, no GPU work):
  *   B outer-wise (the paper's RC, NC, CC)              -> ADAHOP_IHT_OE_COL  (OE-Right)
  *   else A outer-wise (RN; RR by the same argument)    -> ADAHOP_IHT_OE_ROW  (OE-Left)

@@ -358,6 +358,17 @@ def detect_pattern(bits, k_contig, tau=2.0, eps=1e-12):
     return p, np.array([cv_outer, cv_k, hat_outer, hat_k])
 
 
+def vote_pattern(patterns):
+    """Sec. 4.1: the calibrated pattern of a tensor is the majority among its per-step classifications (the
+    paper calibrates over 30 steps).  The class that occurs most often wins; when two or three classes share
+    the top count no pattern dominates and the result is PATTERN_NONE (the paper does not say; NONE is the
+    class that claims no structure, and it sends the pair to plain IHT)."""
+    counts = [sum(1 for p in patterns if p == c) for c in (PATTERN_NONE, PATTERN_OUTER, PATTERN_K)]
+    best = max(counts)
+    winners = [c for c in (PATTERN_NONE, PATTERN_OUTER, PATTERN_K) if counts[c] == best]
+    return winners[0] if len(winners) == 1 else PATTERN_NONE
+
+
 def select_strategy(pattern_a, pattern_b, level=1):
     """Sec. 4.2: pairs whose outliers lie along K in both operands (CN, NN, CR) take IHT alone; outlier
     rows of A (RN) take OE-Left; outlier columns of B (RC, NC, CC) take OE-Right; AdaHOP-Lv2 computes CC

@@ -22,7 +22,7 @@ EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "ada
            "adahop_oht_quantize", "adahop_oht_inverse", "adahop_iht_quantize_sr",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
            "adahop_oe_gemm_bf16", "adahop_detect_pattern_workspace_bytes", "adahop_detect_pattern",
-           "adahop_select_strategy", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
+           "adahop_select_strategy", "adahop_vote_pattern", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
            "adahop_abi_version"]
 
 
@@ -86,6 +86,7 @@ def lib():
         L.adahop_detect_pattern_workspace_bytes.restype = SZ
         L.adahop_detect_pattern.argtypes = [OP, C.c_double, P, P, P, SZ, P]
         L.adahop_select_strategy.argtypes = [I, I, I, C.POINTER(C.c_int)]
+        L.adahop_vote_pattern.argtypes = [C.POINTER(C.c_int32), I]
         L.adahop_probe_mfma_rate.argtypes = [I, I, I, I, P, P]
         L.adahop_status_string.restype = C.c_char_p
         L.adahop_status_string.argtypes = [I]
@@ -301,6 +302,15 @@ def adahop_detect_pattern(x, tau=2.0, workspace=None, stream=None):
     _check(lib().adahop_detect_pattern(C.byref(x.c()), float(tau), _ptr(pattern), _ptr(stats), _ptr(workspace),
                                        workspace.numel(), _stream(stream)), "adahop_detect_pattern")
     return pattern, stats
+
+
+def adahop_vote_pattern(patterns):
+    """Majority class of a sequence of per-step patterns (host-side)."""
+    arr = (C.c_int32 * len(patterns))(*[int(p) for p in patterns])
+    r = lib().adahop_vote_pattern(arr, len(patterns))
+    if r < 0:
+        raise AdahopError(r, "adahop_vote_pattern")
+    return r
 
 
 def adahop_select_strategy(pattern_a, pattern_b, level=1):

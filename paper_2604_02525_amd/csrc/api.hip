@@ -235,6 +235,22 @@ int adahop_detect_pattern(const adahop_operand_t *x, double tau, int32_t *patter
     return launch_detect_pattern(*x, tau, 1e-12, pattern_out, stats_out, workspace, static_cast<hipStream_t>(stream));
 }
 
+int adahop_vote_pattern(const int32_t *patterns, int n)
+{
+    if (!patterns || n < 1) return ADAHOP_E_INVALID_ARG;
+    int count[3] = {0, 0, 0};
+    for (int i = 0; i < n; ++i) {
+        if (patterns[i] < ADAHOP_PATTERN_NONE || patterns[i] > ADAHOP_PATTERN_K) return ADAHOP_E_INVALID_ARG;
+        ++count[patterns[i]];
+    }
+    int best = ADAHOP_PATTERN_NONE;
+    for (int c = ADAHOP_PATTERN_OUTER; c <= ADAHOP_PATTERN_K; ++c)
+        if (count[c] > count[best]) best = c;
+    for (int c = ADAHOP_PATTERN_NONE; c <= ADAHOP_PATTERN_K; ++c)
+        if (c != best && count[c] == count[best]) return ADAHOP_PATTERN_NONE; // no single most frequent class
+    return best;
+}
+
 int adahop_select_strategy(adahop_pattern_t pattern_a, adahop_pattern_t pattern_b, int level, int *full_bf16)
 {
     auto ok = [](int p) { return p == ADAHOP_PATTERN_NONE || p == ADAHOP_PATTERN_OUTER || p == ADAHOP_PATTERN_K; };

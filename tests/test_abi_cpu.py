@@ -254,3 +254,18 @@ def test_pattern_argument_checks_and_strategy_table():
         ah.adahop_select_strategy(3, N)
     with pytest.raises(ah.AdahopError):
         ah.adahop_select_strategy(N, N, 3)
+
+
+def test_vote_pattern_matches_the_oracle_and_rejects_bad_input():
+    """Host-side function: compared with the oracle on every multiset of up to 7 votes, plus the error paths."""
+    import itertools
+    from oracle import reference as orc
+    L = ah.lib()
+    for n in range(1, 8):
+        for votes in itertools.combinations_with_replacement((0, 1, 2), n):
+            assert ah.adahop_vote_pattern(list(votes)) == orc.vote_pattern(list(votes)), votes
+    assert ah.adahop_vote_pattern([2] * 17 + [0] * 13) == ah.ADAHOP_PATTERN_K
+    arr = (C.c_int32 * 3)(0, 3, 1)
+    assert L.adahop_vote_pattern(arr, 3) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_vote_pattern(arr, 0) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_vote_pattern(None, 3) == ah.ADAHOP_E_INVALID_ARG

@@ -119,6 +119,36 @@ def test_patterns_and_strategy_selection_on_config_tensors(ah):
     torch.cuda.empty_cache()
 
 
+def test_calibration_phase_end_to_end(ah):
+    """The calibration of Sec. 4.1 with this library's pieces: classify the operands of a dgrad-like product at every
+    step of a short run of fresh synthetic tensors (the paper uses 30 steps; 9 here), vote, select, and run the
+    selected strategy.  A few steps carry no planted outliers, so the per-step classes are not all equal; every
+    per-step class and the outcome must equal the oracle's."""
+    steps, T, d_out, d_in = 9, 1024, 1024, 768
+    votes_a, votes_b = [], []
+    for s in range(steps):
+        quiet = s in (2, 5)                     # steps whose gradient shows no outlier rows
+        G = inputs.Operand(inputs.matrix(T, d_out, 1e-3, 9000 + s, row_outliers=None if quiet else (5, 100.0, 100.0)), True)
+        W = inputs.Operand(inputs.matrix(d_out, d_in, 0.02, 9100 + s), False)
+        for x, votes in ((G, votes_a), (W, votes_b)):
+            p, _ = ah.adahop_detect_pattern(dev_op(ah, x))
+            torch.cuda.synchronize()
+            got = int(host(p)[0])
+            assert got == orc.detect_pattern(x.bits, x.k_contig)[0]
+            votes.append(got)
+    say("calibration votes A", votes_a, "B", votes_b)
+    assert len(set(votes_a)) > 1                # the vote has something to decide
+    pa, pb = ah.adahop_vote_pattern(votes_a), ah.adahop_vote_pattern(votes_b)
+    assert (pa, pb) == (orc.vote_pattern(votes_a), orc.vote_pattern(votes_b)) == (ah.ADAHOP_PATTERN_OUTER, ah.ADAHOP_PATTERN_NONE)
+    strategy, full_bf16 = ah.adahop_select_strategy(pa, pb, 1)
+    assert (strategy, full_bf16) == (inputs.IHT_OE_ROW, False)
+    g = inputs.Gemm("calibrated.dgrad", G, W, strategy, 128, 5)
+    _, q_sel = run_whole(ah, g)
+    g.strategy, g.k = inputs.IHT, 0
+    _, q_iht = run_whole(ah, g)
+    assert q_sel < q_iht                        # the calibrated choice beats the uniform default on this pair
+
+
 # ----------------------------------------------------------------------------- variants at full size
 
 def test_config4_bf16_output_and_packed_operands(ah):

@@ -500,6 +500,18 @@ def test_strategy_table_matches_the_papers_section():
         assert orc.select_strategy(a, b, int(level)) == names[want], (pair, level)
 
 
+def test_calibration_vote_is_the_majority_with_ties_to_none():
+    """Hand cases for the 30-step vote of Sec. 4.1."""
+    N, O, K = orc.PATTERN_NONE, orc.PATTERN_OUTER, orc.PATTERN_K
+    assert orc.vote_pattern([K] * 30) == K
+    assert orc.vote_pattern([K] * 16 + [N] * 14) == K
+    assert orc.vote_pattern([O] * 11 + [K] * 10 + [N] * 9) == O          # a plurality is enough
+    assert orc.vote_pattern([O] * 15 + [K] * 15) == N                    # nothing dominates
+    assert orc.vote_pattern([O] * 10 + [K] * 10 + [N] * 10) == N
+    assert orc.vote_pattern([N] * 15 + [K] * 15) == N
+    assert orc.vote_pattern([O]) == O
+
+
 def test_pattern_closed_form_rank_one():
     """T[i, j] = a_i * s_j with s = +-1 alternating: every row has mean 0 and variance a_i^2 exactly, every
     column has the same variance var(a) -> CV of the column variances is 0 and CV_row = std(a^2) / mean(a^2).
