@@ -248,6 +248,20 @@ def main():
                                         "quantize_a_ms": t_q,
                                         "quantize_a_GBps": 2.53125 * big.A.outer * big.K / (t_q * 1e-3) / 1e9}
             del qa, qs
+        # launch-bound case (configs[0]: 256^3, IHT block 32): the same call eager and replayed from a HIP graph
+        g0 = inputs.config0()[0]
+        p0 = Prepared(ah, torch, g0, cache)
+        ws0 = torch.empty(ah.adahop_gemm_workspace_bytes(p0.M, p0.N, p0.K, g0.strategy, g0.k), dtype=torch.uint8, device="cuda")
+        run_gemm(ah, p0, ws0)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                run_gemm(ah, p0, ws0)
+        torch.cuda.synchronize()
+        extras["launch_bound_256cubed_us"] = {"eager": 1e3 * time_ms(torch, lambda: run_gemm(ah, p0, ws0), 200, warmup=20),
+                                              "graph_replay": 1e3 * time_ms(torch, graph.replay, 200, warmup=20)}
         # what the matrix cores sustain with no memory traffic at all (register-only loop, 256 workgroups)
         sink = torch.zeros(1, dtype=torch.float32, device="cuda")
         probe = {}
