@@ -277,6 +277,28 @@ def test_whole_path_tile_aligned_shape(ah, strategy, k, M, N):
     run_whole(ah, g)
 
 
+@pytest.mark.parametrize("strategy,k", [(inputs.IHT, 0), (inputs.IHT_OE_K, 5), (inputs.IHT_OE_K, 70), (inputs.IHT_OE_K, 150),
+                                        (inputs.IHT_OE_ROW, 9)])
+@pytest.mark.parametrize("M,N", [(4352, 4096), (4608, 3840)])
+def test_more_tiles_than_compute_units(ah, strategy, k, M, N):
+    """272 and 270 tiles of 256x256: some workgroups of the persistent kernel walk two tiles, with the stage pipeline
+    running from one into the next (one, two and three gathered-bf16 stages per tile for the three OE-K ranks; an odd
+    and an even number of stages per tile; a tile count that is and is not a multiple of 8).  C on a seeded sample of
+    rows and columns that covers every tile row and tile column."""
+    K = 768
+    A = inputs.Operand(inputs.matrix(M, K, 1.0, 62, row_outliers=(6, 100.0, 100.0), col_outliers=(5, 50.0, 50.0)), True)
+    B = inputs.Operand(inputs.matrix(N, K, 0.02, 63), True)
+    g = inputs.Gemm("manytiles", A, B, strategy, 256, k)
+    rng = np.random.default_rng(M + k)
+    rows = np.unique(np.concatenate([np.arange(0, M, 256) + rng.integers(0, 256, M // 256), rng.integers(0, M, 16)]))
+    cols = np.unique(np.concatenate([np.arange(0, N, 256) + rng.integers(0, 256, N // 256), rng.integers(0, N, 48)]))
+    if strategy == inputs.IHT_OE_ROW:
+        sel, _ = orc.foid_topk(A.bits, True, 0, k)
+        rows = np.unique(np.concatenate([rows, sel[:4]]))
+    say("more tiles than compute units", inputs.STRATEGY_NAMES[strategy], k, (M, N, K))
+    run_whole(ah, g, rows=rows.astype(np.int32), cols=cols.astype(np.int32))
+
+
 def test_oe_k_zero_equals_iht(ah):
     g = inputs.config0()[0]
     A, B = dev_op(ah, g.A), dev_op(ah, g.B)
