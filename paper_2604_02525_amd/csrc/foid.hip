@@ -184,6 +184,115 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__
     }
 }
 
+// The same selection for dim <= TOPK_REG_KEYS * 1024 with every key held in registers: wave w owns the
+// contiguous index range [w*per, (w+1)*per) throughout and lane l its keys w*per + 64 j + l, loaded once (the
+// general kernel reads all keys from memory in each of its six passes, one dependent load per iteration, which
+// is what its run time consists of at these sizes).
+constexpr int TOPK_REG_KEYS = 32;
+
+__global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restrict__ scores, int dim, int k,
+                                                           int32_t *__restrict__ idx, uint8_t *__restrict__ mask)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sh_prefix, sh_remaining;
+    __shared__ uint32_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint32_t *keys = reinterpret_cast<const uint32_t *>(scores);
+    const int per = ((dim + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64; // <= 64 * TOPK_REG_KEYS
+    const int lo = w * per, hi = min(dim, lo + per);
+
+    if (k <= 0) {
+        for (int i = tid; i < dim; i += TOPK_THREADS) mask[i] = 0;
+        return;
+    }
+    uint32_t key[TOPK_REG_KEYS];
+#pragma unroll
+    for (int j = 0; j < TOPK_REG_KEYS; ++j) {
+        const int i = lo + 64 * j + lane;
+        key[j] = i < hi ? keys[i] : 0u;
+    }
+    const int nj = (per + 63) / 64; // the same for every wave
+
+    uint32_t prefix = 0, pmask = 0, remaining = (uint32_t)k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int b = tid; b < 256; b += TOPK_THREADS) hist[b] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < TOPK_REG_KEYS; ++j)
+            if (j < nj) wave_histogram(hist, lo + 64 * j + lane < hi && (key[j] & pmask) == prefix, (key[j] >> shift) & 255u);
+        __syncthreads();
+        if (w == 0) { // the digit of the k-th largest key, as in k_topk
+            uint32_t c[4], mine = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                c[j] = hist[255 - 4 * lane - j];
+                mine += c[j];
+            }
+            uint32_t incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d *= 2) {
+                const uint32_t up = __shfl_up(incl, d);
+                if (lane >= d) incl += up;
+            }
+            uint32_t cum = incl - mine;
+            int found = -1;
+            uint32_t cum_at = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (found < 0 && cum + c[j] >= remaining) {
+                    found = 255 - 4 * lane - j;
+                    cum_at = cum;
+                }
+                cum += c[j];
+            }
+            const uint64_t hit = __ballot(found >= 0);
+            if (hit && lane == __ffsll((long long)hit) - 1) {
+                sh_prefix = prefix | ((uint32_t)found << shift);
+                sh_remaining = remaining - cum_at;
+            }
+        }
+        __syncthreads();
+        prefix = sh_prefix;
+        remaining = sh_remaining;
+        pmask |= 255u << shift;
+        __syncthreads();
+    }
+    const uint32_t T = prefix;
+
+    uint32_t gt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < TOPK_REG_KEYS; ++j) {
+        const bool in = lo + 64 * j + lane < hi; // false for every lane once j >= nj
+        gt += (uint32_t)__popcll(__ballot(in && key[j] > T));
+        eq += (uint32_t)__popcll(__ballot(in && key[j] == T));
+    }
+    if (lane == 0) {
+        wave_gt[w] = gt;
+        wave_eq[w] = eq;
+    }
+    __syncthreads();
+    uint32_t gt_before = 0, eq_before = 0;
+    for (int v = 0; v < w; ++v) {
+        gt_before += wave_gt[v];
+        eq_before += wave_eq[v];
+    }
+    const uint64_t below = ((uint64_t)1 << lane) - 1;
+#pragma unroll
+    for (int j = 0; j < TOPK_REG_KEYS; ++j) {
+        const int i = lo + 64 * j + lane;
+        const bool in = i < hi;
+        const bool is_gt = in && key[j] > T, is_eq = in && key[j] == T;
+        const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
+        const uint32_t my_gt = gt_before + (uint32_t)__popcll(m_gt & below);
+        const uint32_t my_eq = eq_before + (uint32_t)__popcll(m_eq & below);
+        const bool sel = is_gt || (is_eq && my_eq < remaining);
+        if (sel) idx[my_gt + min(my_eq, remaining)] = i;
+        if (in) mask[i] = sel ? 1 : 0;
+        gt_before += (uint32_t)__popcll(m_gt);
+        eq_before += (uint32_t)__popcll(m_eq);
+    }
+}
+
 __global__ __launch_bounds__(256) void k_fill_u8(uint8_t *p, int64_t n, uint8_t v)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -210,7 +319,10 @@ int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, u
                        static_cast<const uint16_t *>(x.data), x.ld, x.k_contig, axis, dim, L, inv_L, scores);
     int rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
-    hipLaunchKernelGGL(k_topk, dim3(1), dim3(TOPK_THREADS), 0, st, scores, (int)dim, k, idx, mask);
+    if (dim <= (int64_t)TOPK_REG_KEYS * TOPK_THREADS)
+        hipLaunchKernelGGL(k_topk_reg, dim3(1), dim3(TOPK_THREADS), 0, st, scores, (int)dim, k, idx, mask);
+    else
+        hipLaunchKernelGGL(k_topk, dim3(1), dim3(TOPK_THREADS), 0, st, scores, (int)dim, k, idx, mask);
     return check_launch();
 }
 
