@@ -30,7 +30,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=10)
     p.add_argument("--warmup", type=int, default=3)
-    p.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg4-up", "cfg1", "cfg0", "paper-table3"])
+    p.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg4-up", "cfg3", "cfg1", "cfg0", "paper-table3"])
     p.add_argument("--k-pct", type=float, default=1.0, help="extraction count as %% of the extracted dim (cfg4)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the k-sweep / BF16 / per-stage extras")
@@ -50,6 +50,9 @@ def build_workload(name, k_pct):
         return "configs[0]: M=N=K=256, IHT block 32", I.config0()
     if name == "cfg1":
         return "configs[1]: fwd X[8192,2048] W[8192,2048], IHT block 128", I.config1()
+    if name == "cfg3":
+        return ("configs[3]: LLaMA-7B-shaped layer at T=8192 (QKV, O, gate, up, down; fwd+dgrad+wgrad, 15 GEMMs), IHT block "
+                "128, seeded per-GEMM strategy table, k = 1 % of the extracted dim"), I.config3()
     if name == "paper-table3":
         return ("the two GEMMs of the paper's kernel latency table: (14336,4096,32768) and (4096,4096,32768) weight "
                 "gradients, IHT block 32, OE-col with rank 64"), I.paper_latency_shapes()

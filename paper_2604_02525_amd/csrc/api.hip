@@ -377,19 +377,29 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
     const uint8_t *a_scales = a_given ? opts->a_scales : reinterpret_cast<uint8_t *>(ws + L.a_scales);
     const uint8_t *b_codes = b_given ? opts->b_codes : reinterpret_cast<uint8_t *>(ws + L.b_codes);
     const uint8_t *b_scales = b_given ? opts->b_scales : reinterpret_cast<uint8_t *>(ws + L.b_scales);
+    // The tiled GEMM kernel reads the scales in a stage-major copy; the quantisers that run here write it
+    // beside the canonical one, which saves the product its two re-ordering launches.
+    const int kpad_planned = oe && strategy == ADAHOP_IHT_OE_K ? kpad_of(k) : 0;
+    int64_t Mi = 0, Ni = 0;
+    gemm_mx_tiled_part(M, N, K, kpad_planned, a_scales, b_scales, C, ldc, c_bf16, &Mi, &Ni);
+    int sm_ready = 0;
     if (!a_given) {
         uint8_t *c = reinterpret_cast<uint8_t *>(ws + L.a_codes), *s = reinterpret_cast<uint8_t *>(ws + L.a_scales);
+        const scales_sm_t sm = {Mi > 0 && !oht ? gemm_mx_scales_sm(ws + L.gemm, M, K, 0) : nullptr, Mi};
         rc = oht ? launch_oht_quantize(*A, b, c, s, st)
                  : launch_iht_quantize(*A, b, a_kind == 1 ? mask : nullptr, a_kind == 2 ? mask : nullptr, c, s, st,
-                                       opts && opts->sr_a ? &opts->sr_seed_a : nullptr);
+                                       opts && opts->sr_a ? &opts->sr_seed_a : nullptr, &sm);
         if (rc != ADAHOP_OK) return rc;
+        if (sm.out) sm_ready |= 1;
     }
     if (!b_given) {
         uint8_t *c = reinterpret_cast<uint8_t *>(ws + L.b_codes), *s = reinterpret_cast<uint8_t *>(ws + L.b_scales);
+        const scales_sm_t sm = {Ni > 0 && !oht ? gemm_mx_scales_sm(ws + L.gemm, M, K, 1) : nullptr, Ni};
         rc = oht ? launch_oht_quantize(*B, b, c, s, st)
                  : launch_iht_quantize(*B, b, b_kind == 1 ? mask : nullptr, b_kind == 2 ? mask : nullptr, c, s, st,
-                                       opts && opts->sr_b ? &opts->sr_seed_b : nullptr);
+                                       opts && opts->sr_b ? &opts->sr_seed_b : nullptr, &sm);
         if (rc != ADAHOP_OK) return rc;
+        if (sm.out) sm_ready |= 2;
     }
     // 3. MXFP4 product, with the K-channel BF16 product fused in front; 4. row / column BF16 product
     if (oe && strategy == ADAHOP_IHT_OE_K) {
@@ -399,9 +409,11 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
         if (rc != ADAHOP_OK) return rc;
         rc = launch_gather_k(*B, idx_inout, k, kpad, Bg, st);
         if (rc != ADAHOP_OK) return rc;
-        return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, Ag, Bg, kpad, ws + L.gemm, st);
+        return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, Ag, Bg, kpad, ws + L.gemm, st,
+                              sm_ready);
     }
-    rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, nullptr, nullptr, 0, ws + L.gemm, st);
+    rc = launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, nullptr, nullptr, 0, ws + L.gemm, st,
+                        sm_ready);
     if (rc != ADAHOP_OK) return rc;
     if (oht) return launch_oht_inverse(static_cast<float *>(C), M, N, ldc, b, st); // the rotations after the product (Eq. 6)
     if (oe) rc = launch_oe_rowcol(*A, *B, strategy, idx_inout, k, C, ldc, c_bf16, ws + L.gather_a, st);

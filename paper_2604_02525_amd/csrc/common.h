@@ -26,18 +26,30 @@ int validate_operand(const adahop_operand_t *x);
 bool valid_iht_block(int b);
 
 // Launchers (one per kernel family); each validates nothing and returns a status.
+// Stage-major copy of the scales for the tiled GEMM kernel (see gemm_mx_tiled_part): [K/256][rows][8].
+struct scales_sm_t {
+    uint8_t *out; // stage-major copy, or nullptr
+    int64_t rows; // rows [0, rows) are written
+};
 // sr_seed: NULL = round to nearest even; else the elements are rounded stochastically under that seed.
 int launch_iht_quantize(const adahop_operand_t &x, int iht_block, const uint8_t *zero_outer,
                         const uint8_t *zero_k, uint8_t *codes, uint8_t *scales, hipStream_t st,
-                        const uint64_t *sr_seed = nullptr);
+                        const uint64_t *sr_seed = nullptr, const scales_sm_t *sm = nullptr);
 int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, uint8_t *mask, float *scores,
                      hipStream_t st);
 int launch_mask_from_idx(const int32_t *idx, int k, uint8_t *mask, int64_t dim, hipStream_t st);
 // OE-K operands for the fused prologue: Ag [M, kpad], Bg [N, kpad] bf16, K-contiguous, zero padded.
 int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
                    const uint8_t *b_codes, const uint8_t *b_scales, void *C, int64_t ldc, int c_bf16,
-                   const uint16_t *Ag, const uint16_t *Bg, int kpad, void *workspace, hipStream_t st);
+                   const uint16_t *Ag, const uint16_t *Bg, int kpad, void *workspace, hipStream_t st,
+                   int sm_ready = 0);
 size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
+// The tiled kernel reads the scales in a stage-major copy, [K/256][rows][8] over the rows it takes.  A caller
+// that quantises right before the product lets the quantiser write that copy as well (scales_sm_t above) and
+// says so with sm_ready (bit 0: A, bit 1: B); otherwise launch_gemm_mx re-orders the canonical scales itself.
+void gemm_mx_tiled_part(int64_t M, int64_t N, int64_t K, int kpad, const uint8_t *a_scales, const uint8_t *b_scales,
+                        const void *C, int64_t ldc, int c_bf16, int64_t *Mi, int64_t *Ni);
+uint8_t *gemm_mx_scales_sm(void *workspace, int64_t M, int64_t K, int which);
 int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kpad, uint16_t *out, hipStream_t st);
 // C is float[M, ldc], or bf16[M, ldc] when c_bf16 is set (here and in launch_oe_rowcol).
 // Row / column outlier product; workspace of oe_rowcol_workspace_bytes() bytes, 256-byte aligned.

@@ -646,12 +646,32 @@ size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
     return align_up((size_t)M * (K / 32), 256) + align_up((size_t)N * (K / 32), 256);
 }
 
+// Which part of the product the tiled kernel takes: whole 256x256 tiles (rows [0, Mi), columns [0, Ni)), or
+// nothing.  At least three pipeline stages are needed (64 gathered channels or 256 K-elements each, two of
+// them FP4 stages); the bf16 epilogue stores 16 bytes per lane.
+void gemm_mx_tiled_part(int64_t M, int64_t N, int64_t K, int kpad, const uint8_t *a_scales, const uint8_t *b_scales,
+                        const void *C, int64_t ldc, int c_bf16, int64_t *Mi, int64_t *Ni)
+{
+    const bool fast_c = !c_bf16 || (aligned(C, 16) && ldc % 8 == 0);
+    const bool fast_k = fast_c && K % 256 == 0 && K >= (kpad > 0 ? 512 : 768) && kpad % 64 == 0 &&
+                        aligned(a_scales, 8) && aligned(b_scales, 8);
+    *Mi = fast_k ? M / TM * TM : 0;
+    *Ni = fast_k ? N / TN * TN : 0;
+    if (*Mi == 0 || *Ni == 0 || (*Mi / TM) * (*Ni / TN) >= (1 << 30)) *Mi = *Ni = 0;
+}
+
+uint8_t *gemm_mx_scales_sm(void *workspace, int64_t M, int64_t K, int which)
+{
+    uint8_t *a_sm = static_cast<uint8_t *>(workspace);
+    return which == 0 ? a_sm : a_sm + align_up((size_t)M * (K / 32), 256);
+}
+
 namespace {
 
 template <typename OUT>
 int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
                      const uint8_t *b_codes, const uint8_t *b_scales, OUT *C, int64_t ldc, const uint16_t *Ag,
-                     const uint16_t *Bg, int kpad, void *workspace, hipStream_t st)
+                     const uint16_t *Bg, int kpad, void *workspace, int sm_ready, hipStream_t st)
 {
     if (M == 0 || N == 0) return ADAHOP_OK;
     auto generic = [&](int64_t m, int64_t n, const uint8_t *ac, const uint8_t *as, const uint8_t *bc, const uint8_t *bs,
@@ -662,14 +682,10 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
         return check_launch();
     };
     // The tiled kernel takes the whole 256x256 tiles; ragged edges (and shapes it cannot take at all) go to
-    // the bounds-checked kernel.  Its bf16 epilogue stores 16 bytes per lane.
-    const bool fast_c = sizeof(OUT) == 4 || (aligned(C, 16) && ldc % 8 == 0);
-    // (at least three pipeline stages: 64 gathered channels or 256 K-elements each, two of them FP4 stages)
-    const bool fast_k = fast_c && K % 256 == 0 && K >= (kpad > 0 ? 512 : 768) && kpad % 64 == 0 &&
-                        aligned(a_scales, 8) && aligned(b_scales, 8);
-    const int64_t Mi = fast_k ? M / TM * TM : 0, Ni = fast_k ? N / TN * TN : 0;
-    if (Mi == 0 || Ni == 0 || (Mi / TM) * (Ni / TN) >= (1 << 30))
-        return generic(M, N, a_codes, a_scales, b_codes, b_scales, C, Ag, Bg);
+    // the bounds-checked kernel.
+    int64_t Mi, Ni;
+    gemm_mx_tiled_part(M, N, K, kpad, a_scales, b_scales, C, ldc, sizeof(OUT) == 2, &Mi, &Ni);
+    if (Mi == 0) return generic(M, N, a_codes, a_scales, b_codes, b_scales, C, Ag, Bg);
 
     int dev = 0, ncu = 0;
     int rc0 = check_hip(hipGetDevice(&dev));
@@ -690,14 +706,16 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
         if (rc != ADAHOP_OK) return rc;
         configured.fetch_or(dev_bit);
     }
-    // scales of the tiled part, stage-major, in the caller's workspace
-    uint8_t *a_sm = static_cast<uint8_t *>(workspace);
-    uint8_t *b_sm = a_sm + align_up((size_t)M * (K / 32), 256);
+    // scales of the tiled part, stage-major, in the caller's workspace (sm_ready bit 0 / 1: the quantiser of A / B
+    // has already written them there)
+    uint8_t *a_sm = gemm_mx_scales_sm(workspace, M, K, 0), *b_sm = gemm_mx_scales_sm(workspace, M, K, 1);
     const int64_t KB8 = K / 256;
-    hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(Mi * KB8, 256)), dim3(256), 0, st,
-                       reinterpret_cast<const uint64_t *>(a_scales), reinterpret_cast<uint64_t *>(a_sm), Mi, KB8);
-    hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(Ni * KB8, 256)), dim3(256), 0, st,
-                       reinterpret_cast<const uint64_t *>(b_scales), reinterpret_cast<uint64_t *>(b_sm), Ni, KB8);
+    if (!(sm_ready & 1))
+        hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(Mi * KB8, 256)), dim3(256), 0, st,
+                           reinterpret_cast<const uint64_t *>(a_scales), reinterpret_cast<uint64_t *>(a_sm), Mi, KB8);
+    if (!(sm_ready & 2))
+        hipLaunchKernelGGL(k_stage_major_scales, dim3((unsigned)ceil_div(Ni * KB8, 256)), dim3(256), 0, st,
+                           reinterpret_cast<const uint64_t *>(b_scales), reinterpret_cast<uint64_t *>(b_sm), Ni, KB8);
     int rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
     const int tiles_m = (int)(Mi / TM), tiles_n = (int)(Ni / TN);
@@ -728,13 +746,13 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
 
 int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,
                    const uint8_t *b_codes, const uint8_t *b_scales, void *C, int64_t ldc, int c_bf16, const uint16_t *Ag,
-                   const uint16_t *Bg, int kpad, void *workspace, hipStream_t st)
+                   const uint16_t *Bg, int kpad, void *workspace, hipStream_t st, int sm_ready)
 {
     if (c_bf16)
         return launch_gemm_mx_t(M, N, K, a_codes, a_scales, b_codes, b_scales, static_cast<uint16_t *>(C), ldc, Ag, Bg,
-                                kpad, workspace, st);
+                                kpad, workspace, sm_ready, st);
     return launch_gemm_mx_t(M, N, K, a_codes, a_scales, b_codes, b_scales, static_cast<float *>(C), ldc, Ag, Bg, kpad,
-                            workspace, st);
+                            workspace, sm_ready, st);
 }
 
 int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint16_t *Bg, int kpad, float *C,

@@ -497,8 +497,10 @@ __device__ __forceinline__ void apply_k_mask(float (&w)[8], const uint8_t *zero_
         if ((zm >> (8 * i)) & 0xffu) w[i] = 0.0f;
 }
 
+// k0: start of the lane group's 256 K-elements (a multiple of 256).  sm: optional second copy of the scales in
+// the order the tiled GEMM kernel reads them, [K/256][sm.rows][8].
 __device__ __forceinline__ void store_codes_scales(uint8_t *codes, uint8_t *scales, int64_t row, int64_t K, int64_t k0,
-                                                   int chunk, uint32_t c0, uint32_t c1, int s0, int s1)
+                                                   int chunk, uint32_t c0, uint32_t c1, int s0, int s1, scales_sm_t sm)
 {
     uint8_t *crow = codes + row * (K >> 1) + ((k0 + chunk * 8) >> 1);
     *reinterpret_cast<uint32_t *>(crow) = c0;
@@ -507,6 +509,11 @@ __device__ __forceinline__ void store_codes_scales(uint8_t *codes, uint8_t *scal
         uint8_t *srow = scales + row * (K >> 5) + ((k0 + chunk * 8) >> 5);
         srow[0] = (uint8_t)s0;
         srow[4] = (uint8_t)s1;
+        if (sm.out && row < sm.rows) {
+            uint8_t *q = sm.out + ((k0 >> 8) * sm.rows + row) * 8 + (chunk >> 2);
+            q[0] = (uint8_t)s0;
+            q[4] = (uint8_t)s1;
+        }
     }
 }
 
@@ -516,7 +523,7 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
                                                     int64_t ld, const uint8_t *__restrict__ zero_outer,
                                                     const uint8_t *__restrict__ zero_k,
                                                     uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
-                                                    sr_key_t key)
+                                                    sr_key_t key, scales_sm_t sm)
 {
     const uint32_t upr = (uint32_t)(K >> 8); // 256-element units per row
     int64_t row;
@@ -553,7 +560,7 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
     uint32_t c0, c1;
     int s0, s1;
     transform_quantize16<B, SR>(w0, w1, plan, c0, c1, s0, s1, key, row, kk, kk + 128);
-    if (active) store_codes_scales(codes, scales, row, K, k0, plan.chunk, c0, c1, s0, s1);
+    if (active) store_codes_scales(codes, scales, row, K, k0, plan.chunk, c0, c1, s0, s1, sm);
 }
 
 // K-strided operand (element (o, kk) at x[kk*ld + o]).  A workgroup takes a tile of 256 K-rows x 64
@@ -568,7 +575,7 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
                                                     int64_t ld, const uint8_t *__restrict__ zero_outer,
                                                     const uint8_t *__restrict__ zero_k,
                                                     uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
-                                                    sr_key_t key)
+                                                    sr_key_t key, scales_sm_t sm)
 {
     __shared__ uint16_t tile[256 * KS_PITCH];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -617,13 +624,13 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
         uint32_t c0, c1;
         int s0, s1;
         transform_quantize16<B, SR>(w0, w1, plan, c0, c1, s0, s1, key, o, k0 + kc, k0 + kc + 128);
-        if (active) store_codes_scales(codes, scales, o, K, k0, plan.chunk, c0, c1, s0, s1);
+        if (active) store_codes_scales(codes, scales, o, K, k0, plan.chunk, c0, c1, s0, s1, sm);
     }
 }
 
 template <int B, bool SR>
 int launch_kc(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
-              sr_key_t key, hipStream_t st)
+              sr_key_t key, scales_sm_t sm, hipStream_t st)
 {
     const uint16_t *d = static_cast<const uint16_t *>(x.data);
     if (x.K % 256 == 0) {
@@ -631,11 +638,11 @@ int launch_kc(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, u
         if (tpr >= 128) {
             dim3 grid((unsigned)x.outer, (unsigned)ceil_div(tpr, 256));
             hipLaunchKernelGGL((k_quant_kc16<B, 0, SR>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes,
-                               scales, key);
+                               scales, key, sm);
         } else {
             dim3 grid((unsigned)ceil_div(x.outer * tpr, 256));
             hipLaunchKernelGGL((k_quant_kc16<B, 1, SR>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes,
-                               scales, key);
+                               scales, key, sm);
         }
         return check_launch();
     }
@@ -654,12 +661,12 @@ int launch_kc(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, u
 
 template <int B, bool SR>
 int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
-              sr_key_t key, hipStream_t st)
+              sr_key_t key, scales_sm_t sm, hipStream_t st)
 {
     if (x.K % 256 == 0 && x.K / 256 <= 65535) {
         dim3 grid((unsigned)ceil_div(x.outer, KS_COLS), (unsigned)(x.K / 256));
         hipLaunchKernelGGL((k_quant_ks16<B, SR>), grid, dim3(256), 0, st, static_cast<const uint16_t *>(x.data), x.outer,
-                           x.K, x.ld, zo, zk, codes, scales, key);
+                           x.K, x.ld, zo, zk, codes, scales, key, sm);
         return check_launch();
     }
     constexpr int NW = ks_cfg<B>::NW;
@@ -678,12 +685,12 @@ int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, u
 
 template <bool SR>
 int dispatch_block(const adahop_operand_t &x, int b, const uint8_t *zo, const uint8_t *zk, uint8_t *codes,
-                   uint8_t *scales, sr_key_t key, hipStream_t st)
+                   uint8_t *scales, sr_key_t key, scales_sm_t sm, hipStream_t st)
 {
 #define ADAHOP_DISPATCH(BB)                                                                  \
     case BB:                                                                                 \
-        return x.k_contig ? launch_kc<BB, SR>(x, zo, zk, codes, scales, key, st)             \
-                          : launch_ks<BB, SR>(x, zo, zk, codes, scales, key, st);
+        return x.k_contig ? launch_kc<BB, SR>(x, zo, zk, codes, scales, key, sm, st)         \
+                          : launch_ks<BB, SR>(x, zo, zk, codes, scales, key, sm, st);
     switch (b) {
         ADAHOP_DISPATCH(0)
         ADAHOP_DISPATCH(32)
@@ -699,15 +706,18 @@ int dispatch_block(const adahop_operand_t &x, int b, const uint8_t *zo, const ui
 } // namespace
 
 // sr_seed: NULL for round-to-nearest-even, else the seed of the stochastic rounding of the elements.
+// sm: NULL, or where a stage-major copy of the scales goes; honoured by the kernels for K % 256 == 0 only,
+// which is also the only case in which the tiled GEMM kernel asks for it.
 int launch_iht_quantize(const adahop_operand_t &x, int b, const uint8_t *zo, const uint8_t *zk, uint8_t *codes,
-                        uint8_t *scales, hipStream_t st, const uint64_t *sr_seed)
+                        uint8_t *scales, hipStream_t st, const uint64_t *sr_seed, const scales_sm_t *sm)
 {
     if (x.outer == 0 || x.K == 0) return ADAHOP_OK;
+    const scales_sm_t smv = sm && x.K % 256 == 0 && x.K / 256 <= 65535 ? *sm : scales_sm_t{nullptr, 0};
     if (sr_seed) {
         const sr_key_t key = {(uint32_t)*sr_seed, (uint32_t)(*sr_seed >> 32)};
-        return dispatch_block<true>(x, b, zo, zk, codes, scales, key, st);
+        return dispatch_block<true>(x, b, zo, zk, codes, scales, key, smv, st);
     }
-    return dispatch_block<false>(x, b, zo, zk, codes, scales, sr_key_t{0, 0}, st);
+    return dispatch_block<false>(x, b, zo, zk, codes, scales, sr_key_t{0, 0}, smv, st);
 }
 
 } // namespace adahop
