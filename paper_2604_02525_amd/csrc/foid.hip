@@ -190,10 +190,24 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__
 // is what its run time consists of at these sizes).
 constexpr int TOPK_REG_KEYS = 32;
 
+// hist[bin] += 1 for every lane with valid set, hist being private to the wave: one combined add for the bin
+// of the first valid lane (the scores of ordinary rows share their high bytes, so that bin usually takes most of
+// the wave), plain per-lane adds for the rest (conflicts only among the lanes of this wave).
+__device__ __forceinline__ void wave_histogram_private(uint32_t *hist, bool valid, uint32_t bin)
+{
+    const uint64_t todo = __ballot(valid);
+    if (todo == 0) return;
+    const int leader = __ffsll((long long)todo) - 1;
+    const uint32_t b = __builtin_amdgcn_readlane(bin, leader);
+    const uint64_t same = __ballot(valid && bin == b);
+    if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[b], (uint32_t)__popcll(same));
+    if (valid && bin != b) atomicAdd(&hist[bin], 1u);
+}
+
 __global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restrict__ scores, int dim, int k,
                                                            int32_t *__restrict__ idx, uint8_t *__restrict__ mask)
 {
-    __shared__ uint32_t hist[256];
+    __shared__ uint32_t hist[TOPK_WAVES + 1][256]; // one per wave, and their sum
     __shared__ uint32_t sh_prefix, sh_remaining;
     __shared__ uint32_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -214,18 +228,29 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restri
     const int nj = (per + 63) / 64; // the same for every wave
 
     uint32_t prefix = 0, pmask = 0, remaining = (uint32_t)k;
+    uint32_t *total = hist[TOPK_WAVES];
     for (int shift = 24; shift >= 0; shift -= 8) {
-        for (int b = tid; b < 256; b += TOPK_THREADS) hist[b] = 0;
-        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) hist[w][lane + 64 * q] = 0;
+        // (each wave clears and fills its own histogram: no barrier needed in between)
 #pragma unroll
         for (int j = 0; j < TOPK_REG_KEYS; ++j)
-            if (j < nj) wave_histogram(hist, lo + 64 * j + lane < hi && (key[j] & pmask) == prefix, (key[j] >> shift) & 255u);
+            if (j < nj)
+                wave_histogram_private(hist[w], lo + 64 * j + lane < hi && (key[j] & pmask) == prefix,
+                                       (key[j] >> shift) & 255u);
+        __syncthreads();
+        if (tid < 256) {
+            uint32_t sum = 0;
+#pragma unroll
+            for (int v = 0; v < TOPK_WAVES; ++v) sum += hist[v][tid];
+            total[tid] = sum;
+        }
         __syncthreads();
         if (w == 0) { // the digit of the k-th largest key, as in k_topk
             uint32_t c[4], mine = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                c[j] = hist[255 - 4 * lane - j];
+                c[j] = total[255 - 4 * lane - j];
                 mine += c[j];
             }
             uint32_t incl = mine;
@@ -255,7 +280,6 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restri
         prefix = sh_prefix;
         remaining = sh_remaining;
         pmask |= 255u << shift;
-        __syncthreads();
     }
     const uint32_t T = prefix;
 
