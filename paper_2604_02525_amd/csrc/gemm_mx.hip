@@ -136,8 +136,9 @@ __global__ __launch_bounds__(256) void k_gemm_mx_generic(int64_t M, int64_t N, i
 // ------------------------------------------------------------------------------------------------
 // Tiled kernel for M % 256 == 0, N % 256 == 0, K % 256 == 0 (and kpad % 64 == 0).
 //
-// One workgroup (4 waves, 2x2) per 256x256 tile of C; each wave owns 128x128 = 4x4 matrix-core
-// tiles, i.e. 256 fp32 accumulators per lane, and the workgroup is alone on its compute unit.
+// A workgroup (4 waves, 2x2) computes 256x256 tiles of C, one after the other; each wave owns 128x128 =
+// 4x4 matrix-core tiles, i.e. 256 fp32 accumulators per lane, and the workgroup is alone on its compute
+// unit (see k_gemm_mx_tile256 for the walk over the tiles).
 //
 // Pipeline.  A stage holds 128 bytes of K per row for the 256 A rows and the 256 B rows -- 256 FP4
 // K-elements (8 MX blocks, four matrix-core steps) or 64 gathered bf16 K-channels -- plus the 8 scale
@@ -159,9 +160,9 @@ __global__ __launch_bounds__(256) void k_gemm_mx_generic(int64_t M, int64_t N, i
 //
 // Scales reach LDS by DMA as well, so the main loop has no register-targeted global loads and only
 // waits where the kernel says so.  Fetching 8 bytes per row from the canonical [rows, K/32] array
-// would cost one cache-line request per row and stage -- as many requests as the codes need -- so a
-// small pre-pass (k_stage_major_scales) first rewrites the scales stage-major, [K/256][rows][8],
-// where the 256 rows of a slab are 2 KiB contiguous.
+// would cost one cache-line request per row and stage -- as many requests as the codes need -- so the
+// kernel reads a stage-major copy, [K/256][rows][8], where the 256 rows of a slab are 2 KiB contiguous:
+// written by the quantiser beside the canonical scales, or by a small pre-pass (k_stage_major_scales).
 // ------------------------------------------------------------------------------------------------
 constexpr int TM = 256, TN = 256, TKB = 128, NSTAGE = 2;
 constexpr int SLAB_BYTES = (TM + TN) * TKB;             // codes (or gathered bf16) of one stage
