@@ -203,10 +203,14 @@ def main():
             am = a16 if p.A.k_contig else a16.t()
             bm = b16.t() if p.B.k_contig else b16
             t_bf16 = time_ms(torch, lambda: torch.matmul(am, bm), 5)
+            # the same with an fp32 result, as this path delivers it (torch exposes no bf16-in / fp32-out GEMM:
+            # the conversion is a second pass over C)
+            t_bf16_f32 = time_ms(torch, lambda: p.C.copy_(torch.matmul(am, bm)), 3)
             per.append({"name": p.g.name, "shape": [p.M, p.N, p.K], "strategy": inputs.STRATEGY_NAMES[p.g.strategy],
                         "k": p.g.k, "ms": t_cfg, "tflops": p.flops / t_cfg / 1e9, "ms_iht_only": t_iht,
                         "tflops_iht_only": p.flops / t_iht / 1e9, "oe_overhead_pct": 100.0 * (t_cfg - t_iht) / t_iht,
                         "ms_bf16_hipblaslt": t_bf16, "tflops_bf16_hipblaslt": p.flops / t_bf16 / 1e9,
+                        "ms_bf16_hipblaslt_fp32_result": t_bf16_f32,
                         "speedup_vs_bf16": t_bf16 / t_cfg})
         extras["per_gemm"] = per
         t_iht_total = sum(x["ms_iht_only"] for x in per)
