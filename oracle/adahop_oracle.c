@@ -74,9 +74,14 @@ void orc_fwht(float *v, int b)
     float c = (float)(1.0 / sqrt((double)b));
     for (int j = 0; j < b; ++j) {
         v[j] = v[j] * c;
-        /* A transformed value that is exactly zero carries no sign: it is stored as +0.  (The paper
-         * does not say; without this the sign of such a zero would depend on the order in which
-         * cancelling terms were added, which is not part of the definition of H v.) */
+        /* Convention, chosen here (the paper is silent): a transformed value that is exactly zero is
+         * stored as +0.  Mathematically (H v)_j = 0 has no sign.  The plain butterflies above would
+         * give -0 only where every contributing input is -0 (round-to-nearest cancellation of
+         * nonzero terms yields +0 in any order), so the rule changes the sign nibble of such
+         * all-negative-zero blocks and nothing else; both zeros dequantise to 0, so no product
+         * changes.  It is fixed so that the sign of a zero is defined by the value alone and an
+         * implementation that tracks signs differently (e.g. negated intermediate sums) is not
+         * forced to reproduce IEEE -0 propagation.  Pinned by test_sign_of_zero_rules. */
         if (v[j] == 0.0f) v[j] = 0.0f;
     }
 }

@@ -290,7 +290,8 @@ def test_fused_closed_form_hadamard_rows(b, golden_dir):
 
 def test_sign_of_zero_rules():
     """Without a transform the sign bit of a zero is the input's; a transformed value that is exactly
-    zero is stored as +0 (its sign would otherwise depend on the order of cancelling additions)."""
+    zero is stored as +0: a convention (the paper is silent; H v = 0 has no sign).  Plain IEEE
+    butterflies would keep -0 only for an all -0 block, which is the case planted here."""
     x = np.zeros((1, 64), dtype=np.float32)
     x[0, :32] = -0.0
     x[0, 32] = 1.0
@@ -381,6 +382,80 @@ def test_oe_row_residual_rows_have_zero_codes():
     # with the residual rows zero the MXFP4 part contributes nothing there: C[S] is the bf16 product
     exact = orc.exact_gemm(g.A.bits, True, g.B.bits, True)
     assert np.allclose(res["C"][S], exact[S], rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("b_k_contig", [True, False])
+@pytest.mark.parametrize("a_k_contig", [True, False])
+def test_oe_col_whole_path_against_numpy_pieces(a_k_contig, b_k_contig, golden_dir):
+    """OE-Right (Eq. 8) through adahop_gemm, B in both storage orders: FOID must pick the planted columns of B
+    (scored on B, over each column's first 64 K-elements), the residual of B -- and only of B -- loses exactly
+    those columns, C[:, S] is the float64 product on the original values and every other column is the product
+    of the two dequantised operands, all rebuilt here with numpy and the golden E2M1 table.  A carries amplified
+    rows and K-channels of its own, so scoring A, masking A or adding into rows instead of columns would each
+    fail one of the assertions."""
+    table = e2m1_table(golden_dir)
+    M, N, K, k = 40, 56, 128, 5
+    A = inputs.matrix(M, K, 1.0, 91, row_outliers=(4, 60.0, 60.0), col_outliers=(3, 40.0, 40.0))
+    Bt = inputs.matrix(N, K, 0.02, 92)                       # logical [N, K]: row n is column n of the paper's B
+    planted = np.sort(np.random.default_rng(93).permutation(N)[:k]).astype(np.int32)
+    bt = bits_to_f64(Bt)
+    bt[planted] *= 32.0                                      # power of two: stays exactly representable
+    Bt = bf16_bits(bt.astype(np.float32))
+    a_store = A if a_k_contig else np.ascontiguousarray(A.T)
+    b_store = Bt if b_k_contig else np.ascontiguousarray(Bt.T)
+    res = orc.adahop_gemm(a_store, a_k_contig, b_store, b_k_contig, orc.IHT_OE_COL, 32, k)
+    S = res["idx"]
+    assert S.tolist() == planted.tolist()
+    # residual: the extracted columns of B are gone from the MXFP4 operand, nothing is removed from A
+    assert np.all(res["b_codes"][S] == 0) and np.all(res["b_scales"][S] == 0)
+    rest = np.setdiff1d(np.arange(N), S)
+    assert np.all(res["b_scales"][rest] != 0)
+    ca, sa = orc.iht_quantize(a_store, a_k_contig, 32)
+    assert np.array_equal(ca, res["a_codes"]) and np.array_equal(sa, res["a_scales"])
+    Bres = Bt.copy()
+    Bres[S] = 0
+    cb, sb = orc.iht_quantize(Bres, True, 32)
+    assert np.array_equal(cb, res["b_codes"]) and np.array_equal(sb, res["b_scales"])
+    # C: extracted columns exact, the others the emulated MXFP4 product
+    a64, b64 = bits_to_f64(A), bits_to_f64(Bt)
+    assert np.allclose(res["C"][:, S], a64 @ b64[S].T, rtol=1e-12, atol=1e-14)
+    emu = dequant(res["a_codes"], res["a_scales"], table) @ dequant(res["b_codes"], res["b_scales"], table).T
+    assert np.all(emu[:, S] == 0)
+    assert np.allclose(res["C"][:, rest], emu[:, rest], rtol=1e-12, atol=1e-14)
+    # the quantised columns really differ from the exact ones (the test would not notice a BF16 product
+    # written everywhere otherwise)
+    assert np.linalg.norm(res["C"][:, rest] - (a64 @ b64[rest].T)) > 1e-3 * np.linalg.norm(a64 @ b64[rest].T)
+    # sampled outputs: rows x cols selections address the same matrix
+    rows = np.array([3, 17, 39], dtype=np.int32)
+    cols = np.array([int(S[1]), int(rest[0]), int(S[4]), int(rest[7])], dtype=np.int32)
+    sub = orc.adahop_gemm(a_store, a_k_contig, b_store, b_k_contig, orc.IHT_OE_COL, 32, k, rows=rows, cols=cols)
+    assert np.allclose(sub["C"], res["C"][np.ix_(rows, cols)], rtol=1e-13, atol=1e-300)
+    # caller-chosen indices take the place of FOID's
+    given = np.array([int(rest[2]), int(S[0])], dtype=np.int32)
+    alt = orc.adahop_gemm(a_store, a_k_contig, b_store, b_k_contig, orc.IHT_OE_COL, 32, 2, idx=given)
+    assert alt["idx"].tolist() == sorted(given.tolist())
+    assert np.all(alt["b_codes"][given] == 0) and np.any(alt["b_codes"][S[1]] != 0)
+    assert np.allclose(alt["C"][:, given], a64 @ b64[given].T, rtol=1e-12, atol=1e-14)
+
+
+def test_oe_row_whole_path_sampled_outputs(golden_dir):
+    """OE-Left (Eq. 7) with a rows x cols sample: the sample addresses the same C, extracted rows in it carry the
+    float64 product, the others the emulated MXFP4 product (numpy + golden table)."""
+    table = e2m1_table(golden_dir)
+    A = inputs.matrix(48, 96, 1.0, 95, row_outliers=(4, 100.0, 100.0))
+    Bt = inputs.matrix(40, 96, 0.02, 96, row_outliers=(3, 30.0, 30.0))
+    b_store = np.ascontiguousarray(Bt.T)
+    full = orc.adahop_gemm(A, True, b_store, False, orc.IHT_OE_ROW, 32, 4)
+    S = full["idx"]
+    rows = np.array([int(S[2]), 0 if 0 not in S else 1, int(S[0]), 47 if 47 not in S else 46], dtype=np.int32)
+    cols = np.array([39, 5, 12], dtype=np.int32)
+    sub = orc.adahop_gemm(A, True, b_store, False, orc.IHT_OE_ROW, 32, 4, rows=rows, cols=cols)
+    assert np.allclose(sub["C"], full["C"][np.ix_(rows, cols)], rtol=1e-13, atol=1e-300)
+    a64, b64 = bits_to_f64(A), bits_to_f64(Bt)
+    emu = dequant(full["a_codes"], full["a_scales"], table) @ dequant(full["b_codes"], full["b_scales"], table).T
+    for r, row in enumerate(rows):
+        want = (a64[row] @ b64.T)[cols] if row in S else emu[row, cols]
+        assert np.allclose(sub["C"][r], want, rtol=1e-12, atol=1e-14)
 
 
 def test_whole_path_matches_step_by_step_numpy(golden_dir):
