@@ -11,9 +11,15 @@
  * part chosen by a 64-sample variance score (paper Eq. 7-8, App. F).
  *
  * Conventions for every entry point
- *   - All data pointers are DEVICE pointers owned by the caller; the library allocates nothing,
- *     keeps no state between calls and never synchronises: work is queued on `stream`
- *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns.
+ *   - All data pointers are DEVICE pointers owned by the caller; the library allocates nothing
+ *     and never synchronises: work is queued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns.  No data is kept between calls.  The only state is
+ *     a per-device "configured" flag: the first call on a device that reaches a kernel with a
+ *     large LDS footprint sets that kernel's function attribute and reads the device's
+ *     compute-unit count (host-side HIP calls, no allocation, no synchronisation); make that
+ *     first call outside a stream capture.
+ *   - Sizes: 1 <= outer <= 2^21 and 32 <= K <= 2^21 for every operand (M, N, K of a product
+ *     alike), and outer * K < 2^35; anything larger is ADAHOP_E_INVALID_ARG.
  *   - Outputs are fully overwritten.  Inputs are not modified.
  *   - Return value: ADAHOP_OK, or a negative adahop_status_t.  Arguments are validated before any
  *     HIP call, so ADAHOP_E_INVALID_ARG / ADAHOP_E_WORKSPACE can be exercised without a GPU.
@@ -95,7 +101,7 @@ int adahop_iht_quantize(const adahop_operand_t *x, int iht_block, const uint8_t 
  * idx_out  int32 [k]    selected indices, ascending
  * mask_out uint8 [dim]  1 where selected, else 0 (8-byte aligned; usable as zero_outer / zero_k)
  * scores_ws float [dim] scratch for the scores (left filled on return)
- * 0 <= k <= dim, dim <= 2^24.
+ * 0 <= k <= dim.
  * ------------------------------------------------------------------------------------------- */
 int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_out, uint8_t *mask_out,
                      float *scores_ws, void *stream);
@@ -176,7 +182,8 @@ int adahop_iht_quantize_sr(const adahop_operand_t *x, int iht_block, const uint8
  *   adahop_oht_inverse: C (float [M, ldc], M % oht_block == 0, N % oht_block == 0) <- H^T C H^T in place.
  * adahop_gemm / adahop_gemm_ex with strategy ADAHOP_OHT run both operands through adahop_oht_quantize,
  * the MXFP4 product and adahop_oht_inverse; iht_block is then the OHT block, k is ignored, C must be
- * float (c_bf16 = 0) and M, N multiples of the block: INVALID_ARG otherwise.
+ * float (c_bf16 = 0) and M, N multiples of the block: INVALID_ARG otherwise.  outer / oht_block (M / oht_block
+ * for adahop_oht_inverse) must not exceed 65535.
  * ------------------------------------------------------------------------------------------- */
 int adahop_oht_quantize(const adahop_operand_t *x, int oht_block, uint8_t *codes, uint8_t *scales, void *stream);
 int adahop_oht_inverse(float *C, int64_t M, int64_t N, int64_t ldc, int oht_block, void *stream);
@@ -237,7 +244,8 @@ int adahop_oe_gemm_bf16(const adahop_operand_t *A, const adahop_operand_t *B, ad
 /* ---------------------------------------------------------------------------------------------
  * Outlier-pattern detection of one tensor and the pattern-pair -> strategy table (paper Sec. 4.1,
  * 4.2, App. A) -- what the paper's 30-step calibration evaluates per tensor and per step; the
- * majority vote over steps is left to the caller.
+ * majority vote over the steps is adahop_vote_pattern below (host-side), the table
+ * adahop_select_strategy.
  *
  * For the operand in its logical [outer, K] shape: v_outer[o] = variance of x[o, :], v_k[kk] =
  * variance of x[:, kk] (population variances, fp64), CV = std(v) / (mean(v) + 1e-12) for each vector,
@@ -273,7 +281,16 @@ int adahop_vote_pattern(const int32_t *patterns, int n);
  * returns ADAHOP_E_INVALID_ARG (as a negative value) on bad arguments. */
 int adahop_select_strategy(adahop_pattern_t pattern_a, adahop_pattern_t pattern_b, int level, int *full_bf16);
 
-/* Measurement aid (not part of the method): launches `workgroups` x 4 waves that each run
+/* hipError_t (as int) of the most recent failed HIP call on this thread, 0 if none. */
+int adahop_last_hip_error(void);
+const char *adahop_status_string(int status);
+/* ABI version: bumped on any incompatible change. */
+int adahop_abi_version(void);
+
+/* =============================================================================================
+ * DIAGNOSTICS -- not part of the method and not needed by a user of the product path.
+ * =============================================================================================
+ * Measurement aid: launches `workgroups` x 4 waves that each run
  * iters x 16 block-scaled FP4 matrix-core instructions (32x32x64, 131072 flop each) on register
  * operands only -- constant bits, or pseudo-random bits if random_operands != 0 -- so that a caller
  * timing the launch obtains the rate the matrix cores sustain on this machine without any memory
@@ -283,12 +300,6 @@ int adahop_select_strategy(adahop_pattern_t pattern_a, adahop_pattern_t pattern_
  * ceiling beside the published peak. */
 int adahop_probe_mfma_rate(int random_operands, int idle_sleeps, int workgroups, int iters, float *sink,
                            void *stream);
-
-/* hipError_t (as int) of the most recent failed HIP call on this thread, 0 if none. */
-int adahop_last_hip_error(void);
-const char *adahop_status_string(int status);
-/* ABI version: bumped on any incompatible change. */
-int adahop_abi_version(void);
 
 #ifdef __cplusplus
 }

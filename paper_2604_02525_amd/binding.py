@@ -111,6 +111,26 @@ def _ptr(t):
     return None if t is None else t.data_ptr()
 
 
+def _hold(stream, *temporaries):
+    """Temporaries allocated here are released when the Python call returns, while the kernels that use them may
+    still be queued.  That is safe on torch's current stream (the allocator hands the block to later work of the
+    same stream only).  For any other stream the block must be tied to it: a torch stream object is recorded on
+    each temporary; a raw stream handle cannot be, so the caller then has to pass the buffers in."""
+    if stream is None:
+        return
+    handle = getattr(stream, "cuda_stream", stream)
+    if handle == torch.cuda.current_stream().cuda_stream:
+        return
+    live = [t for t in temporaries if t is not None]
+    if not live:
+        return
+    if not hasattr(stream, "cuda_stream"):
+        raise ValueError("a raw stream handle other than the current stream needs caller-owned workspaces "
+                         "(pass workspace= / gather_ws=, or a torch.cuda.Stream)")
+    for t in live:
+        t.record_stream(stream)
+
+
 class Operand:
     """A bf16 device matrix as stored plus the flag saying which of its axes is K.
 
@@ -185,6 +205,7 @@ def adahop_gemm_mx(a_codes, a_scales, b_codes, b_scales, Cout=None, workspace=No
         Cout = torch.empty((M, N), dtype=torch.bfloat16 if c_bf16 else torch.float32, device=a_codes.device)
     if workspace is None:
         workspace = _u8((adahop_gemm_mx_workspace_bytes(M, N, K),), a_codes.device)
+        _hold(stream, workspace)
     fn, name = ((lib().adahop_gemm_mx_bf16out, "adahop_gemm_mx_bf16out") if Cout.element_size() == 2
                 else (lib().adahop_gemm_mx, "adahop_gemm_mx"))
     _check(fn(M, N, K, _ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), _ptr(Cout), Cout.stride(0),
@@ -226,6 +247,7 @@ def adahop_pack_operand(x, is_b, strategy, iht_block, k=0, idx=None, codes=None,
     codes = _u8((x.outer, x.K // 2), dev) if codes is None else codes
     scales = _u8((x.outer, x.K // 32), dev) if scales is None else scales
     mask_ws = _u8((max(x.outer, x.K),), dev) if k else None
+    _hold(stream, mask_ws)
     _check(lib().adahop_pack_operand(C.byref(x.c()), int(bool(is_b)), strategy, iht_block, k, _ptr(idx), _ptr(mask_ws),
                                      _ptr(codes), _ptr(scales), _stream(stream)), "adahop_pack_operand")
     return codes, scales
@@ -277,6 +299,7 @@ def adahop_oe_gemm_bf16(A, B, kind, idx, Cout, gather_ws=None, stream=None):
     need = adahop_oe_gather_bytes(A.outer, B.outer, A.K, kind, k)
     if gather_ws is None and need:
         gather_ws = _u8((need,), A.tensor.device)
+        _hold(stream, gather_ws)
     _check(lib().adahop_oe_gemm_bf16(C.byref(A.c()), C.byref(B.c()), kind, _ptr(idx), k, _ptr(Cout), Cout.stride(0),
                                      _ptr(gather_ws), 0 if gather_ws is None else gather_ws.numel(), _stream(stream)),
            "adahop_oe_gemm_bf16")
@@ -297,6 +320,7 @@ def adahop_detect_pattern(x, tau=2.0, workspace=None, stream=None):
     need = int(lib().adahop_detect_pattern_workspace_bytes(C.byref(x.c())))
     if workspace is None:
         workspace = _u8((max(need, 256),), dev)
+        _hold(stream, workspace)
     pattern = torch.empty(1, dtype=torch.int32, device=dev)
     stats = torch.empty(4, dtype=torch.float64, device=dev)
     _check(lib().adahop_detect_pattern(C.byref(x.c()), float(tau), _ptr(pattern), _ptr(stats), _ptr(workspace),

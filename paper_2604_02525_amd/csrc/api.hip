@@ -8,8 +8,12 @@ namespace adahop {
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(int e) { g_last_hip_error = e; }
 
-static const int64_t MAX_OUTER = (int64_t)1 << 22; // keeps every grid dimension legal
-static const int64_t MAX_K = (int64_t)1 << 24;
+// Largest operand extents.  They keep every launch legal: the second grid dimension of a launch may not exceed
+// 65535, and the kernels put K / 256 (fast quantisers), K / 128 (general K-strided quantiser: K / 32 blocks over
+// 4 waves) and stored rows / 256 (pattern detector) there.  The OHT kernels put outer / block there and check it
+// themselves (oht_grid_ok).
+static const int64_t MAX_OUTER = (int64_t)1 << 21;
+static const int64_t MAX_K = (int64_t)1 << 21;
 
 bool valid_iht_block(int b) { return b == 0 || b == 32 || b == 64 || b == 128 || b == 256; }
 
@@ -284,7 +288,8 @@ int adahop_pack_operand(const adahop_operand_t *x, int is_b, adahop_strategy_t s
     if (strategy < ADAHOP_NONE || strategy > ADAHOP_OHT) return ADAHOP_E_INVALID_ARG;
     if (!codes || !scales || !aligned(codes, 16)) return ADAHOP_E_INVALID_ARG;
     if (strategy == ADAHOP_OHT) {
-        if (!valid_oht_block(iht_block) || x->outer % iht_block != 0) return ADAHOP_E_INVALID_ARG;
+        if (!valid_oht_block(iht_block) || x->outer % iht_block != 0 || !oht_grid_ok(x->outer, iht_block))
+            return ADAHOP_E_INVALID_ARG;
         return launch_oht_quantize(*x, iht_block, codes, scales, static_cast<hipStream_t>(stream));
     }
     const int b = strategy == ADAHOP_NONE ? 0 : iht_block;
@@ -307,7 +312,8 @@ int adahop_oht_quantize(const adahop_operand_t *x, int oht_block, uint8_t *codes
 {
     int rc = validate_operand(x);
     if (rc != ADAHOP_OK) return rc;
-    if (!valid_oht_block(oht_block) || x->outer % oht_block != 0) return ADAHOP_E_INVALID_ARG;
+    if (!valid_oht_block(oht_block) || x->outer % oht_block != 0 || !oht_grid_ok(x->outer, oht_block))
+        return ADAHOP_E_INVALID_ARG;
     if (!codes || !scales || !aligned(codes, 16)) return ADAHOP_E_INVALID_ARG;
     return launch_oht_quantize(*x, oht_block, codes, scales, static_cast<hipStream_t>(stream));
 }
@@ -315,7 +321,8 @@ int adahop_oht_quantize(const adahop_operand_t *x, int oht_block, uint8_t *codes
 int adahop_oht_inverse(float *C, int64_t M, int64_t N, int64_t ldc, int oht_block, void *stream)
 {
     if (!C || !aligned(C, 4) || M < 1 || N < 1 || M > MAX_OUTER || N > MAX_OUTER || ldc < N) return ADAHOP_E_INVALID_ARG;
-    if (!valid_oht_block(oht_block) || M % oht_block != 0 || N % oht_block != 0) return ADAHOP_E_INVALID_ARG;
+    if (!valid_oht_block(oht_block) || M % oht_block != 0 || N % oht_block != 0 || !oht_grid_ok(M, oht_block))
+        return ADAHOP_E_INVALID_ARG;
     return launch_oht_inverse(C, M, N, ldc, oht_block, static_cast<hipStream_t>(stream));
 }
 
@@ -333,7 +340,8 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
     const bool oht = strategy == ADAHOP_OHT;
     const int b = strategy == ADAHOP_NONE ? 0 : iht_block;
     if (oht) {
-        if (!valid_oht_block(b) || M % b != 0 || N % b != 0 || c_bf16) return ADAHOP_E_INVALID_ARG;
+        if (!valid_oht_block(b) || M % b != 0 || N % b != 0 || c_bf16 || !oht_grid_ok(M, b) || !oht_grid_ok(N, b))
+            return ADAHOP_E_INVALID_ARG;
     } else {
         if (!valid_iht_block(b) || (b > 0 && K % b != 0)) return ADAHOP_E_INVALID_ARG;
         if (strategy != ADAHOP_NONE && b == 0) return ADAHOP_E_INVALID_ARG;
@@ -390,7 +398,7 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
                  : launch_iht_quantize(*A, b, a_kind == 1 ? mask : nullptr, a_kind == 2 ? mask : nullptr, c, s, st,
                                        opts && opts->sr_a ? &opts->sr_seed_a : nullptr, &sm);
         if (rc != ADAHOP_OK) return rc;
-        if (sm.out) sm_ready |= 1;
+        if (sm.out && iht_quantize_writes_scales_sm(*A)) sm_ready |= 1;
     }
     if (!b_given) {
         uint8_t *c = reinterpret_cast<uint8_t *>(ws + L.b_codes), *s = reinterpret_cast<uint8_t *>(ws + L.b_scales);
@@ -399,7 +407,7 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
                  : launch_iht_quantize(*B, b, b_kind == 1 ? mask : nullptr, b_kind == 2 ? mask : nullptr, c, s, st,
                                        opts && opts->sr_b ? &opts->sr_seed_b : nullptr, &sm);
         if (rc != ADAHOP_OK) return rc;
-        if (sm.out) sm_ready |= 2;
+        if (sm.out && iht_quantize_writes_scales_sm(*B)) sm_ready |= 2;
     }
     // 3. MXFP4 product, with the K-channel BF16 product fused in front; 4. row / column BF16 product
     if (oe && strategy == ADAHOP_IHT_OE_K) {

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/adahop.h"
 
 namespace adahop {
@@ -31,6 +33,9 @@ struct scales_sm_t {
     uint8_t *out; // stage-major copy, or nullptr
     int64_t rows; // rows [0, rows) are written
 };
+// Whether launch_iht_quantize honours a scales_sm_t for this operand (only its kernels for K % 256 == 0 write the
+// copy); a caller may tell the product that the copy is there only if this holds.
+bool iht_quantize_writes_scales_sm(const adahop_operand_t &x);
 // sr_seed: NULL = round to nearest even; else the elements are rounded stochastically under that seed.
 int launch_iht_quantize(const adahop_operand_t &x, int iht_block, const uint8_t *zero_outer,
                         const uint8_t *zero_k, uint8_t *codes, uint8_t *scales, hipStream_t st,
@@ -61,12 +66,26 @@ int launch_oe_k_accumulate(int64_t M, int64_t N, const uint16_t *Ag, const uint1
 
 // Outer Hadamard Transform strategy (paper Eq. 6): operand side and the rotations of C after the product.
 bool valid_oht_block(int b);
+// The OHT kernels put outer / b into the second grid dimension, which may not exceed 65535.
+inline bool oht_grid_ok(int64_t outer, int b) { return b > 0 && outer / b <= 65535; }
 int launch_oht_quantize(const adahop_operand_t &x, int b, uint8_t *codes, uint8_t *scales, hipStream_t st);
 int launch_oht_inverse(float *C, int64_t M, int64_t N, int64_t ldc, int b, hipStream_t st);
 
 size_t pattern_workspace_bytes(const adahop_operand_t &x);
 int launch_detect_pattern(const adahop_operand_t &x, double tau, double eps, int32_t *pattern_out, double *stats_out,
                           void *workspace, hipStream_t st);
+
+// One-time set-up per device (function attributes, device properties): the only state the library keeps.
+// need(dev) is true until mark(dev) has been called for that device; devices numbered 64 and above are set
+// up on every call.
+struct device_once_t {
+    std::atomic<uint64_t> done{0};
+    bool need(int dev) const { return dev < 0 || dev >= 64 || !((done.load(std::memory_order_acquire) >> dev) & 1u); }
+    void mark(int dev)
+    {
+        if (dev >= 0 && dev < 64) done.fetch_or((uint64_t)1 << dev, std::memory_order_release);
+    }
+};
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -14,7 +14,6 @@
 // 8*(l/32) .. +7 of row / column l % 32.
 #include "common.h"
 
-#include <atomic>
 #include <type_traits>
 
 namespace adahop {
@@ -184,8 +183,8 @@ __global__ __launch_bounds__(256) void k_stage_major_scales(const uint64_t *__re
 // assembly on purpose: with the builtin the compiler's wait-count pass makes every later LDS read
 // wait for ALL outstanding copies (it cannot tell that they target the other stage), which
 // serialises the copies with the matrix-core work.  The kernel waits for the copies itself
-// (s_waitcnt vmcnt(0) before the stage barrier).  M0 is written here and used by nothing else in
-// these kernels (no dynamic register indexing, no other DMA).
+// (s_waitcnt vmcnt(0) before the stage barrier).  M0 is written here (and declared clobbered) and used
+// by nothing else in these kernels (no dynamic register indexing, no other DMA).
 __device__ __forceinline__ const uint8_t *uniform_ptr(const uint8_t *p)
 {
     const uint64_t v = reinterpret_cast<uint64_t>(p);
@@ -202,7 +201,7 @@ __device__ __forceinline__ void dma16(const uint8_t *base, uint32_t voff, uint32
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(voff), "s"(base), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ uint32_t lds_address(const void *p)
@@ -688,25 +687,28 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     gemm_mx_tiled_part(M, N, K, kpad, a_scales, b_scales, C, ldc, sizeof(OUT) == 2, &Mi, &Ni);
     if (Mi == 0) return generic(M, N, a_codes, a_scales, b_codes, b_scales, C, Ag, Bg);
 
-    int dev = 0, ncu = 0;
+    int dev = 0;
     int rc0 = check_hip(hipGetDevice(&dev));
     if (rc0 != ADAHOP_OK) return rc0;
-    rc0 = check_hip(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
-    if (rc0 != ADAHOP_OK) return rc0;
-    ncu = ncu / 8 * 8; // keep a workgroup's tiles on one XCD
-    if (ncu < 8) ncu = 8;
-    // the kernels need more LDS than a launch may ask for by default: once per output type and device
-    static std::atomic<uint64_t> configured{0};
-    const uint64_t dev_bit = dev < 64 ? (uint64_t)1 << dev : 0;
-    if (!(configured.load() & dev_bit)) {
+    // Once per output type and device: the compute-unit count, and the kernels' LDS size (more than a launch may
+    // ask for by default).
+    static device_once_t once;
+    static std::atomic<int> cu_count[64];
+    int ncu = dev >= 0 && dev < 64 ? cu_count[dev].load(std::memory_order_relaxed) : 0;
+    if (once.need(dev) || ncu == 0) {
+        rc0 = check_hip(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+        if (rc0 != ADAHOP_OK) return rc0;
         int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false, OUT>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
         if (rc != ADAHOP_OK) return rc;
         rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true, OUT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
         if (rc != ADAHOP_OK) return rc;
-        configured.fetch_or(dev_bit);
+        if (dev >= 0 && dev < 64) cu_count[dev].store(ncu, std::memory_order_relaxed);
+        once.mark(dev);
     }
+    ncu = ncu / 8 * 8; // keep a workgroup's tiles on one XCD
+    if (ncu < 8) ncu = 8;
     // scales of the tiled part, stage-major, in the caller's workspace (sm_ready bit 0 / 1: the quantiser of A / B
     // has already written them there)
     uint8_t *a_sm = gemm_mx_scales_sm(workspace, M, K, 0), *b_sm = gemm_mx_scales_sm(workspace, M, K, 1);

@@ -152,10 +152,17 @@ __global__ __launch_bounds__(256) void k_oht_inverse(float *__restrict__ C, int6
 template <int B> int launch_quant(const adahop_operand_t &x, uint8_t *codes, uint8_t *scales, hipStream_t st)
 {
     const size_t lds = (size_t)B * OHT_KP * sizeof(float);
-    // more LDS than a launch may ask for by default (B = 128): the attribute is per device and cheap to set
-    int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_quant<B>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    // more LDS than a launch may ask for by default (B = 128): set once per device
+    static device_once_t once;
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
     if (rc != ADAHOP_OK) return rc;
+    if (once.need(dev)) {
+        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_quant<B>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (rc != ADAHOP_OK) return rc;
+        once.mark(dev);
+    }
     const dim3 grid((unsigned)ceil_div(x.K, OHT_TK), (unsigned)(x.outer / B));
     hipLaunchKernelGGL(k_oht_quant<B>, grid, dim3(256), lds, st, static_cast<const uint16_t *>(x.data), x.outer, x.K, x.ld,
                        x.k_contig, codes, scales);
@@ -165,10 +172,17 @@ template <int B> int launch_quant(const adahop_operand_t &x, uint8_t *codes, uin
 template <int B> int launch_inverse(float *C, int64_t M, int64_t N, int64_t ldc, hipStream_t st)
 {
     const size_t lds = (size_t)B * OHT_NP * sizeof(float);
-    // more LDS than a launch may ask for by default (B = 128): the attribute is per device and cheap to set
-    int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    // more LDS than a launch may ask for by default (B = 128): set once per device
+    static device_once_t once;
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
     if (rc != ADAHOP_OK) return rc;
+    if (once.need(dev)) {
+        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (rc != ADAHOP_OK) return rc;
+        once.mark(dev);
+    }
     const dim3 grid((unsigned)ceil_div(N, OHT_TN), (unsigned)(M / B));
     hipLaunchKernelGGL(k_oht_inverse<B>, grid, dim3(256), lds, st, C, M, N, ldc);
     return check_launch();

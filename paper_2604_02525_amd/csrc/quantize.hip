@@ -663,7 +663,7 @@ template <int B, bool SR>
 int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
               sr_key_t key, scales_sm_t sm, hipStream_t st)
 {
-    if (x.K % 256 == 0 && x.K / 256 <= 65535) {
+    if (iht_quantize_writes_scales_sm(x)) {
         dim3 grid((unsigned)ceil_div(x.outer, KS_COLS), (unsigned)(x.K / 256));
         hipLaunchKernelGGL((k_quant_ks16<B, SR>), grid, dim3(256), 0, st, static_cast<const uint16_t *>(x.data), x.outer,
                            x.K, x.ld, zo, zk, codes, scales, key, sm);
@@ -672,10 +672,17 @@ int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, u
     constexpr int NW = ks_cfg<B>::NW;
     constexpr int NCH = ks_cfg<B>::NCH;
     const size_t lds = NCH > 1 ? (size_t)NW * 32 * 64 * sizeof(float2) : 0;
-    if (lds > 48 * 1024) {
-        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_quant_ks<B, SR>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    if (lds > 48 * 1024) { // more LDS than a launch may ask for by default: set once per device
+        static device_once_t once;
+        int dev = 0;
+        int rc = check_hip(hipGetDevice(&dev));
         if (rc != ADAHOP_OK) return rc;
+        if (once.need(dev)) {
+            rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_quant_ks<B, SR>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            if (rc != ADAHOP_OK) return rc;
+            once.mark(dev);
+        }
     }
     dim3 grid((unsigned)ceil_div(x.outer, 128), (unsigned)ceil_div(x.K / 32, NW));
     hipLaunchKernelGGL((k_quant_ks<B, SR>), grid, dim3(NW * 64), lds, st, static_cast<const uint16_t *>(x.data),
@@ -705,6 +712,10 @@ int dispatch_block(const adahop_operand_t &x, int b, const uint8_t *zo, const ui
 
 } // namespace
 
+// The kernels for K % 256 == 0 (K / 256 is a grid dimension of the K-strided one) are the ones that also write
+// the stage-major copy of the scales.
+bool iht_quantize_writes_scales_sm(const adahop_operand_t &x) { return x.K % 256 == 0 && x.K / 256 <= 65535; }
+
 // sr_seed: NULL for round-to-nearest-even, else the seed of the stochastic rounding of the elements.
 // sm: NULL, or where a stage-major copy of the scales goes; honoured by the kernels for K % 256 == 0 only,
 // which is also the only case in which the tiled GEMM kernel asks for it.
@@ -712,7 +723,7 @@ int launch_iht_quantize(const adahop_operand_t &x, int b, const uint8_t *zo, con
                         uint8_t *scales, hipStream_t st, const uint64_t *sr_seed, const scales_sm_t *sm)
 {
     if (x.outer == 0 || x.K == 0) return ADAHOP_OK;
-    const scales_sm_t smv = sm && x.K % 256 == 0 && x.K / 256 <= 65535 ? *sm : scales_sm_t{nullptr, 0};
+    const scales_sm_t smv = sm && iht_quantize_writes_scales_sm(x) ? *sm : scales_sm_t{nullptr, 0};
     if (sr_seed) {
         const sr_key_t key = {(uint32_t)*sr_seed, (uint32_t)(*sr_seed >> 32)};
         return dispatch_block<true>(x, b, zo, zk, codes, scales, key, smv, st);

@@ -269,3 +269,33 @@ def test_vote_pattern_matches_the_oracle_and_rejects_bad_input():
     assert L.adahop_vote_pattern(arr, 3) == ah.ADAHOP_E_INVALID_ARG
     assert L.adahop_vote_pattern(arr, 0) == ah.ADAHOP_E_INVALID_ARG
     assert L.adahop_vote_pattern(None, 3) == ah.ADAHOP_E_INVALID_ARG
+
+
+def test_size_limits_keep_every_launch_legal():
+    """Operand extents beyond 2^21 are rejected up front (the second grid dimension of the K-strided quantisers,
+    the pattern detector and the OHT kernels is K / 256, K / 128, stored rows / 256 and outer / block, and may not
+    exceed 65535), so that no accepted shape can reach a launch that fails -- in particular the K = 2^24 operand for
+    which the K-strided quantiser once dropped the stage-major scale copy the product then relied on."""
+    L = ah.lib()
+    big = 1 << 21
+    q = lambda x: L.adahop_iht_quantize(C.byref(x), 256, None, None, FAKE, FAKE, None)
+    for K in (1 << 24, big + 256):
+        for kc in (1, 0):
+            assert q(op(64, K, kc=kc)) == ah.ADAHOP_E_INVALID_ARG, (K, kc)
+    assert q(op(big + 8, 256, kc=0)) == ah.ADAHOP_E_INVALID_ARG
+    assert q(op(big, 1 << 15)) == ah.ADAHOP_E_INVALID_ARG                 # outer * K reaches 2^35
+    assert L.adahop_gemm_mx_workspace_bytes(256, 256, 1 << 24) == 0
+    assert L.adahop_gemm_mx_workspace_bytes(256, 256, big) == 2 * 256 * (big // 32)
+    assert L.adahop_gemm_workspace_bytes(256, 256, 1 << 24, ah.ADAHOP_IHT, 0) == 0
+    need = L.adahop_gemm_workspace_bytes(256, 256, big, ah.ADAHOP_IHT, 0)
+    assert need > 0
+    A = op(256, 1 << 24, kc=0)
+    assert L.adahop_gemm(C.byref(A), C.byref(A), FAKE, 256, ah.ADAHOP_IHT, 256, 0, None, 0, FAKE, 1 << 40,
+                         None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_foid_topk(C.byref(op(64, 1 << 24)), 1, 4, FAKE, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_detect_pattern_workspace_bytes(C.byref(op(64, 1 << 24, kc=0))) == 0
+    # OHT: outer / block is a grid dimension
+    assert L.adahop_oht_quantize(C.byref(op(big, 32)), 32, FAKE, FAKE, None) == ah.ADAHOP_E_INVALID_ARG   # 65536 blocks
+    assert L.adahop_oht_inverse(FAKE, big, 32, 32, 32, None) == ah.ADAHOP_E_INVALID_ARG
+    assert L.adahop_pack_operand(C.byref(op(big, 32)), 0, ah.ADAHOP_OHT, 32, 0, None, None, FAKE, FAKE,
+                                 None) == ah.ADAHOP_E_INVALID_ARG
