@@ -1,9 +1,12 @@
 """Parity at the full BASELINE sizes, in the launch configuration bench.py times.
 
 For every GEMM of configs[1..4]: FOID indices, masks, packed codes and scales of both operands are
-compared bit for bit over the whole operand; C is compared with the oracle on a seeded sample of
-rows x columns (always containing some extracted rows / columns when the strategy extracts any),
-within 1e-3 relative Frobenius error.
+compared bit for bit over the whole operand.  C: configs[1] and configs[2] against the oracle's whole C;
+configs[3], configs[4] and the latency-table shapes on a seeded sample of rows x columns that has two
+rows in every 256-row band of C and two columns in every 256-column band (one in each half: the
+sample touches every 256x256 workgroup tile and every 128x128 wave tile of the product) plus, when
+the strategy extracts rows / columns, some of those.  Bars as in test_gpu_parity (1e-3 relative
+Frobenius per row class, per-element accumulation allowance).
 """
 import numpy as np
 import pytest
@@ -16,39 +19,48 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def sample(g, nrows=40, ncols=160, seed=0):
-    """Seeded rows x cols sample of C; when rows / columns are extracted, a few of them are included."""
+def one_per_half_band(n, rng, band=256):
+    """Two indices in every band of `band` consecutive ones (one per half band), jittered; clipped to n."""
+    starts = np.arange(0, n, band // 2)
+    picks = starts + rng.integers(0, band // 2, len(starts))
+    return picks[picks < n]
+
+
+def sample(g, seed=0, extracted=6):
+    """Seeded rows x cols sample of C with an element in every 128x128 block; when rows / columns are
+    extracted, `extracted` of them are included."""
     M, N, K = g.shape
     rng = np.random.default_rng(seed + M + N)
-    rows = rng.permutation(M)[:nrows]
-    cols = rng.permutation(N)[:ncols]
+    rows, cols = one_per_half_band(M, rng), one_per_half_band(N, rng)
     if g.k > 0 and g.strategy == inputs.IHT_OE_ROW:
         sel, _ = orc.foid_topk(g.A.bits, g.A.k_contig, 0, g.k)
-        rows[:6] = sel[np.linspace(0, len(sel) - 1, 6).astype(int)]
+        rows = np.concatenate([rows, sel[np.linspace(0, len(sel) - 1, extracted).astype(int)]])
     if g.k > 0 and g.strategy == inputs.IHT_OE_COL:
         sel, _ = orc.foid_topk(g.B.bits, g.B.k_contig, 0, g.k)
-        cols[:6] = sel[np.linspace(0, len(sel) - 1, 6).astype(int)]
+        cols = np.concatenate([cols, sel[np.linspace(0, len(sel) - 1, extracted).astype(int)]])
     return np.unique(rows).astype(np.int32), np.unique(cols).astype(np.int32)
 
 
-def check(ah, g, rows_cols=None):
-    rows, cols = rows_cols if rows_cols is not None else sample(g)
-    say("config GEMM", g.name, inputs.STRATEGY_NAMES[g.strategy], "k =", g.k, g.shape)
+def check(ah, g, rows_cols=None, whole=False):
+    """whole: compare every element of C (the oracle's double-precision product of the full size)."""
+    rows, cols = (None, None) if whole else (rows_cols if rows_cols is not None else sample(g))
+    say("config GEMM", g.name, inputs.STRATEGY_NAMES[g.strategy], "k =", g.k, g.shape,
+        "whole C" if whole else f"sample {len(rows)} x {len(cols)}")
     return run_whole(ah, g, rows=rows, cols=cols)
 
 
 def test_config1_forward_up_projection(ah):
     g = inputs.config1()[0]
-    _, q_iht = check(ah, g)
+    _, q_iht = check(ah, g, whole=True)
     g_oe = inputs.config1(strategy=inputs.IHT_OE_K, k=8)[0]
-    _, q_oe = check(ah, g_oe)
+    _, q_oe = check(ah, g_oe, whole=True)
     # the 8 amplified channels are exactly what FOID finds, and routing them to BF16 must help
     assert q_oe < q_iht
 
 
 def test_config2_oe_row(ah):
     g = inputs.config2()[0]
-    _, q_oe = check(ah, g)
+    _, q_oe = check(ah, g, whole=True)
     g_iht = inputs.config2()[0]
     g_iht.strategy, g_iht.k = inputs.IHT, 0
     _, q_iht = check(ah, g_iht)

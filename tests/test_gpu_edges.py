@@ -125,15 +125,15 @@ def test_extreme_magnitudes_quantise_bit_exact(ah, b, k_contig):
 
 
 def test_operands_at_the_size_limits(ah):
-    """outer = 2^22 (the documented maximum) with the shortest K, and a long-K operand: every byte against the oracle;
-    FOID over 2^22 indices."""
+    """outer = 2^21 (the documented maximum) with the shortest K, and a long-K operand: every byte against the oracle;
+    FOID over 2^21 indices."""
     rng = np.random.default_rng(5)
-    outer = 1 << 22
+    outer = 1 << 21
     x = torch.randn((outer, 32), generator=torch.Generator().manual_seed(11)).to(torch.bfloat16)
     x[rng.integers(0, outer, 50)] *= 30.0
     bits = x.view(torch.int16).numpy().view(np.uint16)
     for kc, arr in ((True, bits), (False, np.ascontiguousarray(bits.T))):
-        say("outer = 2^22", "K-contiguous" if kc else "K-strided")
+        say("outer = 2^21", "K-contiguous" if kc else "K-strided")
         op = ah.Operand(torch.from_numpy(arr.view(np.int16)).cuda(), kc)
         codes, scales = ah.adahop_iht_quantize(op, 32)
         torch.cuda.synchronize()
@@ -146,10 +146,10 @@ def test_operands_at_the_size_limits(ah):
         assert np.array_equal(host(idx), ri) and np.array_equal(host(mask), rm)
         del op
     torch.cuda.empty_cache()
-    K = 1 << 22
+    K = 1 << 21
     y = torch.randn((24, K), generator=torch.Generator().manual_seed(12)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     for kc, arr in ((True, y), (False, np.ascontiguousarray(y.T))):
-        say("K = 2^22", "K-contiguous" if kc else "K-strided")
+        say("K = 2^21", "K-contiguous" if kc else "K-strided")
         op = ah.Operand(torch.from_numpy(arr.view(np.int16)).cuda(), kc)
         codes, scales = ah.adahop_iht_quantize(op, 256)
         torch.cuda.synchronize()

@@ -1,8 +1,15 @@
 """GPU-vs-oracle parity through the C ABI (run with -m gpu on an MI355X).
 
-Bars: packed E2M1 codes, E8M0 scales, FOID indices and masks bit-exact; GEMM outputs within 1e-3
-relative Frobenius error of the oracle's emulated-MXFP4 result (the arithmetic only differs in fp32
-accumulation order, so the observed error is ~1e-6).
+Bars: packed E2M1 codes, E8M0 scales, FOID indices and masks bit-exact.  GEMM outputs: within 1e-3
+relative Frobenius error of the oracle's emulated-MXFP4 result, taken separately over the extracted
+rows / columns (BF16 path, ~100x larger values) and over the rest, so that the large entries cannot
+hide an error in the ordinary ones; and every compared element within
+    |C_gpu[i, j] - C_oracle[i, j]| <= 2^-20 |A[i, :]|_2 |B[j, :]|_2.
+Both sides sum the same exact products (E2M1 values times powers of two, or bf16 x bf16, are exact in
+fp32); only the fp32 accumulation order of the GPU differs from the oracle's double sum.  A length-K
+fp32 accumulation errs by about sqrt(K) 2^-24 |C| and |C| is about |A_i| |B_j| / sqrt(K) for these
+inputs, so the allowance is some tens of times the expected error and, relative to a typical |C|,
+sqrt(K) 2^-20 <= 1e-4: a wrong operand byte, scale or tile lands orders of magnitude above it.
 """
 import numpy as np
 import pytest
@@ -38,6 +45,48 @@ def host(t):
 
 def rel_fro(got, ref):
     return float(np.linalg.norm(got.astype(np.float64) - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def row_norms(op, sel=None):
+    """2-norms of the logical rows (all of them, or those in sel) of an inputs.Operand, in float64."""
+    bits = op.bits if op.k_contig else op.bits.T
+    if sel is not None:
+        bits = bits[np.asarray(sel, dtype=np.int64)]
+    out = np.empty(bits.shape[0])
+    for r0 in range(0, bits.shape[0], 1024):          # in slabs: a whole config operand in float64 is gigabytes
+        v = (np.ascontiguousarray(bits[r0:r0 + 1024]).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        out[r0:r0 + 1024] = np.sqrt((v * v).sum(axis=1))
+    return out
+
+
+def check_c(got, ref, g, rows=None, cols=None, extracted=None, tol=1e-3):
+    """The bars of the module docstring on C (got: what the GPU wrote, ref: the oracle's, both on rows x cols).
+    extracted: the indices the strategy routed to BF16 (rows for OE-row, columns for OE-col)."""
+    got = got.astype(np.float64)
+    bar = 2.0 ** -20 * np.outer(row_norms(g.A, rows), row_norms(g.B, cols))
+    excess = np.abs(got - ref) - bar
+    worst = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess[worst] <= 0.0, (f"element {worst} of the compared block: |{got[worst]} - {ref[worst]}| exceeds the "
+                                  f"accumulation allowance {bar[worst]:.3e}")
+    err = rel_fro(got, ref)
+    assert err < tol
+    parts = {}
+    if extracted is not None and len(extracted):
+        R = np.arange(ref.shape[0]) if rows is None else np.asarray(rows)
+        Cc = np.arange(ref.shape[1]) if cols is None else np.asarray(cols)
+        if g.strategy == inputs.IHT_OE_ROW:
+            m = np.isin(R, extracted)
+            split = ((got[m], ref[m]), (got[~m], ref[~m]))
+        elif g.strategy == inputs.IHT_OE_COL:
+            m = np.isin(Cc, extracted)
+            split = ((got[:, m], ref[:, m]), (got[:, ~m], ref[:, ~m]))
+        else:
+            split = ()
+        for name, (a, b) in zip(("extracted", "residual"), split):
+            if a.size:
+                parts[name] = rel_fro(a, b)
+                assert parts[name] < tol, name
+    return err, parts, float((np.abs(got - ref) / bar).max())
 
 
 def rand_bits(rng, shape, scale=1.0):
@@ -220,12 +269,13 @@ def run_whole(ah, g, rows=None, cols=None, given_idx=None, tol=1e-3):
     if cols is not None:
         C = C[:, torch.from_numpy(np.asarray(cols, dtype=np.int64)).cuda()]
     got = host(C)
-    err = rel_fro(got, ref["C"])
+    err, parts, used = check_c(got, ref["C"], g, rows, cols, ref["idx"] if g.k > 0 else None, tol)
     exact = orc.exact_gemm(g.A.bits, g.A.k_contig, g.B.bits, g.B.k_contig, rows=rows, cols=cols)
     q = rel_fro(got, exact)
     say(f"  {g.name} {inputs.STRATEGY_NAMES[g.strategy]} b={g.iht_block} k={g.k} shape={g.shape}: "
-        f"vs oracle {err:.3e}, vs exact product {q:.3e}")
-    assert err < tol
+        f"vs oracle {err:.3e} " + " ".join(f"{n} {v:.3e}" for n, v in parts.items()) +
+        f", worst element at {used:.3f} of its allowance, vs exact product {q:.3e} "
+        f"({got.shape[0]} x {got.shape[1]} elements compared)")
     return err, q
 
 
