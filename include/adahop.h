@@ -106,6 +106,23 @@ int adahop_iht_quantize(const adahop_operand_t *x, int iht_block, const uint8_t 
 int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_out, uint8_t *mask_out,
                      float *scores_ws, void *stream);
 
+/* adahop_foid_topk for callers that cannot allocate device memory or hand over a scratch buffer (code under
+ * stream capture, tight serving loops, harnesses that forbid allocation): same arguments and results, but the
+ * scores go to a fixed array inside the library's device image instead of scores_ws.  The call allocates
+ * and frees nothing.
+ *   - Limit: dim (outer for axis 0, K for axis 1) <= ADAHOP_FOID_NOALLOC_MAX_DIM; beyond it the call returns
+ *     ADAHOP_E_WORKSPACE and queues nothing.  The array takes ADAHOP_FOID_NOALLOC_MAX_DIM * 4 bytes (1 MiB) on
+ *     every GPU the library runs on, until the process ends.
+ *   - The first call on a device looks up the array's device address (a host-side HIP call, no allocation);
+ *     later calls on that device reuse it.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *     threads) race on it and must be serialised by the caller.  Calls in sequence on one stream are safe; the
+ *     array keeps the previous call's scores, and every entry a call reads is written by that call first, so
+ *     nothing needs clearing. */
+#define ADAHOP_FOID_NOALLOC_MAX_DIM 262144
+int adahop_foid_topk_noalloc(const adahop_operand_t *x, int axis, int k, int32_t *idx_out, uint8_t *mask_out,
+                             void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Block-scaled FP4 product on packed operands (the MXFP4 term of Eq. 4 / 5 / 7 / 8):
  *   C[m, n] = sum_blk 2^(sa[m,blk]-127) 2^(sb[n,blk]-127) sum_{i<32} a[m, 32 blk + i] b[n, 32 blk + i]

@@ -17,7 +17,7 @@ ADAHOP_NONE, ADAHOP_IHT, ADAHOP_IHT_OE_ROW, ADAHOP_IHT_OE_COL, ADAHOP_IHT_OE_K, 
 ADAHOP_OK, ADAHOP_E_INVALID_ARG, ADAHOP_E_WORKSPACE, ADAHOP_E_HIP = 0, -1, -2, -3
 ADAHOP_PATTERN_NONE, ADAHOP_PATTERN_OUTER, ADAHOP_PATTERN_K = range(3)
 
-EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_gemm_mx",
+EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "adahop_foid_topk_noalloc", "adahop_gemm_mx",
            "adahop_gemm_mx_bf16out", "adahop_gemm_mx_workspace_bytes", "adahop_pack_operand", "adahop_gemm_ex",
            "adahop_oht_quantize", "adahop_oht_inverse", "adahop_iht_quantize_sr",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
@@ -67,6 +67,7 @@ def lib():
         L.adahop_iht_quantize.argtypes = [OP, I, P, P, P, P, P]
         L.adahop_iht_quantize_sr.argtypes = [OP, I, P, P, C.c_uint64, P, P, P]
         L.adahop_foid_topk.argtypes = [OP, I, I, P, P, P, P]
+        L.adahop_foid_topk_noalloc.argtypes = [OP, I, I, P, P, P]
         L.adahop_gemm_mx.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P, SZ, P]
         L.adahop_gemm_mx_bf16out.argtypes = [I64, I64, I64, P, P, P, P, P, I64, P, SZ, P]
         L.adahop_pack_operand.argtypes = [OP, I, I, I, I, P, P, P, P, P]
@@ -191,6 +192,17 @@ def adahop_foid_topk(x, axis, k, stream=None):
     _check(lib().adahop_foid_topk(C.byref(x.c()), axis, k, _ptr(idx), _ptr(mask), _ptr(scores), _stream(stream)),
            "adahop_foid_topk")
     return idx[:k], mask, scores
+
+
+FOID_NOALLOC_MAX_DIM = 262144
+
+
+def adahop_foid_topk_noalloc(x, axis, k, idx, mask, stream=None):
+    """adahop_foid_topk with the scores in the library's built-in scratch: idx (int32, at least k entries) and mask
+    (uint8 [dim]) are the caller's; nothing is allocated here or in the library."""
+    _check(lib().adahop_foid_topk_noalloc(C.byref(x.c()), axis, k, _ptr(idx), _ptr(mask), _stream(stream)),
+           "adahop_foid_topk_noalloc")
+    return idx[:k], mask
 
 
 def adahop_gemm_mx_workspace_bytes(M, N, K):

@@ -108,6 +108,21 @@ int adahop_foid_topk(const adahop_operand_t *x, int axis, int k, int32_t *idx_ou
     return launch_foid_topk(*x, axis, k, idx_out, mask_out, scores_ws, static_cast<hipStream_t>(stream));
 }
 
+int adahop_foid_topk_noalloc(const adahop_operand_t *x, int axis, int k, int32_t *idx_out, uint8_t *mask_out,
+                             void *stream)
+{
+    int rc = validate_operand(x);
+    if (rc != ADAHOP_OK) return rc;
+    if (axis != 0 && axis != 1) return ADAHOP_E_INVALID_ARG;
+    const int64_t dim = axis == 0 ? x->outer : x->K;
+    if (dim > ADAHOP_FOID_NOALLOC_MAX_DIM) return ADAHOP_E_WORKSPACE; // beyond the built-in scratch
+    if (k < 0 || k > dim || !mask_out || (k > 0 && !idx_out) || !aligned(mask_out, 8)) return ADAHOP_E_INVALID_ARG;
+    float *scores = nullptr;
+    rc = foid_static_scores(&scores);
+    if (rc != ADAHOP_OK) return rc;
+    return launch_foid_topk(*x, axis, k, idx_out, mask_out, scores, static_cast<hipStream_t>(stream));
+}
+
 size_t adahop_gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (M < 1 || N < 1 || K < 32 || K % 32 != 0 || M > MAX_OUTER || N > MAX_OUTER || K > MAX_K) return 0;

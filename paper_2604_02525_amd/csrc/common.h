@@ -42,6 +42,8 @@ int launch_iht_quantize(const adahop_operand_t &x, int iht_block, const uint8_t 
                         const uint64_t *sr_seed = nullptr, const scales_sm_t *sm = nullptr);
 int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, uint8_t *mask, float *scores,
                      hipStream_t st);
+// Device address, on the current device, of the library's built-in score scratch (ADAHOP_FOID_NOALLOC_MAX_DIM floats).
+int foid_static_scores(float **out);
 int launch_mask_from_idx(const int32_t *idx, int k, uint8_t *mask, int64_t dim, hipStream_t st);
 // OE-K operands for the fused prologue: Ag [M, kpad], Bg [N, kpad] bf16, K-contiguous, zero padded.
 int launch_gemm_mx(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, const uint8_t *a_scales,

@@ -350,6 +350,32 @@ int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, u
     return check_launch();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Score scratch that needs no allocation: a fixed array in the library's own device image, for the entry point
+// that serves callers which cannot allocate.  Every GPU the library runs on holds its own copy (at its own
+// address) until the process ends.  In host code the array's name is only a stand-in; the address that kernels
+// and copies may use is asked for once per device, with that device current, and kept.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) float scratch[ADAHOP_FOID_NOALLOC_MAX_DIM];
+
+int foid_static_scores(float **out)
+{
+    static std::atomic<float *> per_device[64];
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
+    if (rc != ADAHOP_OK) return rc;
+    if (dev < 0 || dev >= 64) return ADAHOP_E_INVALID_ARG;
+    float *ptr = per_device[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        rc = check_hip(hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)));
+        if (rc != ADAHOP_OK) return rc;
+        if (!ptr) return ADAHOP_E_HIP;
+        per_device[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return ADAHOP_OK;
+}
+
 int launch_mask_from_idx(const int32_t *idx, int k, uint8_t *mask, int64_t dim, hipStream_t st)
 {
     if (dim == 0) return ADAHOP_OK;

@@ -299,3 +299,15 @@ def test_size_limits_keep_every_launch_legal():
     assert L.adahop_oht_inverse(FAKE, big, 32, 32, 32, None) == ah.ADAHOP_E_INVALID_ARG
     assert L.adahop_pack_operand(C.byref(op(big, 32)), 0, ah.ADAHOP_OHT, 32, 0, None, None, FAKE, FAKE,
                                  None) == ah.ADAHOP_E_INVALID_ARG
+
+
+def test_foid_noalloc_rejects_before_touching_the_gpu():
+    L = ah.lib()
+    f = lambda x, axis=0, k=4, idx=FAKE, mask=FAKE: L.adahop_foid_topk_noalloc(C.byref(x), axis, k, idx, mask, None)
+    assert f(op(ah.FOID_NOALLOC_MAX_DIM + 8, 64)) == ah.ADAHOP_E_WORKSPACE        # beyond the built-in scratch
+    assert f(op(64, ah.FOID_NOALLOC_MAX_DIM + 32), axis=1) == ah.ADAHOP_E_WORKSPACE
+    assert f(op(), axis=2) == ah.ADAHOP_E_INVALID_ARG
+    assert f(op(), k=65) == ah.ADAHOP_E_INVALID_ARG
+    assert f(op(), idx=None) == ah.ADAHOP_E_INVALID_ARG
+    assert f(op(), mask=FAKE + 4) == ah.ADAHOP_E_INVALID_ARG
+    assert f(op(K=100)) == ah.ADAHOP_E_INVALID_ARG
