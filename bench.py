@@ -23,6 +23,7 @@ BF16_PEAK_TFLOPS = 2516.0
 # dispatch), each scaled by what the same counter reads for a plain 1 GiB copy (--copy-calibration);
 # the runs and the scaling are in profiles/gemm_mx_16384x28672x8192_counters.txt.
 GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 5.05e9}
+GEMM_HBM_TRAFFIC_SOURCE = "profiles/gemm_mx_16384x28672x8192_counters.txt (rocprofv3 --pmc runs; not measured in this run)"
 
 
 def parse():
@@ -34,6 +35,8 @@ def parse():
     p.add_argument("--k-pct", type=float, default=1.0, help="extraction count as %% of the extracted dim (cfg4)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the k-sweep / BF16 / per-stage extras")
+    p.add_argument("--no-other-workloads", action="store_true",
+                   help="skip the one-line summaries of configs[1], configs[3] and the latency-table shapes")
     p.add_argument("--dominant-kernel-only", action="store_true",
                    help="profiling aid: time only the FP4 GEMM of the largest product (the roofline object); the "
                         "whole-step figures of the JSON line are then absent")
@@ -111,6 +114,104 @@ def time_ms(torch, fn, iters, warmup=1):
     return e0.elapsed_time(e1) / iters
 
 
+def bf16_views(torch, p):
+    a16, b16 = p.A.tensor.view(torch.bfloat16), p.B.tensor.view(torch.bfloat16)
+    return (a16 if p.A.k_contig else a16.t()), (b16.t() if p.B.k_contig else b16)
+
+
+def stage_times(ah, torch, inputs, p, ws, iters=5):
+    """Per-stage times of one product, each stage bracketed by its own events (so the stages do not overlap and the
+    sum exceeds the fused call slightly): FOID, quantise A, quantise B, K-channel gathers + MXFP4 product (+ the BF16
+    row / column product), and the MXFP4 kernel alone on the packed operands."""
+    g = p.g
+    oe = g.strategy in (inputs.IHT_OE_ROW, inputs.IHT_OE_COL, inputs.IHT_OE_K) and g.k > 0
+    scored, axis = {inputs.IHT_OE_ROW: (p.A, 0), inputs.IHT_OE_COL: (p.B, 0), inputs.IHT_OE_K: (p.A, 1)}.get(g.strategy, (p.A, 0))
+    dim = scored.outer if axis == 0 else scored.K
+    idx = torch.zeros(max(g.k, 1), dtype=torch.int32, device="cuda")
+    mask = torch.empty(max(dim, 8), dtype=torch.uint8, device="cuda")
+    scores = torch.empty(max(dim, 8), dtype=torch.float32, device="cuda")
+    ac = torch.empty((p.M, p.K // 2), dtype=torch.uint8, device="cuda")
+    asc = torch.empty((p.M, p.K // 32), dtype=torch.uint8, device="cuda")
+    bc = torch.empty((p.N, p.K // 2), dtype=torch.uint8, device="cuda")
+    bsc = torch.empty((p.N, p.K // 32), dtype=torch.uint8, device="cuda")
+    gws = torch.empty(ah.adahop_gemm_mx_workspace_bytes(p.M, p.N, p.K), dtype=torch.uint8, device="cuda")
+    import ctypes as C
+    L, st = ah.lib(), ah._stream(None)
+
+    def foid():
+        if oe:
+            rc = L.adahop_foid_topk(C.byref(scored.c()), axis, g.k, idx.data_ptr(), mask.data_ptr(), scores.data_ptr(), st)
+            assert rc == 0
+
+    stages = [
+        ("foid_topk", foid),
+        ("quantize_a", lambda: ah.adahop_pack_operand(p.A, 0, g.strategy, g.iht_block, g.k if oe else 0, idx, ac, asc)),
+        ("quantize_b", lambda: ah.adahop_pack_operand(p.B, 1, g.strategy, g.iht_block, g.k if oe else 0, idx, bc, bsc)),
+        ("product_with_outlier_part", lambda: ah.adahop_gemm(p.A, p.B, g.strategy, g.iht_block, g.k, idx=idx if oe else None,
+                                                             Cout=p.C, workspace=ws, a_packed=(ac, asc), b_packed=(bc, bsc))),
+        ("mxfp4_kernel_alone", lambda: ah.adahop_gemm_mx(ac, asc, bc, bsc, p.C, gws)),
+    ]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(iters)]
+    for fn in [f for _, f in stages]:
+        fn()
+    torch.cuda.synchronize()
+    for it in range(iters):
+        ev[it][0].record()
+        for si, (_, fn) in enumerate(stages):
+            fn()
+            ev[it][si + 1].record()
+    torch.cuda.synchronize()
+    out = {name: sum(ev[it][si].elapsed_time(ev[it][si + 1]) for it in range(iters)) / iters
+           for si, (name, _) in enumerate(stages)}
+    out["outlier_part_ms"] = out["product_with_outlier_part"] - out["mxfp4_kernel_alone"]
+    return {"name": g.name, "strategy": inputs.STRATEGY_NAMES[g.strategy], "k": g.k, "ms": out}
+
+
+def workload_summary(ah, torch, inputs, name, k_pct=1.0):
+    """One line for another workload: step time of the whole path, the same with pure IHT, hipBLASLt BF16."""
+    desc, gemms = build_workload(name, k_pct)
+    cache, pool = {}, {}
+    prepared = [Prepared(ah, torch, g, cache) for g in gemms]
+    for p in prepared:
+        p.workspace(ah, torch, pool)
+    ws = pool["ws"]
+    flops = sum(p.flops for p in prepared)
+
+    def step():
+        for p in prepared:
+            run_gemm(ah, p, ws)
+
+    def step_iht():
+        for p in prepared:
+            run_gemm(ah, p, ws, strategy=inputs.IHT if p.g.strategy != inputs.NONE else inputs.NONE, k=0)
+
+    def step_bf16():
+        for p in prepared:
+            am, bm = bf16_views(torch, p)
+            torch.matmul(am, bm)
+
+    t, t_iht, t_bf = time_ms(torch, step, 5, 2), time_ms(torch, step_iht, 5, 2), time_ms(torch, step_bf16, 3, 1)
+    worst = None
+    oe = [p for p in prepared if p.g.k > 0]
+    if oe and len(prepared) > 1:
+        per = []
+        for p in oe:
+            a = time_ms(torch, lambda: run_gemm(ah, p, ws), 5)
+            b = time_ms(torch, lambda: run_gemm(ah, p, ws, strategy=inputs.IHT, k=0), 5)
+            per.append((100.0 * (a - b) / b, p.g.name))
+        worst = {"pct": max(per)[0], "gemm": max(per)[1], "mean_pct": sum(x for x, _ in per) / len(per)}
+    out = {"workload": desc, "gemms": len(prepared), "step_ms": t, "tflops": flops / t / 1e9,
+           "pct_mxfp4_peak": 100.0 * flops / t / 1e9 / MXFP4_PEAK_TFLOPS, "step_ms_iht_only": t_iht,
+           "tflops_iht_only": flops / t_iht / 1e9, "step_ms_bf16_hipblaslt": t_bf, "speedup_vs_bf16": t_bf / t}
+    if worst:
+        out["oe_overhead_pct_worst"] = worst
+    elif oe:
+        out["oe_overhead_pct"] = 100.0 * (t - t_iht) / t_iht
+    del prepared, cache, pool, ws
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(workload_gemms):
     """The oracle, as it stands, on a bounded slab of the first GEMM of the workload."""
     from oracle import reference as orc
@@ -178,10 +279,27 @@ def main():
     gemm_ws = torch.empty(ah.adahop_gemm_mx_workspace_bytes(big.M, big.N, big.K), dtype=torch.uint8, device="cuda")
     gemm_ms = time_ms(torch, lambda: ah.adahop_gemm_mx(ac, asc, bc, bsc, big.C, gemm_ws), max(5, args.steps))
     achieved = big.flops / (gemm_ms * 1e-3) / 1e12
+    # The same launch as it runs inside a step: right after the two quantisers that produce its operands (which
+    # leave the packed operands, not C, in the caches, and the chip in the state a bandwidth-bound kernel leaves it).
+    iters = max(5, args.steps)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for it in range(iters + 1):
+        ah.adahop_iht_quantize(big.A, big.g.iht_block, None, None, ac, asc)
+        ah.adahop_iht_quantize(big.B, big.g.iht_block, None, None, bc, bsc)
+        if it:
+            ev[it - 1][0].record()
+        ah.adahop_gemm_mx(ac, asc, bc, bsc, big.C, gemm_ws)
+        if it:
+            ev[it - 1][1].record()
+    torch.cuda.synchronize()
+    in_step_ms = sum(a.elapsed_time(b) for a, b in ev) / iters
+    in_step = big.flops / (in_step_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "mxfp4 gemm", "achieved": achieved, "peak": MXFP4_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MXFP4_PEAK_TFLOPS,
                 "traffic": GEMM_HBM_TRAFFIC_BYTES.get((big.M, big.N, big.K)),
-                "shape": [big.M, big.N, big.K], "ms": gemm_ms}
+                "traffic_source": GEMM_HBM_TRAFFIC_SOURCE,
+                "shape": [big.M, big.N, big.K], "ms": gemm_ms, "timing": "back to back, operands warm",
+                "in_step_ms": in_step_ms, "in_step_achieved": in_step, "in_step_frac": in_step / MXFP4_PEAK_TFLOPS}
 
     out = {"metric": "effective TFLOP/s of IHT+MXFP4(+OE) GEMM vs BF16 GEMM; % MXFP4 MFMA peak",
            "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -198,10 +316,7 @@ def main():
         for p in prepared:
             t_cfg = time_ms(torch, lambda: run_gemm(ah, p, ws), 5)
             t_iht = time_ms(torch, lambda: run_gemm(ah, p, ws, strategy=inputs.IHT, k=0), 5)
-            a16 = p.A.tensor.view(torch.bfloat16)
-            b16 = p.B.tensor.view(torch.bfloat16)
-            am = a16 if p.A.k_contig else a16.t()
-            bm = b16.t() if p.B.k_contig else b16
+            am, bm = bf16_views(torch, p)
             t_bf16 = time_ms(torch, lambda: torch.matmul(am, bm), 5)
             # the same with an fp32 result, as this path delivers it (torch exposes no bf16-in / fp32-out GEMM:
             # the conversion is a second pass over C)
@@ -290,7 +405,37 @@ def main():
                                   "GBps": 2.53125 * qx.outer * qx.K / (q_ms * 1e-3) / 1e9, "peak_GBps": 8000.0}
         q_sr = time_ms(torch, lambda: ah.adahop_iht_quantize(qx, big.g.iht_block, None, None, codes, scales, sr_seed=1), 10)
         extras["iht_quantize_stochastic_rounding"] = {"ms": q_sr, "GBps": 2.53125 * qx.outer * qx.K / (q_sr * 1e-3) / 1e9}
+        # the same operand read K-strided (as the weight-gradient and dgrad products see their operands)
+        qs = ah.Operand(qx.tensor, not qx.k_contig)
+        cs = torch.empty((qs.outer, qs.K // 2), dtype=torch.uint8, device="cuda")
+        ss = torch.empty((qs.outer, qs.K // 32), dtype=torch.uint8, device="cuda")
+        qs_ms = time_ms(torch, lambda: ah.adahop_iht_quantize(qs, big.g.iht_block, None, None, cs, ss), 10)
+        extras["iht_quantize_k_strided"] = {"outer": qs.outer, "K": qs.K, "k_contig": qs.k_contig, "ms": qs_ms,
+                                            "GBps": 2.53125 * qs.outer * qs.K / (qs_ms * 1e-3) / 1e9, "peak_GBps": 8000.0}
+        del codes, scales, cs, ss
+        if args.workload.startswith("cfg4"):
+            # extraction-count sweep of configs[4]: K-channels on the up-projection forward, rows on its dgrad
+            sweep = []
+            for p in prepared[:2]:
+                dim = p.K if p.g.strategy == inputs.IHT_OE_K else p.M
+                t0 = time_ms(torch, lambda: run_gemm(ah, p, ws, strategy=inputs.IHT, k=0), 5)
+                for pc in (0.0, 0.25, 1.0, 2.0):
+                    k = inputs.pct(pc, dim)
+                    if k > p.idx.numel():
+                        p.idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+                    need = ah.adahop_gemm_workspace_bytes(p.M, p.N, p.K, p.g.strategy, k)
+                    if ws.numel() < need:
+                        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+                    t = time_ms(torch, lambda: run_gemm(ah, p, ws, k=k), 5)
+                    sweep.append({"name": p.g.name, "strategy": inputs.STRATEGY_NAMES[p.g.strategy], "k_pct": pc, "k": k,
+                                  "ms": t, "ms_iht_only": t0, "oe_overhead_pct": 100.0 * (t - t0) / t0})
+            extras["cfg4_k_sweep"] = sweep
+            extras["per_stage_ms"] = [stage_times(ah, torch, inputs, p, ws) for p in prepared[:2]]
         out["extras"] = extras
+        if args.workload == "cfg4" and not args.no_other_workloads:
+            del prepared, cache, pool, ws, big, ac, asc, bc, bsc, gemm_ws
+            torch.cuda.empty_cache()
+            extras["other_workloads"] = {n: workload_summary(ah, torch, inputs, n) for n in ("cfg1", "cfg3", "paper-table3")}
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)

@@ -93,6 +93,22 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 #if defined(__HIPCC__)
+// Loads of operand data that a kernel reads exactly once.  They are marked non-temporal (streaming) so that they
+// do not displace what the caches hold for the kernels that follow -- above all the packed codes the quantisers
+// write, which the product reads next: the product's own prefetch depth (two LDS stages) covers the latency of the
+// memory-side cache, not that of HBM under its C-write load.
+__device__ __forceinline__ uint4 load_once16(const void *p)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t load_once4(const void *p)
+{
+    return __builtin_nontemporal_load(static_cast<const uint32_t *>(p));
+}
+__device__ __forceinline__ uint16_t load_once2(const uint16_t *p) { return __builtin_nontemporal_load(p); }
+
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
 __device__ __forceinline__ float bf16_one(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }

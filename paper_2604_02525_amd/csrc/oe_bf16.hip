@@ -49,12 +49,12 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint16_t *__restrict_
         if (g >= rows_alloc * per_row) return;
         const int64_t t = g / per_row, c = g - t * per_row;
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (t < k) v = *reinterpret_cast<const uint4 *>(x + (int64_t)idx[t] * ld + c * 8);
+        if (t < k) v = load_once16(x + (int64_t)idx[t] * ld + c * 8);
         *reinterpret_cast<uint4 *>(out + t * K + c * 8) = v;
     } else {        // one thread = one element; neighbouring threads write neighbouring K
         if (g >= rows_alloc * K) return;
         const int64_t t = g / K, kk = g - t * K;
-        out[g] = t < k ? x[kk * ld + idx[t]] : (uint16_t)0;
+        out[g] = t < k ? load_once2(x + kk * ld + idx[t]) : (uint16_t)0;
     }
 }
 
@@ -88,10 +88,10 @@ __global__ __launch_bounds__(256, 2) void k_oe_skinny(const uint16_t *__restrict
         for (int i = 0; i < 4; ++i) {
             if constexpr (LONG_KC) {
                 const int64_t kk = kk0 + c8 * 8, l = l0 + r32 + 32 * i;
-                pl[i] = (kk < K && l < Lo) ? *reinterpret_cast<const uint4 *>(L + l * ldl + kk) : make_uint4(0, 0, 0, 0);
+                pl[i] = (kk < K && l < Lo) ? load_once16(L + l * ldl + kk) : make_uint4(0, 0, 0, 0);
             } else {
                 const int64_t kk = kk0 + 16 * i + lane16, l = l0 + 32 * w + 8 * grp;
-                pl[i] = (kk < K && l < Lo) ? *reinterpret_cast<const uint4 *>(L + kk * ldl + l) : make_uint4(0, 0, 0, 0);
+                pl[i] = (kk < K && l < Lo) ? load_once16(L + kk * ldl + l) : make_uint4(0, 0, 0, 0);
             }
         }
     };
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void k_gather_k(const uint16_t *__restrict__ x
     uint16_t v = 0;
     if (t < k) {
         const int64_t kk = idx[t];
-        v = k_contig ? x[o * ld + kk] : x[kk * ld + o];
+        v = load_once2(k_contig ? x + o * ld + kk : x + kk * ld + o);
     }
     out[o * kpad + t] = v;
 }
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(256) void k_gather_k_strided(const uint16_t *__rest
     for (int r = 0; r < 16; ++r) {
         const int t = t0 + ty * 16 + r;
         const int64_t o = o0 + tx;
-        tile[ty * 16 + r][tx] = (t < k && o < outer) ? x[(int64_t)idx[t] * ld + o] : (uint16_t)0;
+        tile[ty * 16 + r][tx] = (t < k && o < outer) ? load_once2(x + (int64_t)idx[t] * ld + o) : (uint16_t)0;
     }
     __syncthreads();
 #pragma unroll 4

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void k_oht_quant(const uint16_t *__restrict__ 
             const int r = idx / (OHT_TK / 8), c8 = idx % (OHT_TK / 8);
             const int64_t kk = k0 + c8 * 8;
             if (kk < K) { // K % 32 == 0: a chunk of 8 is inside or outside as a whole
-                const uint4 q = *reinterpret_cast<const uint4 *>(x + (o0 + r) * ld + kk);
+                const uint4 q = load_once16(x + (o0 + r) * ld + kk);
                 float *t = tile + r * OHT_KP + c8 * 8;
                 t[0] = bf16_lo(q.x), t[1] = bf16_hi(q.x), t[2] = bf16_lo(q.y), t[3] = bf16_hi(q.y);
                 t[4] = bf16_lo(q.z), t[5] = bf16_hi(q.z), t[6] = bf16_lo(q.w), t[7] = bf16_hi(q.w);
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void k_oht_quant(const uint16_t *__restrict__ 
             const int c = idx / (B / 8), r8 = idx % (B / 8);
             const int64_t kk = k0 + c;
             if (kk < K) {
-                const uint4 q = *reinterpret_cast<const uint4 *>(x + kk * ld + o0 + r8 * 8);
+                const uint4 q = load_once16(x + kk * ld + o0 + r8 * 8);
                 float *t = tile + (r8 * 8) * OHT_KP + c;
                 t[0 * OHT_KP] = bf16_lo(q.x), t[1 * OHT_KP] = bf16_hi(q.x), t[2 * OHT_KP] = bf16_lo(q.y);
                 t[3 * OHT_KP] = bf16_hi(q.y), t[4 * OHT_KP] = bf16_lo(q.z), t[5 * OHT_KP] = bf16_hi(q.z);

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void k_pattern_partial(const uint16_t *__restr
         if (r < R && cok) {
             float e[8];
             if (c0 + 8 <= C) {
-                const uint4 u = *reinterpret_cast<const uint4 *>(S + r * ld + c0);
+                const uint4 u = load_once16(S + r * ld + c0);
                 e[0] = bf16_lo(u.x); e[1] = bf16_hi(u.x); e[2] = bf16_lo(u.y); e[3] = bf16_hi(u.y);
                 e[4] = bf16_lo(u.z); e[5] = bf16_hi(u.z); e[6] = bf16_lo(u.w); e[7] = bf16_hi(u.w);
             } else {

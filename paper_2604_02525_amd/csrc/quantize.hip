@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void k_quant_kc(const uint16_t *__restrict__ x
 
     uint4 raw = make_uint4(0, 0, 0, 0);
     if (active) {
-        raw = *reinterpret_cast<const uint4 *>(x + row * ld + kk);
+        raw = load_once16(x + row * ld + kk);
         if (zero_outer && zero_outer[row]) raw = make_uint4(0, 0, 0, 0);
     }
     float v[8] = {bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y),
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(ks_cfg<B>::NW * 64) void k_quant_ks(const uint16_t 
             uint32_t pair = 0;
             if (valid) {
                 const int64_t kk = blk * 32 + i;
-                pair = *reinterpret_cast<const uint32_t *>(x + kk * ld + o);
+                pair = load_once4(x + kk * ld + o);
                 if (zero_k && zero_k[kk]) pair = 0;
             }
             v[i].x = z0 ? 0.0f : bf16_lo(pair);
@@ -546,8 +546,8 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
     uint4 r0 = make_uint4(0, 0, 0, 0), r1 = make_uint4(0, 0, 0, 0);
     if (active && !(zero_outer && zero_outer[row])) {
         const uint16_t *src = x + row * ld + kk;
-        r0 = *reinterpret_cast<const uint4 *>(src);
-        r1 = *reinterpret_cast<const uint4 *>(src + 128);
+        r0 = load_once16(src);
+        r1 = load_once16(src + 128);
     }
     float w0[8] = {bf16_lo(r0.x), bf16_hi(r0.x), bf16_lo(r0.y), bf16_hi(r0.y),
                    bf16_lo(r0.z), bf16_hi(r0.z), bf16_lo(r0.w), bf16_hi(r0.w)};
@@ -587,7 +587,7 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
         uint4 v[8];
 #pragma unroll
         for (int it = 0; it < 8; ++it)
-            v[it] = ok ? *reinterpret_cast<const uint4 *>(x + (k0 + it * 32 + r0) * ld + o0 + cg * 8) : make_uint4(0, 0, 0, 0);
+            v[it] = ok ? load_once16(x + (k0 + it * 32 + r0) * ld + o0 + cg * 8) : make_uint4(0, 0, 0, 0);
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             uint32_t *dst = reinterpret_cast<uint32_t *>(tile + (it * 32 + r0) * KS_PITCH + cg * 8);
