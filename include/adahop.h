@@ -318,6 +318,12 @@ int adahop_abi_version(void);
 int adahop_probe_mfma_rate(int random_operands, int idle_sleeps, int workgroups, int iters, float *sink,
                            void *stream);
 
+/* Measurement aid: which tiled kernel the MXFP4 product uses from now on (process-wide).  0 = chosen by shape (the
+ * default), 1 = always the 256 x 256 tile kernel, 2 = the 256 x 128 tile kernel with two accumulator sets wherever it
+ * can run (fp32 C, K % 256 == 0, K >= 2048, no K-channel extraction).  Results are the same up to fp32 summation
+ * order.  Returns ADAHOP_E_INVALID_ARG for any other value. */
+int adahop_debug_force_gemm_kernel(int which);
+
 #ifdef __cplusplus
 }
 #endif

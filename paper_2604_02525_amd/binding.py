@@ -22,7 +22,7 @@ EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "ada
            "adahop_oht_quantize", "adahop_oht_inverse", "adahop_iht_quantize_sr",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
            "adahop_oe_gemm_bf16", "adahop_detect_pattern_workspace_bytes", "adahop_detect_pattern",
-           "adahop_select_strategy", "adahop_vote_pattern", "adahop_probe_mfma_rate", "adahop_last_hip_error", "adahop_status_string",
+           "adahop_select_strategy", "adahop_vote_pattern", "adahop_probe_mfma_rate", "adahop_debug_force_gemm_kernel", "adahop_last_hip_error", "adahop_status_string",
            "adahop_abi_version"]
 
 
@@ -89,6 +89,7 @@ def lib():
         L.adahop_select_strategy.argtypes = [I, I, I, C.POINTER(C.c_int)]
         L.adahop_vote_pattern.argtypes = [C.POINTER(C.c_int32), I]
         L.adahop_probe_mfma_rate.argtypes = [I, I, I, I, P, P]
+        L.adahop_debug_force_gemm_kernel.argtypes = [I]
         L.adahop_status_string.restype = C.c_char_p
         L.adahop_status_string.argtypes = [I]
         for name in EXPORTS:
@@ -324,6 +325,11 @@ def adahop_probe_mfma_rate(random_operands, workgroups, iters, sink, stream=None
                                         _stream(stream)),
            "adahop_probe_mfma_rate")
     return 2.0 * 65536 * 16 * iters * 4 * workgroups
+
+
+def adahop_debug_force_gemm_kernel(which):
+    """Measurement aid: 0 = kernel chosen by shape, 1 = 256 x 256 tiles, 2 = 256 x 128 tiles with two accumulator sets."""
+    _check(lib().adahop_debug_force_gemm_kernel(int(which)), "adahop_debug_force_gemm_kernel")
 
 
 def adahop_detect_pattern(x, tau=2.0, workspace=None, stream=None):

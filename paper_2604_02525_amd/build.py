@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadahop.so")
-SOURCES = ["api.hip", "quantize.hip", "foid.hip", "gemm_mx.hip", "oe_bf16.hip", "pattern.hip", "oht.hip", "probe.hip"]
+SOURCES = ["api.hip", "quantize.hip", "foid.hip", "gemm_mx.hip", "gemm_mx_dual.hip", "oe_bf16.hip", "pattern.hip", "oht.hip", "probe.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
 

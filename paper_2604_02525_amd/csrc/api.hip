@@ -53,6 +53,13 @@ extern "C" {
 
 int adahop_abi_version(void) { return 1; }
 
+int adahop_debug_force_gemm_kernel(int which)
+{
+    if (which < 0 || which > 2) return ADAHOP_E_INVALID_ARG;
+    gemm_mx_force_kernel(which);
+    return ADAHOP_OK;
+}
+
 int adahop_last_hip_error(void) { return g_last_hip_error; }
 
 const char *adahop_status_string(int status)

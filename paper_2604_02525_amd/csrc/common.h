@@ -57,6 +57,12 @@ size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
 void gemm_mx_tiled_part(int64_t M, int64_t N, int64_t K, int kpad, const uint8_t *a_scales, const uint8_t *b_scales,
                         const void *C, int64_t ldc, int c_bf16, int64_t *Mi, int64_t *Ni);
 uint8_t *gemm_mx_scales_sm(void *workspace, int64_t M, int64_t K, int which);
+// The 256 x 128 kernel with two accumulator sets (gemm_mx_dual.hip): fp32 C, no gathered K-channels, K >= 2048.
+bool gemm_mx_dual_eligible(int64_t M, int64_t N, int64_t K);
+int launch_gemm_mx_dual(int64_t Mi, int64_t Ni, int64_t K, const uint8_t *a_codes, const uint8_t *a_sm,
+                        const uint8_t *b_codes, const uint8_t *b_sm, float *C, int64_t ldc, hipStream_t st);
+// Diagnostics: 0 = choose by shape, 1 = always the 256 x 256 kernel, 2 = the 256 x 128 kernel wherever it can run.
+void gemm_mx_force_kernel(int which);
 int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kpad, uint16_t *out, hipStream_t st);
 // C is float[M, ldc], or bf16[M, ldc] when c_bf16 is set (here and in launch_oe_rowcol).
 // Row / column outlier product; workspace of oe_rowcol_workspace_bytes() bytes, 256-byte aligned.

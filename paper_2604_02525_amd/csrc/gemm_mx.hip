@@ -13,28 +13,15 @@
 // v_mfma_f32_32x32x16_bf16 uses the same accumulator layout; lane l supplies K-elements
 // 8*(l/32) .. +7 of row / column l % 32.
 #include "common.h"
+#include "gemm_mx_common.h"
+
+#include <cmath>
 
 #include <type_traits>
 
 namespace adahop {
 
 namespace {
-
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ v16f mfma_fp4(uint4 a, uint4 b, v16f c, int sa, int sb)
-{
-    v8i av = {(int)a.x, (int)a.y, (int)a.z, (int)a.w, 0, 0, 0, 0};
-    v8i bv = {(int)b.x, (int)b.y, (int)b.z, (int)b.w, 0, 0, 0, 0};
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, c, 4, 4, 0, sa, 0, sb);
-}
-
-__device__ __forceinline__ v16f mfma_bf16(uint4 a, uint4 b, v16f c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
-}
 
 // fp32 -> bf16 bits, round to nearest even (finite values and infinities).
 __device__ __forceinline__ uint32_t bf16_bits(float x)
@@ -178,37 +165,6 @@ __global__ __launch_bounds__(256) void k_stage_major_scales(const uint64_t *__re
     out[g] = in[r * KB8 + s];
 }
 
-// Copies from global memory straight into LDS: lane i's 16 bytes, read at base + voff, land at
-// lds_addr + 16 i (base and lds_addr wave-uniform, voff a 32-bit per-lane byte offset).  Inline
-// assembly on purpose: with the builtin the compiler's wait-count pass makes every later LDS read
-// wait for ALL outstanding copies (it cannot tell that they target the other stage), which
-// serialises the copies with the matrix-core work.  The kernel waits for the copies itself
-// (s_waitcnt vmcnt(0) before the stage barrier).  M0 is written here (and declared clobbered) and used
-// by nothing else in these kernels (no dynamic register indexing, no other DMA).
-__device__ __forceinline__ const uint8_t *uniform_ptr(const uint8_t *p)
-{
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
-}
-
-__device__ __forceinline__ void dma16(const uint8_t *base, uint32_t voff, uint32_t lds_addr)
-{
-    // Both are wave-uniform by construction; reading them through the first lane makes sure they sit
-    // in scalar registers, which the instruction requires, whatever the register allocator did.
-    base = uniform_ptr(base);
-    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(voff), "s"(base), "s"(lds_addr)
-                 : "memory", "m0");
-}
-
-__device__ __forceinline__ uint32_t lds_address(const void *p)
-{
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
-}
-
 struct frags_t {
     uint4 a[4], b[4];
 };
@@ -216,10 +172,6 @@ struct frags_t {
 struct scales_t {
     int a[4], b[4];
 };
-
-// Keeps the instruction scheduler from moving anything across this point (one wave per SIMD: the
-// order written here is what hides the LDS and copy-issue latency behind the matrix cores).
-#define ADAHOP_PIN() __builtin_amdgcn_sched_barrier(0)
 
 // Where the copies of one tile come from: wave-uniform bases of its stage 0 (see k_gemm_mx_tile256).
 struct copy_src_t {
@@ -649,15 +601,40 @@ size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
 // Which part of the product the tiled kernel takes: whole 256x256 tiles (rows [0, Mi), columns [0, Ni)), or
 // nothing.  At least three pipeline stages are needed (64 gathered channels or 256 K-elements each, two of
 // them FP4 stages); the bf16 epilogue stores 16 bytes per lane.
+static std::atomic<int> g_kernel_choice{0};
+
+void gemm_mx_force_kernel(int which) { g_kernel_choice.store(which); }
+
+// Which tiled kernel takes a product (fp32 C, no gathered K-channels; otherwise always the 256 x 256 kernel).  The
+// 256 x 128 kernel with two accumulator sets hides the C stores behind the next tile but moves 1.5 times the operand
+// bytes per flop from L2 into LDS and out of LDS; measured on MI355X it wins where the stores are a large part of a
+// tile's time -- K = 2048: 1.2x; K = 4096: 1.04 .. 1.13x up to about 90 M elements of C, 0.97x at 8192 x 12288 -- and
+// loses 4 .. 15 % from K = 8192 on, except where the 256 x 256 tiles fill the last round of the compute units badly
+// (14336 x 4096: 896 tiles on 256 units, 3.5 rounds; 1.1x with 7 rounds of the smaller tiles).
+static bool takes_dual_kernel(int64_t M, int64_t N, int64_t K, int kpad, int c_bf16)
+{
+    if (c_bf16 || kpad > 0 || !gemm_mx_dual_eligible(M, N, K)) return false;
+    const int forced = g_kernel_choice.load();
+    if (forced == 1) return false;
+    if (forced == 2) return true;
+    if (K <= 2048) return true;
+    if (K <= 4096) return M * N <= (int64_t)8192 * 11008;
+    const double units = 256.0, t256 = (double)(M / 256) * (double)(N / 256), t128 = (double)(M / 256) * (double)(N / 128);
+    if (t256 < 1.0) return true; // N in [128, 256): only the smaller tile exists
+    const double waste256 = std::ceil(t256 / units) * units / t256, waste128 = std::ceil(t128 / units) * units / t128;
+    return waste256 >= 1.10 && waste128 + 0.08 <= waste256;
+}
+
 void gemm_mx_tiled_part(int64_t M, int64_t N, int64_t K, int kpad, const uint8_t *a_scales, const uint8_t *b_scales,
                         const void *C, int64_t ldc, int c_bf16, int64_t *Mi, int64_t *Ni)
 {
     const bool fast_c = !c_bf16 || (aligned(C, 16) && ldc % 8 == 0);
     const bool fast_k = fast_c && K % 256 == 0 && K >= (kpad > 0 ? 512 : 768) && kpad % 64 == 0 &&
                         aligned(a_scales, 8) && aligned(b_scales, 8);
+    const int64_t tn = fast_k && takes_dual_kernel(M, N, K, kpad, c_bf16) ? 128 : TN;
     *Mi = fast_k ? M / TM * TM : 0;
-    *Ni = fast_k ? N / TN * TN : 0;
-    if (*Mi == 0 || *Ni == 0 || (*Mi / TM) * (*Ni / TN) >= (1 << 30)) *Mi = *Ni = 0;
+    *Ni = fast_k ? N / tn * tn : 0;
+    if (*Mi == 0 || *Ni == 0 || (*Mi / TM) * (*Ni / tn) >= (1 << 30)) *Mi = *Ni = 0;
 }
 
 uint8_t *gemm_mx_scales_sm(void *workspace, int64_t M, int64_t K, int which)
@@ -726,6 +703,12 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     // one workgroup per compute unit walks the tiles (each workgroup fills a compute unit's LDS and registers)
     const int ntiles = tiles_m * tiles_n;
     const dim3 grid((unsigned)(ntiles < ncu ? ntiles : ncu));
+    if constexpr (sizeof(OUT) == 4) {
+        if (takes_dual_kernel(M, N, K, kpad, 0)) {
+            rc = launch_gemm_mx_dual(Mi, Ni, K, a_codes, a_sm, b_codes, b_sm, reinterpret_cast<float *>(C), ldc, st);
+            goto edges;
+        }
+    }
     if (kpad > 0)
         hipLaunchKernelGGL((k_gemm_mx_tile256<true, OUT>), grid, dim3(256), KERNEL_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
                            b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
@@ -733,6 +716,7 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
         hipLaunchKernelGGL((k_gemm_mx_tile256<false, OUT>), grid, dim3(256), KERNEL_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
                            b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
     rc = check_launch();
+edges:
     if (rc != ADAHOP_OK) return rc;
     if (Mi < M) { // bottom strip: rows [Mi, M), all columns
         rc = generic(M - Mi, N, a_codes + Mi * (K / 2), a_scales + Mi * (K / 32), b_codes, b_scales, C + Mi * ldc,
