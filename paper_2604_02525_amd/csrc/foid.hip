@@ -184,11 +184,21 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__
     }
 }
 
-// The same selection for dim <= TOPK_REG_KEYS * 1024 with every key held in registers: wave w owns the
-// contiguous index range [w*per, (w+1)*per) throughout and lane l its keys w*per + 64 j + l, loaded once (the
-// general kernel reads all keys from memory in each of its six passes, one dependent load per iteration, which
-// is what its run time consists of at these sizes).
+// The same selection for dim <= TOPK_REG_KEYS * 1024 with every key held in registers: wave w owns the contiguous
+// index range [w*per, (w+1)*per) throughout and lane l its keys w*per + 64 j + l, loaded once.
+//
+// One workgroup is all the parallelism there is, so the cost is the number of instructions per key.  A radix pass over
+// all keys costs about 25 of them per key, and four are needed.  Instead:
+//   1. every thread takes the maximum of its keys; the k-th largest of these 1024 maxima, cut down to its upper 16
+//      bits (two radix passes over ONE value per thread), is a threshold T0 that at least k keys reach -- so the k
+//      largest keys, and every key tied with the k-th, are among the keys >= T0 -- and that few others reach
+//      (about 1.2 k of them for scores without structure);
+//   2. the keys >= T0 are collected in LDS (one pass over the registers: a compare per key) and the radix select
+//      runs over this short list (at most TOPK_CAND_PER_THREAD per thread);
+//   3. the ordered compaction walks all keys once, as in k_topk.
+// If k > 1024, or more than TOPK_CAND keys reach T0, the select runs over all register keys as before.
 constexpr int TOPK_REG_KEYS = 32;
+constexpr int TOPK_CAND_PER_THREAD = 4, TOPK_CAND = TOPK_CAND_PER_THREAD * TOPK_THREADS;
 
 // hist[bin] += 1 for every lane with valid set, hist being private to the wave: one combined add for the bin
 // of the first valid lane (the scores of ordinary rows share their high bytes, so that bin usually takes most of
@@ -204,62 +214,58 @@ __device__ __forceinline__ void wave_histogram_private(uint32_t *hist, bool vali
     if (valid && bin != b) atomicAdd(&hist[bin], 1u);
 }
 
-__global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restrict__ scores, int dim, int k,
-                                                           int32_t *__restrict__ idx, uint8_t *__restrict__ mask)
+struct topk_shared_t {
+    uint32_t hist[TOPK_WAVES + 1][256]; // one per wave, and their sum
+    uint32_t prefix, remaining, count;
+    uint32_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
+    uint32_t cand[TOPK_CAND];
+};
+
+// Radix select over NK keys per thread (valid[j] says which exist), digits of 8 bits from bit 24 down to bit
+// LAST_SHIFT: on return `prefix` holds the upper bits of the k-th largest key (k >= 1, at most the number of valid
+// keys) and `remaining` how many keys with exactly these upper bits are among the k largest.  All threads call it.
+template <int NK, int LAST_SHIFT>
+__device__ __forceinline__ void radix_select(topk_shared_t &sh, const uint32_t (&key)[NK], const bool (&valid)[NK], uint32_t k,
+                                             uint32_t &prefix, uint32_t &remaining)
 {
-    __shared__ uint32_t hist[TOPK_WAVES + 1][256]; // one per wave, and their sum
-    __shared__ uint32_t sh_prefix, sh_remaining;
-    __shared__ uint32_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const uint32_t *keys = reinterpret_cast<const uint32_t *>(scores);
-    const int per = ((dim + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64; // <= 64 * TOPK_REG_KEYS
-    const int lo = w * per, hi = min(dim, lo + per);
-
-    if (k <= 0) {
-        for (int i = tid; i < dim; i += TOPK_THREADS) mask[i] = 0;
-        return;
-    }
-    uint32_t key[TOPK_REG_KEYS];
+    uint32_t pmask = 0;
+    prefix = 0;
+    remaining = k;
+    uint32_t *total = sh.hist[TOPK_WAVES];
+    for (int shift = 24; shift >= LAST_SHIFT; shift -= 8) {
 #pragma unroll
-    for (int j = 0; j < TOPK_REG_KEYS; ++j) {
-        const int i = lo + 64 * j + lane;
-        key[j] = i < hi ? keys[i] : 0u;
-    }
-    const int nj = (per + 63) / 64; // the same for every wave
-
-    uint32_t prefix = 0, pmask = 0, remaining = (uint32_t)k;
-    uint32_t *total = hist[TOPK_WAVES];
-    for (int shift = 24; shift >= 0; shift -= 8) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) hist[w][lane + 64 * q] = 0;
+        for (int q = 0; q < 4; ++q) sh.hist[w][lane + 64 * q] = 0;
         // (each wave clears and fills its own histogram: no barrier needed in between)
 #pragma unroll
-        for (int j = 0; j < TOPK_REG_KEYS; ++j)
-            if (j < nj)
-                wave_histogram_private(hist[w], lo + 64 * j + lane < hi && (key[j] & pmask) == prefix,
-                                       (key[j] >> shift) & 255u);
+        for (int j = 0; j < NK; ++j) {
+            const bool in = valid[j] && (key[j] & pmask) == prefix;
+            if (__ballot(in)) wave_histogram_private(sh.hist[w], in, (key[j] >> shift) & 255u);
+        }
         __syncthreads();
         if (tid < 256) {
             uint32_t sum = 0;
 #pragma unroll
-            for (int v = 0; v < TOPK_WAVES; ++v) sum += hist[v][tid];
+            for (int v = 0; v < TOPK_WAVES; ++v) sum += sh.hist[v][tid];
             total[tid] = sum;
         }
         __syncthreads();
-        if (w == 0) { // the digit of the k-th largest key, as in k_topk
+        // The digit of the k-th largest key: the highest bin b with (keys in bins above b) + total[b] >= remaining.
+        // Wave 0 scans the 256 bins in parallel: lane l owns bins 255 - 4l .. 252 - 4l.
+        if (w == 0) {
             uint32_t c[4], mine = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 c[j] = total[255 - 4 * lane - j];
                 mine += c[j];
             }
-            uint32_t incl = mine;
+            uint32_t incl = mine; // inclusive scan over lanes = over descending bins
 #pragma unroll
             for (int d = 1; d < 64; d *= 2) {
                 const uint32_t up = __shfl_up(incl, d);
                 if (lane >= d) incl += up;
             }
-            uint32_t cum = incl - mine;
+            uint32_t cum = incl - mine; // keys in bins above this lane's
             int found = -1;
             uint32_t cum_at = 0;
 #pragma unroll
@@ -272,46 +278,129 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restri
             }
             const uint64_t hit = __ballot(found >= 0);
             if (hit && lane == __ffsll((long long)hit) - 1) {
-                sh_prefix = prefix | ((uint32_t)found << shift);
-                sh_remaining = remaining - cum_at;
+                sh.prefix = prefix | ((uint32_t)found << shift);
+                sh.remaining = remaining - cum_at;
             }
         }
         __syncthreads();
-        prefix = sh_prefix;
-        remaining = sh_remaining;
+        prefix = sh.prefix;
+        remaining = sh.remaining;
         pmask |= 255u << shift;
     }
-    const uint32_t T = prefix;
+}
 
+__global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restrict__ scores, int dim, int k,
+                                                           int32_t *__restrict__ idx, uint8_t *__restrict__ mask)
+{
+    __shared__ topk_shared_t sh;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint32_t *keys = reinterpret_cast<const uint32_t *>(scores);
+    const int per = ((dim + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64; // <= 64 * TOPK_REG_KEYS
+    const int lo = w * per, hi = min(dim, lo + per);
+
+    if (k <= 0) {
+        for (int i = tid; i < dim; i += TOPK_THREADS) mask[i] = 0;
+        return;
+    }
+    uint32_t key[TOPK_REG_KEYS];
+    bool in[TOPK_REG_KEYS];
+    uint32_t tmax = 0;
+    bool any = false;
+#pragma unroll
+    for (int j = 0; j < TOPK_REG_KEYS; ++j) {
+        const int i = lo + 64 * j + lane;
+        in[j] = i < hi; // false for every lane once 64 j >= per
+        key[j] = in[j] ? keys[i] : 0u;
+        tmax = max(tmax, key[j]);
+        any |= in[j];
+    }
+    if (tid == 0) sh.count = 0;
+
+    // 1. threshold from the thread maxima (dim <= TOPK_CAND: every key is a candidate anyway)
+    uint32_t T0 = 0;
+    bool short_list = dim <= TOPK_CAND;
+    if (!short_list && k <= TOPK_THREADS) {
+        const uint32_t m[1] = {tmax};
+        const bool mv[1] = {any};
+        // threads that own at least one key (a wave's range may hold fewer than 64): with fewer than k of them there
+        // is no k-th largest maximum and no threshold
+        uint32_t have = 0;
+        for (int v = 0; v < TOPK_WAVES; ++v) {
+            const int n = min(dim, (v + 1) * per) - v * per;
+            have += (uint32_t)max(0, min(n, 64));
+        }
+        if ((uint32_t)k <= have) {
+            uint32_t p, r;
+            radix_select<1, 16>(sh, m, mv, (uint32_t)k, p, r);
+            T0 = p; // upper 16 bits of the k-th largest maximum, lower bits 0
+            short_list = true;
+        }
+    }
+    __syncthreads(); // sh.count = 0 is visible; the histograms are free again
+
+    uint32_t T = 0, remaining = (uint32_t)k;
+    bool selected = false;
+    if (short_list) {
+        // 2. collect the keys >= T0, in any order
+#pragma unroll
+        for (int j = 0; j < TOPK_REG_KEYS; ++j) {
+            const bool c = in[j] && key[j] >= T0;
+            const uint64_t m = __ballot(c);
+            if (m) {
+                uint32_t base = 0;
+                const int leader = __ffsll((long long)m) - 1;
+                if (lane == leader) base = atomicAdd(&sh.count, (uint32_t)__popcll(m));
+                base = __builtin_amdgcn_readlane(base, leader);
+                const uint32_t pos = base + (uint32_t)__popcll(m & (((uint64_t)1 << lane) - 1));
+                if (c && pos < (uint32_t)TOPK_CAND) sh.cand[pos] = key[j];
+            }
+        }
+        __syncthreads();
+        const uint32_t count = sh.count;
+        if (count <= (uint32_t)TOPK_CAND) {
+            uint32_t ck[TOPK_CAND_PER_THREAD];
+            bool cv[TOPK_CAND_PER_THREAD];
+#pragma unroll
+            for (int q = 0; q < TOPK_CAND_PER_THREAD; ++q) {
+                const uint32_t i = (uint32_t)tid + (uint32_t)q * TOPK_THREADS;
+                cv[q] = i < count;
+                ck[q] = cv[q] ? sh.cand[i] : 0u;
+            }
+            radix_select<TOPK_CAND_PER_THREAD, 0>(sh, ck, cv, (uint32_t)k, T, remaining);
+            selected = true;
+        }
+    }
+    if (!selected) radix_select<TOPK_REG_KEYS, 0>(sh, key, in, (uint32_t)k, T, remaining); // the general way
+
+    // 3. ordered compaction, as in k_topk
     uint32_t gt = 0, eq = 0;
 #pragma unroll
     for (int j = 0; j < TOPK_REG_KEYS; ++j) {
-        const bool in = lo + 64 * j + lane < hi; // false for every lane once j >= nj
-        gt += (uint32_t)__popcll(__ballot(in && key[j] > T));
-        eq += (uint32_t)__popcll(__ballot(in && key[j] == T));
+        gt += (uint32_t)__popcll(__ballot(in[j] && key[j] > T));
+        eq += (uint32_t)__popcll(__ballot(in[j] && key[j] == T));
     }
     if (lane == 0) {
-        wave_gt[w] = gt;
-        wave_eq[w] = eq;
+        sh.wave_gt[w] = gt;
+        sh.wave_eq[w] = eq;
     }
     __syncthreads();
     uint32_t gt_before = 0, eq_before = 0;
     for (int v = 0; v < w; ++v) {
-        gt_before += wave_gt[v];
-        eq_before += wave_eq[v];
+        gt_before += sh.wave_gt[v];
+        eq_before += sh.wave_eq[v];
     }
     const uint64_t below = ((uint64_t)1 << lane) - 1;
 #pragma unroll
     for (int j = 0; j < TOPK_REG_KEYS; ++j) {
         const int i = lo + 64 * j + lane;
-        const bool in = i < hi;
-        const bool is_gt = in && key[j] > T, is_eq = in && key[j] == T;
+        const bool is_gt = in[j] && key[j] > T, is_eq = in[j] && key[j] == T;
         const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
+        if ((m_gt | m_eq) == 0 && !__ballot(in[j])) continue; // past the end of the wave's range
         const uint32_t my_gt = gt_before + (uint32_t)__popcll(m_gt & below);
         const uint32_t my_eq = eq_before + (uint32_t)__popcll(m_eq & below);
         const bool sel = is_gt || (is_eq && my_eq < remaining);
         if (sel) idx[my_gt + min(my_eq, remaining)] = i;
-        if (in) mask[i] = sel ? 1 : 0;
+        if (in[j]) mask[i] = sel ? 1 : 0;
         gt_before += (uint32_t)__popcll(m_gt);
         eq_before += (uint32_t)__popcll(m_eq);
     }

@@ -201,6 +201,43 @@ def test_foid_topk_bit_exact(ah, axis, k_contig):
             assert np.array_equal(host(mask), rmask)
 
 
+def test_topk_selection_paths_bit_exact(ah):
+    """The exact top-k on score vectors chosen to take each way through the selection kernel: a short candidate list
+    behind the threshold from the thread maxima; more candidates than the list holds (all scores equal, or equal in
+    their upper 16 bits); k above the number of threads; fewer key-owning threads than k; k = dim; dims just above
+    and below the list size.  Scores come from rows that are constant except for two entries, so that their fp32
+    variance scores can be steered: x = (a, -a, 0, ...) scores 2 a^2 exactly."""
+    rng = np.random.default_rng(77)
+    cases = []
+    for dim, ks, kind in ((28672, (287, 574, 1, 1024, 1025, 3000, 28672), "random"), (28672, (287, 5000), "equal"),
+                          (28672, (300,), "two-level"), (4097, (41, 4097), "random"), (4096, (41, 1500), "random"),
+                          (9000, (90, 1100), "few-big"), (32768, (328, 640), "random"), (1090, (1089, 1024, 70), "random")):
+        if kind == "random":
+            a = np.abs(rng.standard_normal(dim)).astype(np.float32) + 0.5
+        elif kind == "equal":
+            a = np.full(dim, 1.5, dtype=np.float32)
+        elif kind == "two-level":            # upper 16 bits of every score equal; they differ further down
+            a = (1.0 + rng.integers(0, 60, dim) * 2.0 ** -9).astype(np.float32)
+        else:                                # a handful of large scores among many equal small ones
+            a = np.full(dim, 0.25, dtype=np.float32)
+            a[rng.permutation(dim)[:50]] = rng.uniform(8.0, 16.0, 50).astype(np.float32)
+        cases.append((dim, ks, kind, a))
+    for dim, ks, kind, a in cases:
+        x = np.zeros((dim, 64), dtype=np.float32)
+        x[:, 0], x[:, 1] = a, -a
+        bits = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        op = ah.Operand.from_bits(bits, True)
+        ref_scores = orc.foid_scores(bits, True, 0)
+        for k in ks:
+            say("top-k paths", dict(dim=dim, k=k, kind=kind))
+            idx, mask, scores = ah.adahop_foid_topk(op, 0, k)
+            torch.cuda.synchronize()
+            assert np.array_equal(host(scores).view(np.uint32), ref_scores.view(np.uint32))
+            ridx, rmask = orc.topk(ref_scores, k)
+            assert np.array_equal(host(idx), ridx)
+            assert np.array_equal(host(mask), rmask)
+
+
 # ----------------------------------------------------------------------------- MXFP4 product
 
 @pytest.mark.parametrize("shape", [(32, 32, 64), (128, 128, 256), (200, 136, 96), (257, 129, 32), (64, 384, 1056),
