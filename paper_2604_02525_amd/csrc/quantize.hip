@@ -563,12 +563,61 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
     if (active) store_codes_scales(codes, scales, row, K, k0, plan.chunk, c0, c1, s0, s1, sm);
 }
 
-// K-strided operand (element (o, kk) at x[kk*ld + o]).  A workgroup takes a tile of 256 K-rows x 64
-// columns: coalesced 16-byte loads (8 columns of one K-row per lane) go to LDS as they are, then each
-// wave takes 4 columns at a time and every lane pulls its two 8-element groups out of LDS with
-// 2-byte reads -- the transposition -- and carries on exactly like the K-contiguous kernel.  The LDS
-// row pitch of 66 elements keeps those reads down to 2-way bank conflicts.
-constexpr int KS_COLS = 64, KS_PITCH = 66;
+// ------------------------------------------------------------------------------------------------
+// K-strided operand (element (o, kk) at x[kk*ld + o]), K % 256 == 0.  A workgroup takes a tile of 256 K-rows x 64
+// columns: coalesced 16-byte loads (8 columns of one K-row per lane) go to LDS as they are, and the LDS
+// transposing read of gfx950 (ds_read_b64_tr_b16) hands every lane 4 consecutive K-elements of one column per
+// instruction -- the transposition costs a quarter of an LDS instruction per element.
+//
+// The transposing read works on groups of 16 lanes: lane s supplies the address of 4 consecutive 16-bit elements
+// (a piece of one K-row), and lane n of the group receives, as element j, the element n % 4 of the piece that lane
+// 4 j + n / 4 supplied.  With lane s pointing at K-row 64 (s % 4) + 4 t + s / 4 of 4 neighbouring columns, lane n
+// receives K-rows 64 (n / 4) + 4 t .. + 3 of column n % 4: after 16 reads (t = 0 .. 15) a group of 16 lanes holds
+// 4 columns x 256 K, lane n the 64 consecutive K-elements [64 m, 64 m + 64), m = n / 4, of its column.
+//
+// Work split, then: strides 1 .. 32 of the transform are butterflies inside a lane's 64 registers, stride 64 pairs
+// the lanes m and m ^ 1, stride 128 m and m ^ 2 of a column.  A gfx9 DPP row offers lane ^ 8 (row_ror:8) and lane ^ 7
+// (row_half_mirror) but not lane ^ 4, so the K-rows with bit 6 set are stored in LDS with every aligned group of 4
+// columns reversed: lane n then holds column 3 - n % 4 when m is odd, and lane n ^ 7 is its stride-64 partner in
+// the same column.  The two MX blocks of a lane lie entirely in its registers (no cross-lane maximum).
+//
+// LDS layout: K-row kk at row index 4 (kk % 64) + kk / 64, 144 bytes per row (128 of data).  The 16 pieces of one
+// transposing read of a half wave (two groups: 16 bytes per row) then start 4 banks apart and cover the 64 banks
+// exactly once; the 16-byte writes of a 16-lane group go to two rows whose banks do not overlap either.
+// ------------------------------------------------------------------------------------------------
+constexpr int KS_COLS = 64, KT_PITCH = 144;
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+
+#define ADAHOP_FMAC_DPP16_AT(W, O, CTRL, T)                                                                    \
+    asm volatile("s_nop 1\n\t"                                                                                \
+                 "v_fmac_f32_dpp %0, %0, %16 " CTRL "\n\tv_fmac_f32_dpp %1, %1, %16 " CTRL "\n\t"             \
+                 "v_fmac_f32_dpp %2, %2, %16 " CTRL "\n\tv_fmac_f32_dpp %3, %3, %16 " CTRL "\n\t"             \
+                 "v_fmac_f32_dpp %4, %4, %16 " CTRL "\n\tv_fmac_f32_dpp %5, %5, %16 " CTRL "\n\t"             \
+                 "v_fmac_f32_dpp %6, %6, %16 " CTRL "\n\tv_fmac_f32_dpp %7, %7, %16 " CTRL "\n\t"             \
+                 "v_fmac_f32_dpp %8, %8, %16 " CTRL "\n\tv_fmac_f32_dpp %9, %9, %16 " CTRL "\n\t"             \
+                 "v_fmac_f32_dpp %10, %10, %16 " CTRL "\n\tv_fmac_f32_dpp %11, %11, %16 " CTRL "\n\t"         \
+                 "v_fmac_f32_dpp %12, %12, %16 " CTRL "\n\tv_fmac_f32_dpp %13, %13, %16 " CTRL "\n\t"         \
+                 "v_fmac_f32_dpp %14, %14, %16 " CTRL "\n\tv_fmac_f32_dpp %15, %15, %16 " CTRL "\n\t"         \
+                 "s_nop 1"                                                                                    \
+                 : "+v"(W[O + 0]), "+v"(W[O + 1]), "+v"(W[O + 2]), "+v"(W[O + 3]), "+v"(W[O + 4]), "+v"(W[O + 5]),    \
+                   "+v"(W[O + 6]), "+v"(W[O + 7]), "+v"(W[O + 8]), "+v"(W[O + 9]), "+v"(W[O + 10]), "+v"(W[O + 11]),  \
+                   "+v"(W[O + 12]), "+v"(W[O + 13]), "+v"(W[O + 14]), "+v"(W[O + 15])                             \
+                 : "v"(T))
+
+// w <- partner(w) * t + w on all 64 values of the lane; XOR7: the partner is lane ^ 7, else lane ^ 8.
+template <bool XOR7> __device__ __forceinline__ void cross_stage64(float (&w)[64], float t)
+{
+#pragma unroll
+    for (int o = 0; o < 64; o += 16) {
+        if constexpr (XOR7)
+            ADAHOP_FMAC_DPP16_AT(w, o, "row_half_mirror row_mask:0xf bank_mask:0xf", t);
+        else
+            ADAHOP_FMAC_DPP16_AT(w, o, "row_ror:8 row_mask:0xf bank_mask:0xf", t);
+    }
+}
+
+__device__ __forceinline__ uint32_t rot16(uint32_t v) { return __builtin_amdgcn_alignbit(v, v, 16); }
 
 template <int B, bool SR>
 __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__ x, int64_t outer, int64_t K,
@@ -577,54 +626,132 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
                                                     uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
                                                     sr_key_t key, scales_sm_t sm)
 {
-    __shared__ uint16_t tile[256 * KS_PITCH];
+    __shared__ __attribute__((aligned(16))) uint8_t tile[256 * KT_PITCH];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int64_t o0 = (int64_t)blockIdx.x * KS_COLS, k0 = (int64_t)blockIdx.y * 256;
 
+    // ---- global -> LDS: a pass is 32 K-rows x 64 columns; lane: 8 columns (cg) of one of the wave's 8 rows.  A group
+    // of 16 lanes takes two rows two apart (their banks do not overlap: consecutive K-rows are 16 banks apart).
     {
-        const int cg = tid & 7, r0 = tid >> 3; // 8 column groups x 32 rows per pass
-        const bool ok = o0 + cg * 8 < outer;
+        const int cg = lane & 7, q = lane >> 4;
+        const int rw = w * 8 + (q >> 1) * 4 + (q & 1) + 2 * ((lane >> 3) & 1);
+        const int64_t oc = o0 + cg * 8;
+        const bool ok = oc < outer;
+        uint32_t cm[4] = {~0u, ~0u, ~0u, ~0u}; // keeps the columns that are not masked out
+        if (zero_outer && ok) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                if (oc + c < outer && zero_outer[oc + c]) cm[c >> 1] &= (c & 1) ? 0x0000ffffu : 0xffff0000u;
+        }
         uint4 v[8];
 #pragma unroll
-        for (int it = 0; it < 8; ++it)
-            v[it] = ok ? load_once16(x + (k0 + it * 32 + r0) * ld + o0 + cg * 8) : make_uint4(0, 0, 0, 0);
+        for (int it = 0; it < 8; ++it) {
+            const int64_t kk = k0 + it * 32 + rw;
+            v[it] = ok ? load_once16(x + kk * ld + oc) : make_uint4(0, 0, 0, 0);
+            if (zero_k && zero_k[kk]) v[it] = make_uint4(0, 0, 0, 0);
+        }
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
-            uint32_t *dst = reinterpret_cast<uint32_t *>(tile + (it * 32 + r0) * KS_PITCH + cg * 8);
-            dst[0] = v[it].x;
-            dst[1] = v[it].y;
-            dst[2] = v[it].z;
-            dst[3] = v[it].w;
+            const int row = it * 32 + rw; // K-row within the tile; bit 6 = bit 1 of it
+            uint4 u = make_uint4(v[it].x & cm[0], v[it].y & cm[1], v[it].z & cm[2], v[it].w & cm[3]);
+            if (it & 2) u = make_uint4(rot16(u.y), rot16(u.x), rot16(u.w), rot16(u.z)); // groups of 4 columns reversed
+            *reinterpret_cast<uint4 *>(tile + (4 * (row & 63) + (row >> 6)) * KT_PITCH + cg * 16) = u;
         }
     }
     __syncthreads();
 
-    const lane_plan_t plan = make_plan<B>(lane);
-    const int kc = plan.chunk * 8;
-#pragma unroll 1
-    for (int it = 0; it < 4; ++it) {
-        const int col = w * 16 + it * 4 + (lane >> 4);
-        const int64_t o = o0 + col;
-        const bool active = o < outer;
-        const bool zrow = active && zero_outer && zero_outer[o];
-        float w0[8], w1[8];
+    // ---- LDS -> registers, transposed: wave w takes columns [16 w, 16 w + 16)
+    const int n = lane & 15, g = lane >> 4, m = n >> 2, e = n & 3;
+    float wv[64];
+    {
+        // as the supplier of addresses this lane is s = n: K-row 64 (s % 4) + 4 t + s / 4, i.e. row index 16 t + 4 (s / 4) + s % 4
+        const uint8_t *src = tile + (4 * (n >> 2) + (n & 3)) * KT_PITCH + 32 * w + 8 * g;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            w0[i] = bf16_one(tile[(kc + i) * KS_PITCH + col]);
-            w1[i] = bf16_one(tile[(kc + 128 + i) * KS_PITCH + col]);
-            if (zrow) {
-                w0[i] = 0.0f;
-                w1[i] = 0.0f;
+        for (int t = 0; t < 16; ++t) {
+            const v4s d = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) v4s *)(src + t * 16 * KT_PITCH));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wv[4 * t + j] = bf16_one((uint16_t)d[j]);
+        }
+    }
+    const int col = 16 * w + 4 * g + ((m & 1) ? 3 - e : e);
+    const int64_t o = o0 + col;
+    const bool active = o < outer;
+
+    // ---- transform
+    if constexpr (B > 0) {
+        constexpr int HMAX = B >= 64 ? 32 : 16;
+#pragma unroll
+        for (int h = 1; h <= HMAX; h *= 2)
+#pragma unroll
+            for (int i = 0; i < 64; i += 2 * h)
+#pragma unroll
+                for (int j = i; j < i + h; ++j) {
+                    const float a = wv[j], b = wv[j + h];
+                    wv[j] = a + b;
+                    wv[j + h] = a - b;
+                }
+        float sign = 1.0f;
+        if constexpr (B >= 128) { // stride 64: lanes m and m ^ 1 of the column (lane ^ 7)
+            const bool upper = (m & 1) != 0;
+            cross_stage64<true>(wv, upper ? -1.0f : 1.0f);
+            if (upper) sign = -sign;
+        }
+        if constexpr (B == 256) { // stride 128: lanes m and m ^ 2 (lane ^ 8)
+            const bool upper = (m & 2) != 0;
+            cross_stage64<false>(wv, upper ? -1.0f : 1.0f);
+            if (upper) sign = -sign;
+        }
+        // the sign left over from the stages goes into the normalisation; "+ 0" stores exact zeros unsigned
+        const float fin = sign * hadamard_norm<B>();
+#pragma unroll
+        for (int i = 0; i < 64; ++i) wv[i] = __builtin_fmaf(wv[i], fin, 0.0f);
+    }
+
+    // ---- the lane's two MX blocks
+    uint32_t c[8];
+    int sc[2];
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(wv[32 * blk + i]));
+        const int s = e8m0_of_amax(amax);
+        sc[blk] = s;
+        if constexpr (SR) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float t8[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) t8[i] = wv[32 * blk + 8 * q + i];
+                c[4 * blk + q] = pack8_sr(t8, s, key, o, k0 + 64 * m + 32 * blk + 8 * q);
+            }
+        } else {
+            const float X = __uint_as_float((uint32_t)s << 23);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t p = 0;
+                const float *v8 = wv + 32 * blk + 8 * q;
+                p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, v8[0], v8[1], X, 0);
+                p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, v8[2], v8[3], X, 1);
+                p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, v8[4], v8[5], X, 2);
+                p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, v8[6], v8[7], X, 3);
+                c[4 * blk + q] = p;
             }
         }
-        if (zero_k) {
-            apply_k_mask(w0, zero_k, k0 + kc);
-            apply_k_mask(w1, zero_k, k0 + kc + 128);
+    }
+    if (active) {
+        uint8_t *crow = codes + o * (K >> 1) + ((k0 + 64 * m) >> 1);
+        *reinterpret_cast<uint4 *>(crow) = make_uint4(c[0], c[1], c[2], c[3]);
+        *reinterpret_cast<uint4 *>(crow + 16) = make_uint4(c[4], c[5], c[6], c[7]);
+        uint8_t *srow = scales + o * (K >> 5) + ((k0 + 64 * m) >> 5); // (byte stores: the array has no alignment rule)
+        srow[0] = (uint8_t)sc[0];
+        srow[1] = (uint8_t)sc[1];
+        if (sm.out && o < sm.rows) {
+            uint8_t *q = sm.out + ((k0 >> 8) * sm.rows + o) * 8 + 2 * m;
+            q[0] = (uint8_t)sc[0];
+            q[1] = (uint8_t)sc[1];
         }
-        uint32_t c0, c1;
-        int s0, s1;
-        transform_quantize16<B, SR>(w0, w1, plan, c0, c1, s0, s1, key, o, k0 + kc, k0 + kc + 128);
-        if (active) store_codes_scales(codes, scales, o, K, k0, plan.chunk, c0, c1, s0, s1, sm);
     }
 }
 
