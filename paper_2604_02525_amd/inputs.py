@@ -172,3 +172,25 @@ def paper_latency_shapes(which=("mlp", "attn"), T=32768, iht_block=32, k=64):
         G = matrix(T, d_out, 1e-3, seed + 2, row_outliers=(pct(0.5, T), 100.0, 100.0))
         out.append(Gemm(f"table3.{name}.wgrad", Operand(G, False), Operand(X, False), IHT_OE_COL, iht_block, k))
     return out
+
+
+# ---- the paper's synthetic error studies (Sec. 3.2 / Fig. 2 left, App. D; App. G right) ----------------------------
+QUALITY_SEEDS = (42, 256, 1925, 2048, 7777)
+# The paper amplifies "random columns" by 25 (Column-wise) or 5 (Row-wise) and reports the resulting mean kurtosis,
+# 208.30 and 9.08, but not how many columns.  For a 4096-wide Gaussian tensor with n of its columns scaled by f the
+# kurtosis is 3 (1 + p (f^4 - 1)) / (1 + p (f^2 - 1))^2 with p = n / 4096: n = 45 gives 208.7 for f = 25 and n = 18
+# gives 9.1 for f = 5, so these counts reproduce the statistics the paper states.
+QUALITY_COUNT = {"C": 45, "R": 18}
+QUALITY_FACTOR = {"C": 25.0, "R": 5.0}
+
+
+def pattern_operand(kind, outer, K, seed, as_b):
+    """Logical [outer, K] bf16 bits of a tensor with the paper's pattern letter (App. D).
+    A (m x k, passed as [m, k]):  R = amplified rows,                 C = amplified columns = K-channels.
+    B (k x n, passed as [n, k]):  R = amplified rows  = K-channels,   C = amplified columns = outer rows.
+    Row-wise tensors are Column-wise tensors transposed (App. G): x5 on 18 lines; Column-wise: x25 on 45 lines."""
+    if kind == "N":
+        return matrix(outer, K, 1.0, seed)
+    spec = (QUALITY_COUNT[kind], QUALITY_FACTOR[kind], QUALITY_FACTOR[kind])
+    rows_amplified = (kind == "R") != as_b
+    return matrix(outer, K, 1.0, seed, row_outliers=spec) if rows_amplified else matrix(outer, K, 1.0, seed, col_outliers=spec)
