@@ -412,13 +412,29 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
     const int kpad_planned = oe && strategy == ADAHOP_IHT_OE_K ? kpad_of(k) : 0;
     int64_t Mi = 0, Ni = 0;
     gemm_mx_tiled_part(M, N, K, kpad_planned, a_scales, b_scales, C, ldc, c_bf16, &Mi, &Ni);
+    // K-channel extraction: a quantiser that runs here on a K-contiguous operand also copies the extracted channels
+    // out (it has the row in registers); the position of a channel in the index list comes from a 16-bit table that
+    // takes the place of the scores, which nobody reads after the selection.
+    // Only for indices selected here, which are distinct: a repeated index in a caller's list would leave a position
+    // of the copy unwritten, where the separate gather reads the channel twice.
+    const bool oe_k = oe && strategy == ADAHOP_IHT_OE_K, fuse = oe_k && !use_given_idx;
+    const bool a_gathers = fuse && !a_given && iht_quantize_gathers_k(*A, kpad_planned);
+    const bool b_gathers = fuse && !b_given && iht_quantize_gathers_k(*B, kpad_planned);
+    k_gather_t ga = {nullptr, nullptr, 0, 0}, gb = ga;
+    if (a_gathers || b_gathers) {
+        uint16_t *pos1 = reinterpret_cast<uint16_t *>(scores);
+        rc = launch_k_positions(idx_inout, k, mask, K, pos1, st);
+        if (rc != ADAHOP_OK) return rc;
+        if (a_gathers) ga = k_gather_t{pos1, reinterpret_cast<uint16_t *>(ws + L.gather_a), k, kpad_planned};
+        if (b_gathers) gb = k_gather_t{pos1, reinterpret_cast<uint16_t *>(ws + L.gather_b), k, kpad_planned};
+    }
     int sm_ready = 0;
     if (!a_given) {
         uint8_t *c = reinterpret_cast<uint8_t *>(ws + L.a_codes), *s = reinterpret_cast<uint8_t *>(ws + L.a_scales);
         const scales_sm_t sm = {Mi > 0 && !oht ? gemm_mx_scales_sm(ws + L.gemm, M, K, 0) : nullptr, Mi};
         rc = oht ? launch_oht_quantize(*A, b, c, s, st)
                  : launch_iht_quantize(*A, b, a_kind == 1 ? mask : nullptr, a_kind == 2 ? mask : nullptr, c, s, st,
-                                       opts && opts->sr_a ? &opts->sr_seed_a : nullptr, &sm);
+                                       opts && opts->sr_a ? &opts->sr_seed_a : nullptr, &sm, &ga);
         if (rc != ADAHOP_OK) return rc;
         if (sm.out && iht_quantize_writes_scales_sm(*A)) sm_ready |= 1;
     }
@@ -427,17 +443,17 @@ static int gemm_whole_path(const adahop_operand_t *A, const adahop_operand_t *B,
         const scales_sm_t sm = {Ni > 0 && !oht ? gemm_mx_scales_sm(ws + L.gemm, M, K, 1) : nullptr, Ni};
         rc = oht ? launch_oht_quantize(*B, b, c, s, st)
                  : launch_iht_quantize(*B, b, b_kind == 1 ? mask : nullptr, b_kind == 2 ? mask : nullptr, c, s, st,
-                                       opts && opts->sr_b ? &opts->sr_seed_b : nullptr, &sm);
+                                       opts && opts->sr_b ? &opts->sr_seed_b : nullptr, &sm, &gb);
         if (rc != ADAHOP_OK) return rc;
         if (sm.out && iht_quantize_writes_scales_sm(*B)) sm_ready |= 2;
     }
     // 3. MXFP4 product, with the K-channel BF16 product fused in front; 4. row / column BF16 product
-    if (oe && strategy == ADAHOP_IHT_OE_K) {
-        const int kpad = kpad_of(k);
+    if (oe_k) {
+        const int kpad = kpad_planned;
         uint16_t *Ag = reinterpret_cast<uint16_t *>(ws + L.gather_a), *Bg = reinterpret_cast<uint16_t *>(ws + L.gather_b);
-        rc = launch_gather_k(*A, idx_inout, k, kpad, Ag, st);
+        rc = a_gathers ? ADAHOP_OK : launch_gather_k(*A, idx_inout, k, kpad, Ag, st);
         if (rc != ADAHOP_OK) return rc;
-        rc = launch_gather_k(*B, idx_inout, k, kpad, Bg, st);
+        rc = b_gathers ? ADAHOP_OK : launch_gather_k(*B, idx_inout, k, kpad, Bg, st);
         if (rc != ADAHOP_OK) return rc;
         return launch_gemm_mx(M, N, K, a_codes, a_scales, b_codes, b_scales, C, ldc, c_bf16, Ag, Bg, kpad, ws + L.gemm, st,
                               sm_ready);

@@ -36,10 +36,24 @@ struct scales_sm_t {
 // Whether launch_iht_quantize honours a scales_sm_t for this operand (only its kernels for K % 256 == 0 write the
 // copy); a caller may tell the product that the copy is there only if this holds.
 bool iht_quantize_writes_scales_sm(const adahop_operand_t &x);
+// The extracted K-channels of an operand, copied out by the quantiser that reads the operand anyway (Eq. 7 with
+// S a set of K-channels): out[o, pos1[c] - 1] = x(o, c) for every channel c with pos1[c] != 0, out[o, k .. kpad) = 0.
+// out is [outer, kpad] bf16; pos1[c] = t + 1 for the channel c = idx[t], 0 for a channel that is not extracted.
+struct k_gather_t {
+    const uint16_t *pos1; // per K-channel, 16-byte aligned
+    uint16_t *out;        // nullptr: no copy
+    int k, kpad;
+};
+// Whether launch_iht_quantize honours a k_gather_t for this operand (K-contiguous, whole passes of a workgroup
+// along K, a copy that fits its LDS staging).
+bool iht_quantize_gathers_k(const adahop_operand_t &x, int kpad);
+// pos1[c] = t + 1 where c = idx[t], 0 where mask[c] == 0 (mask as launch_foid_topk / launch_mask_from_idx leave it).
+int launch_k_positions(const int32_t *idx, int k, const uint8_t *mask, int64_t K, uint16_t *pos1, hipStream_t st);
 // sr_seed: NULL = round to nearest even; else the elements are rounded stochastically under that seed.
 int launch_iht_quantize(const adahop_operand_t &x, int iht_block, const uint8_t *zero_outer,
                         const uint8_t *zero_k, uint8_t *codes, uint8_t *scales, hipStream_t st,
-                        const uint64_t *sr_seed = nullptr, const scales_sm_t *sm = nullptr);
+                        const uint64_t *sr_seed = nullptr, const scales_sm_t *sm = nullptr,
+                        const k_gather_t *gather = nullptr);
 int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, uint8_t *mask, float *scores,
                      hipStream_t st);
 // Device address, on the current device, of the library's built-in score scratch (ADAHOP_FOID_NOALLOC_MAX_DIM floats).

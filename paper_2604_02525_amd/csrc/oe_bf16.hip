@@ -269,6 +269,25 @@ __global__ __launch_bounds__(256) void k_gather_k_strided(const uint16_t *__rest
 
 } // namespace
 
+// The first K threads clear the entries of the channels that stay, the next k set those of the extracted ones:
+// no entry is written twice.
+__global__ __launch_bounds__(256) void k_positions(const int32_t *__restrict__ idx, int k, const uint8_t *__restrict__ mask,
+                                                   int64_t K, uint16_t *__restrict__ pos1)
+{
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g < K) {
+        if (!mask[g]) pos1[g] = 0;
+    } else if (g < K + k) {
+        pos1[idx[g - K]] = (uint16_t)(g - K + 1);
+    }
+}
+
+int launch_k_positions(const int32_t *idx, int k, const uint8_t *mask, int64_t K, uint16_t *pos1, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_positions, dim3((unsigned)ceil_div(K + k, 256)), dim3(256), 0, st, idx, k, mask, K, pos1);
+    return check_launch();
+}
+
 int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kpad, uint16_t *out, hipStream_t st)
 {
     const int64_t n = x.outer * kpad;

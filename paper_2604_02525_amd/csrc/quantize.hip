@@ -489,12 +489,31 @@ __device__ __forceinline__ void transform_quantize16(float (&w0)[8], float (&w1)
     codes1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes1, w1[6], w1[7], x1, 3);
 }
 
-__device__ __forceinline__ void apply_k_mask(float (&w)[8], const uint8_t *zero_k, int64_t kk)
+__device__ __forceinline__ void apply_k_mask(float (&w)[8], uint64_t zm)
 {
-    const uint64_t zm = *reinterpret_cast<const uint64_t *>(zero_k + kk);
 #pragma unroll
     for (int i = 0; i < 8; ++i)
         if ((zm >> (8 * i)) & 0xffu) w[i] = 0.0f;
+}
+
+// Of 8 consecutive K-elements (raw bf16 in r), the extracted ones go to their positions of the row's copy;
+// pos holds position + 1 per element as 16 bits, 0 for an element that stays.
+__device__ __forceinline__ void scatter_extracted(uint4 r, uint4 pos, uint16_t *dst)
+{
+    const uint32_t e[4] = {r.x, r.y, r.z, r.w}, q[4] = {pos.x, pos.y, pos.z, pos.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t p1 = (q[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+        if (p1) dst[p1 - 1] = (uint16_t)(e[i >> 1] >> (16 * (i & 1)));
+    }
+}
+
+__device__ __forceinline__ void zero_extracted(float (&w)[8], uint4 pos)
+{
+    const uint32_t q[4] = {pos.x, pos.y, pos.z, pos.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if ((q[i >> 1] >> (16 * (i & 1))) & 0xffffu) w[i] = 0.0f;
 }
 
 // k0: start of the lane group's 256 K-elements (a multiple of 256).  sm: optional second copy of the scales in
@@ -554,13 +573,70 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
     float w1[8] = {bf16_lo(r1.x), bf16_hi(r1.x), bf16_lo(r1.y), bf16_hi(r1.y),
                    bf16_lo(r1.z), bf16_hi(r1.z), bf16_lo(r1.w), bf16_hi(r1.w)};
     if (zero_k && active) {
-        apply_k_mask(w0, zero_k, kk);
-        apply_k_mask(w1, zero_k, kk + 128);
+        const uint64_t z0 = *reinterpret_cast<const uint64_t *>(zero_k + kk);
+        const uint64_t z1 = *reinterpret_cast<const uint64_t *>(zero_k + kk + 128);
+        apply_k_mask(w0, z0);
+        apply_k_mask(w1, z1);
     }
     uint32_t c0, c1;
     int s0, s1;
     transform_quantize16<B, SR>(w0, w1, plan, c0, c1, s0, s1, key, row, kk, kk + 128);
     if (active) store_codes_scales(codes, scales, row, K, k0, plan.chunk, c0, c1, s0, s1, sm);
+}
+
+// The same with the extracted K-channels copied out on the way (Eq. 7 with S a set of K-channels).  One workgroup
+// takes a whole row, 4096 K-elements per pass.  In place of the byte mask it reads a 16-bit table, position in the
+// index list + 1 for an extracted channel and 0 for the others, with the operand (one more coalesced load, no
+// dependent look-ups); the extracted elements it meets go to those positions of a copy of the row's extracted part
+// in LDS, which leaves for memory at the end in whole 16-byte pieces.
+// (Two variants were measured on 16384 x 28672 at 1 % and made the quantiser half again as slow, more than the
+// separate gather kernel costs: 2-byte stores straight into the copy, and a look-up of the position in a 32-bit
+// table under the branch that an extracted element takes -- a chain of dependent loads in nearly every wave.)
+constexpr int KC_GATHER_MAX_KPAD = 4096;
+
+template <int B, bool SR>
+__global__ __launch_bounds__(256) void k_quant_kc16_gather(const uint16_t *__restrict__ x, int64_t K, int64_t ld,
+                                                           uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
+                                                           sr_key_t key, scales_sm_t sm, k_gather_t gk)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t part[KC_GATHER_MAX_KPAD];
+    const uint32_t upr = (uint32_t)(K >> 8);
+    const int64_t row = blockIdx.x;
+    const lane_plan_t plan = make_plan<B>(threadIdx.x & 63);
+    for (int p = gk.k + threadIdx.x; p < gk.kpad; p += 256) part[p] = 0;
+    for (uint32_t u0 = 0; u0 < upr; u0 += 16) {
+        const uint32_t unit = u0 + (threadIdx.x >> 4);
+        const bool active = unit < upr;
+        const int64_t k0 = (int64_t)unit * 256, kk = k0 + plan.chunk * 8;
+        uint4 r0 = make_uint4(0, 0, 0, 0), r1 = r0, p0 = r0, p1 = r0;
+        if (active) {
+            const uint16_t *src = x + row * ld + kk;
+            r0 = load_once16(src);
+            r1 = load_once16(src + 128);
+            p0 = *reinterpret_cast<const uint4 *>(gk.pos1 + kk);
+            p1 = *reinterpret_cast<const uint4 *>(gk.pos1 + kk + 128);
+        }
+        float w0[8] = {bf16_lo(r0.x), bf16_hi(r0.x), bf16_lo(r0.y), bf16_hi(r0.y),
+                       bf16_lo(r0.z), bf16_hi(r0.z), bf16_lo(r0.w), bf16_hi(r0.w)};
+        float w1[8] = {bf16_lo(r1.x), bf16_hi(r1.x), bf16_lo(r1.y), bf16_hi(r1.y),
+                       bf16_lo(r1.z), bf16_hi(r1.z), bf16_lo(r1.w), bf16_hi(r1.w)};
+        if (p0.x | p0.y | p0.z | p0.w) {
+            zero_extracted(w0, p0);
+            scatter_extracted(r0, p0, part);
+        }
+        if (p1.x | p1.y | p1.z | p1.w) {
+            zero_extracted(w1, p1);
+            scatter_extracted(r1, p1, part);
+        }
+        uint32_t c0, c1;
+        int s0, s1;
+        transform_quantize16<B, SR>(w0, w1, plan, c0, c1, s0, s1, key, row, kk, kk + 128);
+        if (active) store_codes_scales(codes, scales, row, K, k0, plan.chunk, c0, c1, s0, s1, sm);
+    }
+    __syncthreads();
+    uint16_t *dst = gk.out + row * gk.kpad;
+    for (int p = threadIdx.x * 8; p < gk.kpad; p += 256 * 8)
+        *reinterpret_cast<uint4 *>(dst + p) = *reinterpret_cast<const uint4 *>(part + p);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -757,11 +833,16 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
 
 template <int B, bool SR>
 int launch_kc(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
-              sr_key_t key, scales_sm_t sm, hipStream_t st)
+              sr_key_t key, scales_sm_t sm, k_gather_t gk, hipStream_t st)
 {
     const uint16_t *d = static_cast<const uint16_t *>(x.data);
     if (x.K % 256 == 0) {
         const int64_t tpr = x.K / 16; // threads per row
+        if (gk.out) {
+            hipLaunchKernelGGL((k_quant_kc16_gather<B, SR>), dim3((unsigned)x.outer), dim3(256), 0, st, d, x.K, x.ld, codes,
+                               scales, key, sm, gk);
+            return check_launch();
+        }
         if (tpr >= 128) {
             dim3 grid((unsigned)x.outer, (unsigned)ceil_div(tpr, 256));
             hipLaunchKernelGGL((k_quant_kc16<B, 0, SR>), grid, dim3(256), 0, st, d, x.outer, x.K, x.ld, zo, zk, codes,
@@ -819,11 +900,11 @@ int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, u
 
 template <bool SR>
 int dispatch_block(const adahop_operand_t &x, int b, const uint8_t *zo, const uint8_t *zk, uint8_t *codes,
-                   uint8_t *scales, sr_key_t key, scales_sm_t sm, hipStream_t st)
+                   uint8_t *scales, sr_key_t key, scales_sm_t sm, k_gather_t gk, hipStream_t st)
 {
 #define ADAHOP_DISPATCH(BB)                                                                  \
     case BB:                                                                                 \
-        return x.k_contig ? launch_kc<BB, SR>(x, zo, zk, codes, scales, key, sm, st)         \
+        return x.k_contig ? launch_kc<BB, SR>(x, zo, zk, codes, scales, key, sm, gk, st)     \
                           : launch_ks<BB, SR>(x, zo, zk, codes, scales, key, sm, st);
     switch (b) {
         ADAHOP_DISPATCH(0)
@@ -846,16 +927,28 @@ bool iht_quantize_writes_scales_sm(const adahop_operand_t &x) { return x.K % 256
 // sr_seed: NULL for round-to-nearest-even, else the seed of the stochastic rounding of the elements.
 // sm: NULL, or where a stage-major copy of the scales goes; honoured by the kernels for K % 256 == 0 only,
 // which is also the only case in which the tiled GEMM kernel asks for it.
+// A whole row per workgroup pays from 4096 K-elements on (one pass of all its lanes); the copy is staged in LDS.
+bool iht_quantize_gathers_k(const adahop_operand_t &x, int kpad)
+{
+    return x.k_contig && x.K % 4096 == 0 && kpad <= KC_GATHER_MAX_KPAD && kpad % 8 == 0 && x.outer <= 0x7fffffff;
+}
+
+// gather: NULL, or where the extracted channels are copied to and the table that names them (it must describe the
+// same channels as zk); honoured only where iht_quantize_gathers_k holds and zk is given.
 int launch_iht_quantize(const adahop_operand_t &x, int b, const uint8_t *zo, const uint8_t *zk, uint8_t *codes,
-                        uint8_t *scales, hipStream_t st, const uint64_t *sr_seed, const scales_sm_t *sm)
+                        uint8_t *scales, hipStream_t st, const uint64_t *sr_seed, const scales_sm_t *sm,
+                        const k_gather_t *gather)
 {
     if (x.outer == 0 || x.K == 0) return ADAHOP_OK;
     const scales_sm_t smv = sm && iht_quantize_writes_scales_sm(x) ? *sm : scales_sm_t{nullptr, 0};
+    const k_gather_t gk = gather && gather->out && zk && !zo && iht_quantize_gathers_k(x, gather->kpad)
+                              ? *gather
+                              : k_gather_t{nullptr, nullptr, 0, 0};
     if (sr_seed) {
         const sr_key_t key = {(uint32_t)*sr_seed, (uint32_t)(*sr_seed >> 32)};
-        return dispatch_block<true>(x, b, zo, zk, codes, scales, key, smv, st);
+        return dispatch_block<true>(x, b, zo, zk, codes, scales, key, smv, gk, st);
     }
-    return dispatch_block<false>(x, b, zo, zk, codes, scales, sr_key_t{0, 0}, smv, st);
+    return dispatch_block<false>(x, b, zo, zk, codes, scales, sr_key_t{0, 0}, smv, gk, st);
 }
 
 } // namespace adahop

@@ -386,6 +386,29 @@ def test_more_tiles_than_compute_units(ah, strategy, k, M, N):
     run_whole(ah, g, rows=rows.astype(np.int32), cols=cols.astype(np.int32))
 
 
+@pytest.mark.parametrize("a_kc,b_kc", [(True, True), (True, False), (False, True)])
+@pytest.mark.parametrize("K,k", [(4096, 41), (8192, 5), (8192, 200)])
+def test_oe_k_channels_copied_by_the_quantiser(ah, a_kc, b_kc, K, k):
+    """K-contiguous operands whose K is a whole number of 4096-element passes: the quantiser that the whole path runs
+    also copies the extracted channels out, where otherwise a gather kernel does.  With the indices handed back in,
+    the path takes the gather kernels: both must give the same C bit for bit (same copy, same summation order), and
+    the oracle's on a sample of rows.  (Operands with one K-strided side mix the two routes in one product.)"""
+    M, N, b = 304, 264, 128
+    A_log = inputs.matrix(M, K, 1.0, 70 + k, col_outliers=(max(k // 2, 3), 40.0, 80.0))
+    B_log = inputs.matrix(N, K, 0.02, 71 + k)
+    A = inputs.Operand(A_log if a_kc else np.ascontiguousarray(A_log.T), a_kc)
+    B = inputs.Operand(B_log if b_kc else np.ascontiguousarray(B_log.T), b_kc)
+    g = inputs.Gemm("kcopy", A, B, inputs.IHT_OE_K, b, k)
+    say("K-channels copied by the quantiser", (M, N, K), k, a_kc, b_kc)
+    rows = np.arange(0, M, 7, dtype=np.int32)
+    run_whole(ah, g, rows=rows)
+    dA, dB = dev_op(ah, A), dev_op(ah, B)
+    first = ah.adahop_gemm(dA, dB, inputs.IHT_OE_K, b, k)
+    c_first, idx = host(first["C"]), first["idx"].clone()
+    second = ah.adahop_gemm(dA, dB, inputs.IHT_OE_K, b, k, idx=idx)
+    assert np.array_equal(c_first, host(second["C"]))
+
+
 def test_oe_k_zero_equals_iht(ah):
     g = inputs.config0()[0]
     A, B = dev_op(ah, g.A), dev_op(ah, g.B)
