@@ -25,19 +25,25 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 //
 //   1. k_gather_rows   copies the extracted rows into a K-contiguous staging matrix Sg, zero padded to
 //                      whole 32-row matrix-core tiles;
-//   2. k_oe_skinny     workgroup = (RT x 32 rows of Sg) x (128 rows of L) x (one slice of K); both
-//                      operands go through LDS in a K-contiguous [row][64 K] layout, so a K-strided L
-//                      is transposed on its way into LDS (16-bit scatter stores) while its global reads
-//                      stay 16 bytes per lane; the next stage is fetched into registers while the
-//                      matrix cores work on the current one.  K is split over workgroups so that the
-//                      chip is full although there are few tiles; every slice writes its own partial
-//                      tile (no atomics: the result does not depend on scheduling);
+//   2. k_oe_skinny     workgroup = (RT x 32 rows of Sg) x (256 rows of L) x (one slice of K), a wave = all the rows
+//                      of Sg x 64 rows of L.  Stages of 64 K-elements travel memory -> registers -> LDS; two are
+//                      on their way in registers while a third is multiplied from one LDS buffer and a fourth is
+//                      being written into the other (one barrier per stage).  Sg and a K-contiguous L lie in LDS
+//                      as [row][64 K]; a K-strided L lies there as it lies in memory, [K][256 rows], and the
+//                      transposing LDS read hands the matrix cores their 8 consecutive K-elements of a row.  K
+//                      is split over workgroups so that the chip is full although there are few tiles; every
+//                      slice writes its own partial tile (no atomics: the result does not depend on scheduling);
 //   3. k_oe_reduce     adds the slices in a fixed order and writes the rows / columns of C.
 // ------------------------------------------------------------------------------------------------
-constexpr int SK_LCOLS = 128;  // rows of L per workgroup
+constexpr int SK_LCOLS = 256;  // rows of L per workgroup
 constexpr int SK_KSTAGE = 64;  // K-elements per pipeline stage
-constexpr int SK_PITCH = 72;   // LDS row pitch in bf16 (144 bytes: 16-byte fragment reads of 16
-                               // consecutive rows then cover the 64 banks exactly once)
+constexpr int SK_PITCH = 72;   // LDS row pitch in bf16 of the [row][64 K] layout (144 bytes: 16-byte fragment
+                               // reads of 16 consecutive rows then cover the 64 banks exactly once)
+constexpr int SK_TPITCH = 288; // pitch in bf16 of the [K][256 rows] layout (576 bytes: the four K-rows of one
+                               // transposing read of 32 lanes start 16 banks apart)
+constexpr int SK_L_ELEMS = SK_LCOLS * SK_PITCH; // = SK_KSTAGE * SK_TPITCH: either layout of a stage of L
+
+typedef short v4s __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(256) void k_gather_rows(const uint16_t *__restrict__ x, int64_t ld, int k_contig, int64_t K,
                                                      const int32_t *__restrict__ idx, int k, int rows_alloc,
@@ -59,12 +65,12 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint16_t *__restrict_
 }
 
 template <int RT, bool LONG_KC>
-__global__ __launch_bounds__(256, 2) void k_oe_skinny(const uint16_t *__restrict__ Sg, const uint16_t *__restrict__ L,
+__global__ __launch_bounds__(256, 1) void k_oe_skinny(const uint16_t *__restrict__ Sg, const uint16_t *__restrict__ L,
                                                       int64_t ldl, int64_t Lo, int64_t K, int stages_per_slice,
                                                       float *__restrict__ P, int64_t rows_all)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t sS[RT * 32 * SK_PITCH];
-    __shared__ __attribute__((aligned(16))) uint16_t sL[SK_LCOLS * SK_PITCH];
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[]; // 2 x (stage of Sg, stage of L)
+    constexpr int S_ELEMS = RT * 32 * SK_PITCH, BUF_ELEMS = S_ELEMS + SK_L_ELEMS;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const int64_t l0 = (int64_t)blockIdx.x * SK_LCOLS;
     const int nstage_all = (int)((K + SK_KSTAGE - 1) / SK_KSTAGE);
@@ -72,82 +78,151 @@ __global__ __launch_bounds__(256, 2) void k_oe_skinny(const uint16_t *__restrict
     Sg += (int64_t)blockIdx.z * RT * 32 * K;
     P += ((int64_t)blockIdx.y * rows_all + (int64_t)blockIdx.z * RT * 32) * Lo;
 
-    // loader geometry
-    const int c8 = tid & 7, r32 = tid >> 3;           // K-contiguous: 16-byte chunk c8 of rows r32 + 32 i
-    const int lane16 = lane & 15, grp = lane >> 4;    // K-strided: K offset lane16, 8 L-rows at 32 w + 8 grp
-    uint4 ps[RT], pl[4];
+    // loader geometry.  [row][K] sources: 16-byte chunk c8 of rows r32 + 32 i.  K-strided L: chunk c32 (8 rows of
+    // L) of K-rows k8 + 8 i, so that a wave reads two whole 512-byte pieces of K-rows.  Every address is a base that
+    // is the same for the whole workgroup plus a 32-bit byte offset of the lane (the offsets stay below 2^31: at most
+    // 256 rows of at most 2^21 elements).  Rows of L past the end are replaced by the last row (their results are
+    // not stored); in a last stage of 32 K-elements the upper half reads the lower half again and the Sg side is
+    // zero there.
+    const int c8 = tid & 7, r32 = tid >> 3, c32 = tid & 31, k8 = tid >> 5;
+    const int64_t last_row = Lo - 1 - l0; // >= 0
+    const char *const Lb = reinterpret_cast<const char *>(L + (LONG_KC ? l0 * ldl : 0));
+    const char *const Sb = reinterpret_cast<const char *>(Sg);
+    const uint32_t voff_s = (uint32_t)(((int64_t)r32 * K + c8 * 8) * 2);
+    uint32_t voff_l[LONG_KC ? 8 : 1];
+    if constexpr (LONG_KC) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int64_t r = r32 + 32 * i;
+            voff_l[i] = (uint32_t)(((r < last_row ? r : last_row) * ldl + c8 * 8) * 2);
+        }
+    } else {
+        const int64_t l = l0 + 8 * c32, l_last = (Lo - 1) / 8 * 8; // whole 16-byte pieces: ld is a multiple of 8
+        voff_l[0] = (uint32_t)(((int64_t)k8 * ldl) * 2) + (uint32_t)((l < l_last ? l : l_last) * 2);
+    }
 
-    auto fetch = [&](int stage) {
+    // A stage past the end of the slice is all zeros (the loop below works on pairs of stages).
+    auto fetch = [&](int stage, uint4 (&fs)[RT], uint4 (&fl)[8]) {
+        if (stage >= s1) {
+#pragma unroll
+            for (int i = 0; i < RT; ++i) fs[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) fl[i] = make_uint4(0, 0, 0, 0);
+            return;
+        }
         const int64_t kk0 = (int64_t)stage * SK_KSTAGE;
+        const bool half = kk0 + SK_KSTAGE > K; // K is a multiple of 32: the last stage may hold 32 K-elements
+        const uint32_t back = half && c8 >= 4 ? 64u : 0u;
 #pragma unroll
         for (int i = 0; i < RT; ++i) {
-            const int64_t kk = kk0 + c8 * 8;
-            ps[i] = kk < K ? *reinterpret_cast<const uint4 *>(Sg + (int64_t)(r32 + 32 * i) * K + kk) : make_uint4(0, 0, 0, 0);
+            fs[i] = *reinterpret_cast<const uint4 *>(Sb + ((int64_t)32 * i * K + kk0) * 2 + (voff_s - back));
+            if (back) fs[i] = make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if constexpr (LONG_KC) {
-                const int64_t kk = kk0 + c8 * 8, l = l0 + r32 + 32 * i;
-                pl[i] = (kk < K && l < Lo) ? load_once16(L + l * ldl + kk) : make_uint4(0, 0, 0, 0);
-            } else {
-                const int64_t kk = kk0 + 16 * i + lane16, l = l0 + 32 * w + 8 * grp;
-                pl[i] = (kk < K && l < Lo) ? load_once16(L + kk * ldl + l) : make_uint4(0, 0, 0, 0);
-            }
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (LONG_KC)
+                fl[i] = load_once16(Lb + kk0 * 2 + (voff_l[i] - back));
+            else
+                fl[i] = load_once16(Lb + (kk0 + (half ? (8 * i) & 31 : 8 * i)) * ldl * 2 + voff_l[0]);
         }
     };
-    auto stash = [&]() {
+    auto stash = [&](uint16_t *buf, const uint4 (&fs)[RT], const uint4 (&fl)[8]) {
+        uint16_t *sS = buf, *sL = buf + S_ELEMS;
 #pragma unroll
-        for (int i = 0; i < RT; ++i) *reinterpret_cast<uint4 *>(sS + (r32 + 32 * i) * SK_PITCH + c8 * 8) = ps[i];
+        for (int i = 0; i < RT; ++i) *reinterpret_cast<uint4 *>(sS + (r32 + 32 * i) * SK_PITCH + c8 * 8) = fs[i];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if constexpr (LONG_KC) {
-                *reinterpret_cast<uint4 *>(sL + (r32 + 32 * i) * SK_PITCH + c8 * 8) = pl[i];
-            } else {
-                uint16_t *d = sL + (32 * w + 8 * grp) * SK_PITCH + 16 * i + lane16;
-                const uint32_t e[4] = {pl[i].x, pl[i].y, pl[i].z, pl[i].w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    d[(2 * j) * SK_PITCH] = (uint16_t)(e[j] & 0xffffu);
-                    d[(2 * j + 1) * SK_PITCH] = (uint16_t)(e[j] >> 16);
-                }
-            }
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (LONG_KC)
+                *reinterpret_cast<uint4 *>(sL + (r32 + 32 * i) * SK_PITCH + c8 * 8) = fl[i];
+            else
+                *reinterpret_cast<uint4 *>(sL + (k8 + 8 * i) * SK_TPITCH + 8 * c32) = fl[i];
         }
     };
 
-    v16f acc[RT];
+    v16f acc[RT][2];
 #pragma unroll
     for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][c][r] = 0.0f;
 
-    if (s0 < s1) {
-        fetch(s0);
-        stash();
-    }
-    __syncthreads();
-    for (int stage = s0; stage < s1; ++stage) {
-        const bool more = stage + 1 < s1;
-        if (more) fetch(stage + 1);
+    // As supplier of addresses for the transposing read, lane s of a group of 16 points at 4 consecutive rows of L
+    // (4 (s % 4) ..) in K-row s / 4; lane n of the group then receives K-rows 0 .. 3 of row n.  The four groups of a
+    // wave are (rows 0-15 | 16-31 of the 32-row tile) x (K-half h) as the matrix cores want them.
+    const int tr_elem = ((lane & 15) >> 2) * SK_TPITCH + 64 * w + 16 * ((lane >> 4) & 1) + 4 * (lane & 3) + 8 * h * SK_TPITCH;
+
+    // The fragments of K-step ks + 1 are read from LDS while the matrix cores work on K-step ks; the scheduling
+    // barriers keep the compiler from reading a whole stage's fragments (128 registers) ahead.
+    auto multiply = [&](const uint16_t *buf) {
+        const uint16_t *sS = buf, *sL = buf + S_ELEMS;
+        uint4 a[2][RT];
+        v8bf b[2][2];
+        auto fragments = [&](int ks, uint4 (&fa)[RT], v8bf (&fb)[2]) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                if constexpr (LONG_KC) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(sL + (64 * w + 32 * c + l32) * SK_PITCH + 16 * ks + 8 * h);
+                    fb[c] = __builtin_bit_cast(v8bf, v);
+                } else {
+                    const uint16_t *q = sL + tr_elem + 16 * ks * SK_TPITCH + 32 * c;
+                    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)q);
+                    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) v4s *)(q + 4 * SK_TPITCH));
+                    typedef short v8s __attribute__((ext_vector_type(8)));
+                    const v8s both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    fb[c] = __builtin_bit_cast(v8bf, both);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+                fa[i] = *reinterpret_cast<const uint4 *>(sS + (32 * i + l32) * SK_PITCH + 16 * ks + 8 * h);
+        };
+        fragments(0, a[0], b[0]);
 #pragma unroll
         for (int ks = 0; ks < SK_KSTAGE / 16; ++ks) {
-            const uint4 b = *reinterpret_cast<const uint4 *>(sL + (32 * w + l32) * SK_PITCH + 16 * ks + 8 * h);
+            if (ks + 1 < SK_KSTAGE / 16) fragments(ks + 1, a[(ks + 1) & 1], b[(ks + 1) & 1]);
 #pragma unroll
-            for (int i = 0; i < RT; ++i) {
-                const uint4 a = *reinterpret_cast<const uint4 *>(sS + (32 * i + l32) * SK_PITCH + 16 * ks + 8 * h);
-                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), acc[i], 0, 0, 0);
-            }
+            for (int i = 0; i < RT; ++i)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+                    acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[ks & 1][i]), b[ks & 1][c],
+                                                                        acc[i][c], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    // Register set (stage - s0) & 1 carries a stage from memory to LDS buffer (stage - s0) & 1.  While a stage is
+    // multiplied, the next one is written into the other buffer (which every wave left before the last barrier)
+    // and the two after that are in flight.
+    uint4 ps[2][RT], pl[2][8];
+    uint16_t *buf0 = smem, *buf1 = smem + BUF_ELEMS;
+    fetch(s0, ps[0], pl[0]);
+    fetch(s0 + 1, ps[1], pl[1]);
+    stash(buf0, ps[0], pl[0]);
+    fetch(s0 + 2, ps[0], pl[0]);
+    __syncthreads();
+    for (int stage = s0; stage < s1; stage += 2) { // no branch around a multiply: the accumulators stay where they are
+        stash(buf1, ps[1], pl[1]);
+        fetch(stage + 3, ps[1], pl[1]);
+        multiply(buf0);
         __syncthreads();
-        if (more) stash();
+        stash(buf0, ps[0], pl[0]);
+        fetch(stage + 4, ps[0], pl[0]);
+        multiply(buf1);
         __syncthreads();
     }
 
-    const int64_t l = l0 + 32 * w + l32;
-    if (l < Lo) {
 #pragma unroll
-        for (int i = 0; i < RT; ++i)
+    for (int c = 0; c < 2; ++c) {
+        const int64_t l = l0 + 64 * w + 32 * c + l32;
+        if (l < Lo) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) P[(int64_t)(32 * i + (r >> 2) * 8 + h * 4 + (r & 3)) * Lo + l] = acc[i][r];
+            for (int i = 0; i < RT; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    P[(int64_t)(32 * i + (r >> 2) * 8 + h * 4 + (r & 3)) * Lo + l] = acc[i][c][r];
+        }
     }
 }
 
@@ -182,24 +257,20 @@ struct skinny_plan_t {
     size_t sg_bytes, p_bytes;
 };
 
-// Row tiles per workgroup from {2, 4, 6, 8} with the least padding; K slices so that about two
-// workgroups per compute unit exist, each with at least 8 stages.
+// Row tiles per workgroup from {2, 4, 6}; K slices so that up to one workgroup per compute unit exists, each
+// with at least 8 stages.
 skinny_plan_t plan_skinny(int64_t Lo, int64_t K, int k)
 {
     skinny_plan_t p;
     const int tiles = (k + 31) / 32;
-    p.rt = 8;
-    p.groups = (tiles + 7) / 8;
-    for (int rt = 6; rt >= 2; rt -= 2) {
-        const int g = (tiles + rt - 1) / rt;
-        if (g * rt < p.groups * p.rt || (g * rt == p.groups * p.rt && g < p.groups)) {
-            p.rt = rt;
-            p.groups = g;
-        }
-    }
+    p.groups = (tiles + 5) / 6; // every group of row tiles reads L once: as few as possible
+    p.rt = 6;
+    for (int rt = 4; rt >= 2; rt -= 2)
+        if ((tiles + rt - 1) / rt == p.groups) p.rt = rt; // the same passes with less padding
     p.rows_all = (int64_t)p.groups * p.rt * 32;
     const int64_t nstage = ceil_div(K, SK_KSTAGE), wgs = ceil_div(Lo, SK_LCOLS) * p.groups;
-    int64_t want = ceil_div(512, wgs);
+    int64_t want = 256 / wgs; // one workgroup per compute unit is resident; never more than that many: a second,
+                              // partly filled round costs more than idle compute units do
     if (want > nstage / 8) want = nstage / 8;
     if (want < 1) want = 1;
     p.stages_per_slice = (int)ceil_div(nstage, want);
@@ -209,14 +280,31 @@ skinny_plan_t plan_skinny(int64_t Lo, int64_t K, int k)
     return p;
 }
 
-template <int RT>
-void launch_skinny(bool long_kc, dim3 grid, hipStream_t st, const uint16_t *Sg, const uint16_t *L, int64_t ldl, int64_t Lo,
-                   int64_t K, int sps, float *P, int64_t rows_all)
+template <int RT, bool LONG_KC>
+int launch_skinny_as(dim3 grid, hipStream_t st, const uint16_t *Sg, const uint16_t *L, int64_t ldl, int64_t Lo, int64_t K,
+                     int sps, float *P, int64_t rows_all)
 {
-    if (long_kc)
-        hipLaunchKernelGGL((k_oe_skinny<RT, true>), grid, dim3(256), 0, st, Sg, L, ldl, Lo, K, sps, P, rows_all);
-    else
-        hipLaunchKernelGGL((k_oe_skinny<RT, false>), grid, dim3(256), 0, st, Sg, L, ldl, Lo, K, sps, P, rows_all);
+    constexpr size_t lds = 2 * (RT * 32 * SK_PITCH + SK_L_ELEMS) * sizeof(uint16_t);
+    static device_once_t once; // more LDS than a launch may ask for by default: allowed once per device
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
+    if (rc != ADAHOP_OK) return rc;
+    if (once.need(dev)) {
+        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oe_skinny<RT, LONG_KC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (rc != ADAHOP_OK) return rc;
+        once.mark(dev);
+    }
+    hipLaunchKernelGGL((k_oe_skinny<RT, LONG_KC>), grid, dim3(256), lds, st, Sg, L, ldl, Lo, K, sps, P, rows_all);
+    return check_launch();
+}
+
+template <int RT>
+int launch_skinny(bool long_kc, dim3 grid, hipStream_t st, const uint16_t *Sg, const uint16_t *L, int64_t ldl, int64_t Lo,
+                  int64_t K, int sps, float *P, int64_t rows_all)
+{
+    return long_kc ? launch_skinny_as<RT, true>(grid, st, Sg, L, ldl, Lo, K, sps, P, rows_all)
+                   : launch_skinny_as<RT, false>(grid, st, Sg, L, ldl, Lo, K, sps, P, rows_all);
 }
 
 // out[o, t] = x(o, idx[t]) for t < k, 0 for k <= t < kpad.  out is [outer, kpad] bf16.
@@ -331,12 +419,10 @@ int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int k
     const dim3 grid((unsigned)ceil_div(Lo, SK_LCOLS), (unsigned)p.nslice, (unsigned)p.groups);
     const uint16_t *l = static_cast<const uint16_t *>(L.data);
     switch (p.rt) {
-    case 2: launch_skinny<2>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
-    case 4: launch_skinny<4>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
-    case 6: launch_skinny<6>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
-    default: launch_skinny<8>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
+    case 2: rc = launch_skinny<2>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
+    case 4: rc = launch_skinny<4>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
+    default: rc = launch_skinny<6>(L.k_contig, grid, st, Sg, l, L.ld, Lo, K, p.stages_per_slice, P, p.rows_all); break;
     }
-    rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
 
     const unsigned rblocks = (unsigned)ceil_div((int64_t)k * Lo, 256);
