@@ -45,22 +45,44 @@ constexpr int SK_L_ELEMS = SK_LCOLS * SK_PITCH; // = SK_KSTAGE * SK_TPITCH: eith
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void k_gather_rows(const uint16_t *__restrict__ x, int64_t ld, int k_contig, int64_t K,
+__global__ __launch_bounds__(256) void k_gather_rows(const uint16_t *__restrict__ x, int64_t ld, int64_t K,
                                                      const int32_t *__restrict__ idx, int k, int rows_alloc,
                                                      uint16_t *__restrict__ out)
+{ // K-contiguous source: one thread = 8 consecutive K-elements of one row
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x, per_row = K >> 3;
+    if (g >= rows_alloc * per_row) return;
+    const int64_t t = g / per_row, c = g - t * per_row;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (t < k) v = load_once16(x + (int64_t)idx[t] * ld + c * 8);
+    *reinterpret_cast<uint4 *>(out + t * K + c * 8) = v;
+}
+
+// K-strided source (element (o, kk) at x[kk * ld + o]): a workgroup takes 64 K-rows x 64 extracted columns.  It reads
+// with the extracted column as the fast index, so that a wave's 64 two-byte reads fall into one K-row of the source
+// (one DRAM page, neighbouring sectors where the indices are close) instead of 64 rows, turns the tile in LDS and
+// writes 128-byte runs along K.
+__global__ __launch_bounds__(256) void k_gather_rows_strided(const uint16_t *__restrict__ x, int64_t ld, int64_t K,
+                                                             const int32_t *__restrict__ idx, int k,
+                                                             uint16_t *__restrict__ out)
 {
-    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (k_contig) { // one thread = 8 consecutive K-elements of one row
-        const int64_t per_row = K >> 3;
-        if (g >= rows_alloc * per_row) return;
-        const int64_t t = g / per_row, c = g - t * per_row;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (t < k) v = load_once16(x + (int64_t)idx[t] * ld + c * 8);
-        *reinterpret_cast<uint4 *>(out + t * K + c * 8) = v;
-    } else {        // one thread = one element; neighbouring threads write neighbouring K
-        if (g >= rows_alloc * K) return;
-        const int64_t t = g / K, kk = g - t * K;
-        out[g] = t < k ? load_once2(x + kk * ld + idx[t]) : (uint16_t)0;
+    __shared__ uint16_t tile[64][66]; // [t][kk], 33-word pitch: the column writes below spread over the banks
+    const int64_t kk0 = (int64_t)blockIdx.x * 64;
+    const int t0 = blockIdx.y * 64, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int t = t0 + lane;
+    const int64_t col = t < k ? idx[t] : -1;
+    uint16_t v[16]; // all 16 reads of a thread in flight at once: few workgroups, each bound by its round trips
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int64_t kk = kk0 + 4 * i + w;
+        v[i] = (col >= 0 && kk < K) ? load_once2(x + kk * ld + col) : (uint16_t)0;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tile[lane][4 * i + w] = v[i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int tt = 4 * i + w; // row of the tile; the wave's lanes run along K
+        if (kk0 + lane < K) out[(int64_t)(t0 + tt) * K + kk0 + lane] = tile[tt][lane];
     }
 }
 
@@ -410,9 +432,12 @@ int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int k
     uint16_t *Sg = static_cast<uint16_t *>(workspace);
     float *P = reinterpret_cast<float *>(static_cast<char *>(workspace) + p.sg_bytes);
 
-    const int64_t gthreads = S.k_contig ? p.rows_all * (K >> 3) : p.rows_all * K;
-    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)ceil_div(gthreads, 256)), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(S.data), S.ld, S.k_contig, K, idx, k, (int)p.rows_all, Sg);
+    if (S.k_contig)
+        hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)ceil_div(p.rows_all * (K >> 3), 256)), dim3(256), 0, st,
+                           static_cast<const uint16_t *>(S.data), S.ld, K, idx, k, (int)p.rows_all, Sg);
+    else // rows_all is a multiple of 64: whole tiles of extracted columns
+        hipLaunchKernelGGL(k_gather_rows_strided, dim3((unsigned)ceil_div(K, 64), (unsigned)(p.rows_all / 64)), dim3(256), 0,
+                           st, static_cast<const uint16_t *>(S.data), S.ld, K, idx, k, Sg);
     int rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
 
