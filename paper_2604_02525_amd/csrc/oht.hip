@@ -19,8 +19,10 @@ namespace adahop {
 
 namespace {
 
-constexpr int OHT_TK = 128;            // K-columns of an operand tile
-constexpr int OHT_TN = 256;            // columns of a C tile
+// Tiles are kept small in the direction that is not transformed: several workgroups then share a compute unit and
+// one's loads and stores overlap another's butterflies (a workgroup runs its phases one after the other).
+constexpr int OHT_TK = 64;             // K-columns of an operand tile
+constexpr int OHT_TN = 128;            // columns of a C tile (>= the largest block: a row's blocks lie inside a tile)
 constexpr int OHT_KP = OHT_TK + 1;     // LDS pitches (floats): odd, so that column walks hit distinct banks
 constexpr int OHT_NP = OHT_TN + 1;
 
@@ -29,25 +31,65 @@ template <> __device__ __forceinline__ float oht_norm<32>() { return 0x1.6a09e6p
 template <> __device__ __forceinline__ float oht_norm<64>() { return 0.125f; }
 template <> __device__ __forceinline__ float oht_norm<128>() { return 0x1.6a09e6p-4f; }
 
-// v <- (1/sqrt(B)) H_B v on B values spaced `stride` floats apart in LDS.
-template <int B> __device__ __forceinline__ void fwht_lds(float *p, int stride)
+// v <- (1/sqrt(B)) H_B v on B values spaced `stride` floats apart in LDS, the work of one vector shared by P
+// threads (part = 0 .. P-1) in two passes with a workgroup barrier between them: first every thread runs the
+// strides 1 .. B/(2P) on its own chunk of B/P consecutive values, then the strides B/P .. B/2 on the values of equal
+// position in the P chunks.  Every value still sees the strides in ascending order with x + y to the lower and
+// x - y to the upper index, so the result is that of the plain butterfly network, bit for bit.  All threads of the
+// workgroup must call it (live = false: no memory access, barrier only).
+// gout != nullptr: the results go to gout[index * gstride] (global memory) instead of back into LDS.
+template <int B, int P>
+__device__ __forceinline__ void fwht_lds_split(float *p, int stride, int part, bool live, float *gout = nullptr,
+                                               int64_t gstride = 0)
 {
-    float v[B];
+    constexpr int CH = B / P, G = CH / P;
+    if (live) {
+        float v[CH];
+        float *q = p + part * CH * stride;
 #pragma unroll
-    for (int i = 0; i < B; ++i) v[i] = p[i * stride];
+        for (int i = 0; i < CH; ++i) v[i] = q[i * stride];
 #pragma unroll
-    for (int h = 1; h < B; h *= 2)
+        for (int h = 1; h < CH; h *= 2)
 #pragma unroll
-        for (int i = 0; i < B; i += 2 * h)
+            for (int i = 0; i < CH; i += 2 * h)
 #pragma unroll
-            for (int j = i; j < i + h; ++j) {
-                const float a = v[j], b = v[j + h];
-                v[j] = a + b;
-                v[j + h] = a - b;
+                for (int j = i; j < i + h; ++j) {
+                    const float a = v[j], b = v[j + h];
+                    v[j] = a + b;
+                    v[j + h] = a - b;
+                }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) q[i * stride] = v[i];
+    }
+    __syncthreads();
+    if (live) {
+        const float c = oht_norm<B>();
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float *q = p + (part * G + g) * stride;
+            float u[P];
+#pragma unroll
+            for (int j = 0; j < P; ++j) u[j] = q[j * CH * stride];
+#pragma unroll
+            for (int h = 1; h < P; h *= 2)
+#pragma unroll
+                for (int i = 0; i < P; i += 2 * h)
+#pragma unroll
+                    for (int j = i; j < i + h; ++j) {
+                        const float a = u[j], b = u[j + h];
+                        u[j] = a + b;
+                        u[j + h] = a - b;
+                    }
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+                const float r = __builtin_fmaf(u[j], c, 0.0f); // "+ 0": an exact zero becomes +0
+                if (gout)
+                    gout[(int64_t)(j * CH + part * G + g) * gstride] = r;
+                else
+                    q[j * CH * stride] = r;
             }
-    const float c = oht_norm<B>();
-#pragma unroll
-    for (int i = 0; i < B; ++i) p[i * stride] = __builtin_fmaf(v[i], c, 0.0f); // "+ 0": an exact zero becomes +0
+        }
+    }
 }
 
 __device__ __forceinline__ int e8m0_code(float amax)
@@ -92,8 +134,8 @@ __global__ __launch_bounds__(256) void k_oht_quant(const uint16_t *__restrict__ 
         }
     }
     __syncthreads();
-    // 2. transform along the outer index: one thread per K-column
-    if (tid < OHT_TK && k0 + tid < K) fwht_lds<B>(tile + tid, OHT_KP);
+    // 2. transform along the outer index: four threads (one of each wave) per K-column
+    fwht_lds_split<B, 256 / OHT_TK>(tile + tid % OHT_TK, OHT_KP, tid / OHT_TK, k0 + tid % OHT_TK < K);
     __syncthreads();
     // 3. quantise along K: one lane per 16 consecutive K-elements of a row, two lanes per MX block
     for (int idx = tid; idx < B * (OHT_TK / 16); idx += 256) {
@@ -126,27 +168,44 @@ __global__ __launch_bounds__(256) void k_oht_quant(const uint16_t *__restrict__ 
     }
 }
 
-// Workgroup = B rows x OHT_TN columns of C (OHT_TN / B blocks side by side), transformed along both
-// axes in LDS.  grid (ceil(N / OHT_TN), M / B).  M % B == 0, N % B == 0.
-template <int B>
+// Workgroup = B rows x OHT_TN columns of C (OHT_TN / B blocks side by side), transformed along both axes in LDS.
+// grid (ceil(N / OHT_TN), M / B).  M % B == 0, N % B == 0.
+// VEC: C is 16-byte aligned with ldc % 4 == 0, rows are read as float4 (N % B == 0 makes every float4 whole).
+// (A persistent variant that keeps the next tile on its way in registers while the butterflies run was measured:
+// 1.08 against 1.12 ms for block 128 and 0.78 against 0.68 ms for block 32 on 16384 x 28672 -- the registers it
+// needs cost the occupancy that hides the same latency here.)
+template <int B, bool VEC>
 __global__ __launch_bounds__(256) void k_oht_inverse(float *__restrict__ C, int64_t M, int64_t N, int64_t ldc)
 {
     extern __shared__ float tile[]; // [B][OHT_NP]
     const int tid = threadIdx.x;
     const int64_t n0 = (int64_t)blockIdx.x * OHT_TN, m0 = (int64_t)blockIdx.y * B;
-    const bool col_live = n0 + tid < N;
-    if (col_live)
-        for (int r = 0; r < B; ++r) tile[r * OHT_NP + tid] = C[(m0 + r) * ldc + n0 + tid];
-    __syncthreads();
-    if (col_live) fwht_lds<B>(tile + tid, OHT_NP); // H^T from the left: along the rows-axis of every column
-    __syncthreads();
-    {
-        const int r = tid % B, seg = tid / B; // one thread per (row, B-wide column block)
-        if (seg < OHT_TN / B && n0 + seg * B < N) fwht_lds<B>(tile + r * OHT_NP + seg * B, 1); // H^T from the right
+    if constexpr (VEC) {
+#pragma unroll 4
+        for (int idx = tid; idx < B * (OHT_TN / 4); idx += 256) {
+            const int r = idx / (OHT_TN / 4), c4 = idx % (OHT_TN / 4);
+            if (n0 + 4 * c4 < N) {
+                const float4 q = *reinterpret_cast<const float4 *>(C + (m0 + r) * ldc + n0 + 4 * c4);
+                float *t = tile + r * OHT_NP + 4 * c4;
+                t[0] = q.x, t[1] = q.y, t[2] = q.z, t[3] = q.w;
+            }
+        }
+    } else {
+        for (int idx = tid; idx < B * OHT_TN; idx += 256) {
+            const int r = idx / OHT_TN, c = idx % OHT_TN;
+            if (n0 + c < N) tile[r * OHT_NP + c] = C[(m0 + r) * ldc + n0 + c];
+        }
     }
     __syncthreads();
-    if (col_live)
-        for (int r = 0; r < B; ++r) C[(m0 + r) * ldc + n0 + tid] = tile[r * OHT_NP + tid];
+    {   // H^T from the right: two threads per (row, B-wide column block); there are B * (OHT_TN / B) such pairs
+        const int u = tid % OHT_TN, r = u % B, seg = u / B;
+        fwht_lds_split<B, 256 / OHT_TN>(tile + r * OHT_NP + seg * B, 1, tid / OHT_TN, n0 + seg * B < N);
+    }
+    __syncthreads();
+    // H^T from the left: along the rows of every column, two threads per column; the results leave for memory from
+    // the registers (a wave writes 256 consecutive bytes of a row)
+    fwht_lds_split<B, 256 / OHT_TN>(tile + tid % OHT_TN, OHT_NP, tid / OHT_TN, n0 + tid % OHT_TN < N,
+                                    C + m0 * ldc + n0 + tid % OHT_TN, ldc);
 }
 
 template <int B> int launch_quant(const adahop_operand_t &x, uint8_t *codes, uint8_t *scales, hipStream_t st)
@@ -169,7 +228,7 @@ template <int B> int launch_quant(const adahop_operand_t &x, uint8_t *codes, uin
     return check_launch();
 }
 
-template <int B> int launch_inverse(float *C, int64_t M, int64_t N, int64_t ldc, hipStream_t st)
+template <int B, bool VEC> int launch_inverse_as(float *C, int64_t M, int64_t N, int64_t ldc, hipStream_t st)
 {
     const size_t lds = (size_t)B * OHT_NP * sizeof(float);
     // more LDS than a launch may ask for by default (B = 128): set once per device
@@ -178,14 +237,20 @@ template <int B> int launch_inverse(float *C, int64_t M, int64_t N, int64_t ldc,
     int rc = check_hip(hipGetDevice(&dev));
     if (rc != ADAHOP_OK) return rc;
     if (once.need(dev)) {
-        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B>),
+        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B, VEC>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         if (rc != ADAHOP_OK) return rc;
         once.mark(dev);
     }
     const dim3 grid((unsigned)ceil_div(N, OHT_TN), (unsigned)(M / B));
-    hipLaunchKernelGGL(k_oht_inverse<B>, grid, dim3(256), lds, st, C, M, N, ldc);
+    hipLaunchKernelGGL((k_oht_inverse<B, VEC>), grid, dim3(256), lds, st, C, M, N, ldc);
     return check_launch();
+}
+
+template <int B> int launch_inverse(float *C, int64_t M, int64_t N, int64_t ldc, hipStream_t st)
+{
+    return aligned(C, 16) && ldc % 4 == 0 ? launch_inverse_as<B, true>(C, M, N, ldc, st)
+                                          : launch_inverse_as<B, false>(C, M, N, ldc, st);
 }
 
 } // namespace
