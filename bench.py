@@ -22,8 +22,9 @@ BF16_PEAK_TFLOPS = 2516.0
 # HBM bytes per launch of the FP4 GEMM kernel, by (M, N, K): rocprofv3 FETCH_SIZE + WRITE_SIZE (KiB per
 # dispatch), each scaled by what the same counter reads for a plain 1 GiB copy (--copy-calibration);
 # the runs and the scaling are in profiles/gemm_mx_16384x28672x8192_counters.txt.
-GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 5.05e9}
-GEMM_HBM_TRAFFIC_SOURCE = "profiles/gemm_mx_16384x28672x8192_counters.txt (rocprofv3 --pmc runs; not measured in this run)"
+GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 4.96e9, (8192, 8192, 2048): 3.58e8}
+GEMM_HBM_TRAFFIC_SOURCE = {(16384, 28672, 8192): "profiles/gemm_mx_16384x28672x8192_counters.txt",
+                           (8192, 8192, 2048): "profiles/gemm_mx_dual_8192x8192x2048_counters.txt"}
 
 
 def parse():
@@ -297,7 +298,8 @@ def main():
     roofline = {"bound": "mfma", "kernel": "mxfp4 gemm", "achieved": achieved, "peak": MXFP4_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MXFP4_PEAK_TFLOPS,
                 "traffic": GEMM_HBM_TRAFFIC_BYTES.get((big.M, big.N, big.K)),
-                "traffic_source": GEMM_HBM_TRAFFIC_SOURCE,
+                "traffic_source": (GEMM_HBM_TRAFFIC_SOURCE[(big.M, big.N, big.K)] + " (rocprofv3 --pmc runs; not measured in "
+                                   "this run)") if (big.M, big.N, big.K) in GEMM_HBM_TRAFFIC_SOURCE else None,
                 "shape": [big.M, big.N, big.K], "ms": gemm_ms, "timing": "back to back, operands warm",
                 "in_step_ms": in_step_ms, "in_step_achieved": in_step, "in_step_frac": in_step / MXFP4_PEAK_TFLOPS}
 
