@@ -89,3 +89,23 @@ def test_whole_path_with_stochastically_rounded_gradient_operand(ah, strategy, k
     det = ah.adahop_gemm(dG, dW, strategy, 128, k)
     torch.cuda.synchronize()
     assert torch.equal(det["b_codes"], out["b_codes"]) and not torch.equal(det["a_codes"], out["a_codes"])
+
+
+def test_stochastic_rounding_in_the_quantiser_that_copies_k_channels(ah):
+    """OE-K on K-contiguous operands with K a whole number of 4096-element passes takes the quantiser that also
+    copies the extracted channels out; its stochastic-rounding instance must draw as every other quantiser does."""
+    M, N, K, k, b = 136, 72, 4096, 37, 128
+    A = inputs.Operand(inputs.matrix(M, K, 1.0, 720, col_outliers=(12, 40.0, 80.0)), True)
+    B = inputs.Operand(inputs.matrix(N, K, 0.02, 721), True)
+    say("whole path, SR on both operands, channels copied by the quantiser")
+    dA, dB = ah.Operand.from_bits(A.bits, True), ah.Operand.from_bits(B.bits, True)
+    out = ah.adahop_gemm(dA, dB, inputs.IHT_OE_K, b, k, sr_seed_a=5, sr_seed_b=6)
+    torch.cuda.synchronize()
+    ref = orc.adahop_gemm(A.bits, True, B.bits, True, inputs.IHT_OE_K, b, k, sr_seed_a=5, sr_seed_b=6)
+    for name in ("a_scales", "b_scales", "a_codes", "b_codes"):
+        assert np.array_equal(host(out[name]), ref[name]), name
+    assert np.array_equal(np.sort(host(out["idx"])), ref["idx"])
+    err = np.linalg.norm(host(out["C"]).astype(np.float64) - ref["C"]) / np.linalg.norm(ref["C"])
+    say(f"  vs oracle {err:.2e}")
+    assert err < 1e-3
+
