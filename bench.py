@@ -415,6 +415,28 @@ def main():
         extras["iht_quantize_k_strided"] = {"outer": qs.outer, "K": qs.K, "k_contig": qs.k_contig, "ms": qs_ms,
                                             "GBps": 2.53125 * qs.outer * qs.K / (qs_ms * 1e-3) / 1e9, "peak_GBps": 8000.0}
         del codes, scales, cs, ss
+        # the BF16 row / column product alone (gather, skinny product, slice reduction): bound by reading the long
+        # operand once; and FOID (scores + top-k) alone
+        rowp = next((p for p in prepared if p.g.strategy in (inputs.IHT_OE_ROW, inputs.IHT_OE_COL) and p.g.k > 0), None)
+        if rowp is not None:
+            kind = rowp.g.strategy
+            long_op, dim = (rowp.B, rowp.M) if kind == inputs.IHT_OE_ROW else (rowp.A, rowp.N)
+            scored = rowp.A if kind == inputs.IHT_OE_ROW else rowp.B
+            sel = torch.randperm(dim, device="cuda")[:rowp.g.k].to(torch.int32)
+            gws = torch.empty(ah.adahop_oe_gather_bytes(rowp.M, rowp.N, rowp.K, kind, rowp.g.k), dtype=torch.uint8, device="cuda")
+            oe_ms = time_ms(torch, lambda: ah.adahop_oe_gemm_bf16(rowp.A, rowp.B, kind, sel, rowp.C, gws), 10)
+            lbytes = 2.0 * long_op.outer * long_op.K
+            extras["oe_row_col_product"] = {"gemm": rowp.g.name, "k": rowp.g.k, "long_operand": [long_op.outer, long_op.K],
+                                            "long_operand_k_contig": bool(long_op.k_contig), "ms": oe_ms,
+                                            "GBps": lbytes / (oe_ms * 1e-3) / 1e9, "peak_GBps": 8000.0,
+                                            "tflops_bf16": 2.0 * rowp.g.k * long_op.outer * long_op.K / oe_ms / 1e9}
+            mask = torch.empty(dim, dtype=torch.uint8, device="cuda")
+            scores = torch.empty(dim, dtype=torch.float32, device="cuda")
+            import ctypes as C
+            f_ms = time_ms(torch, lambda: ah.lib().adahop_foid_topk(C.byref(scored.c()), 0, rowp.g.k, sel.data_ptr(),
+                                                                    mask.data_ptr(), scores.data_ptr(), ah._stream(None)), 10)
+            extras["foid_topk"] = {"dim": dim, "k": rowp.g.k, "ms": f_ms}
+            del gws, mask, scores, sel
         if args.workload.startswith("cfg4"):
             # extraction-count sweep of configs[4]: K-channels on the up-projection forward, rows on its dgrad
             sweep = []
