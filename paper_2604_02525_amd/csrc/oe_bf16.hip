@@ -123,43 +123,58 @@ __global__ __launch_bounds__(256, 1) void k_oe_skinny(const uint16_t *__restrict
         voff_l[0] = (uint32_t)(((int64_t)k8 * ldl) * 2) + (uint32_t)((l < l_last ? l : l_last) * 2);
     }
 
-    // A stage past the end of the slice is all zeros (the loop below works on pairs of stages).
-    auto fetch = [&](int stage, uint4 (&fs)[RT], uint4 (&fl)[8]) {
-        if (stage >= s1) {
-#pragma unroll
-            for (int i = 0; i < RT; ++i) fs[i] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) fl[i] = make_uint4(0, 0, 0, 0);
-            return;
-        }
-        const int64_t kk0 = (int64_t)stage * SK_KSTAGE;
+    // A stage past the end of the slice (the loop below works on pairs of stages) reads the slice's last stage
+    // again with the Sg side cleared.  No branches: the loop body stays one block, which the interleaving of
+    // memory and matrix-core instructions below relies on.
+    // QUARTER = 0 .. 3: the quarter of a stage's loads / LDS writes that is slotted between the matrix-core
+    // instructions of K-step QUARTER (rows of L 2 q and 2 q + 1 of the lane's eight, row tiles q and q + 4 of Sg);
+    // QUARTER = -1: all of them.
+    // (The clearing of the Sg side happens when the registers are written to LDS, stage_keep below: touching a
+    // loaded value here would make the wave wait for the load it has just issued.)
+    auto stage_keep = [&](int stage) -> uint32_t {
+        const bool ghost = stage >= s1;
+        const int64_t kk0 = (int64_t)(ghost ? s1 - 1 : stage) * SK_KSTAGE;
+        return (ghost || (kk0 + SK_KSTAGE > K && c8 >= 4)) ? 0u : 0xffffffffu;
+    };
+    auto fetch = [&](int stage, uint4 (&fs)[RT], uint4 (&fl)[8], auto quarter) {
+        constexpr int Q = decltype(quarter)::value;
+        const bool ghost = stage >= s1;
+        const int64_t kk0 = (int64_t)(ghost ? s1 - 1 : stage) * SK_KSTAGE;
         const bool half = kk0 + SK_KSTAGE > K; // K is a multiple of 32: the last stage may hold 32 K-elements
         const uint32_t back = half && c8 >= 4 ? 64u : 0u;
 #pragma unroll
         for (int i = 0; i < RT; ++i) {
+            if (Q >= 0 && (i & 3) != Q) continue;
             fs[i] = *reinterpret_cast<const uint4 *>(Sb + ((int64_t)32 * i * K + kk0) * 2 + (voff_s - back));
-            if (back) fs[i] = make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
+            if (Q >= 0 && (i >> 1) != Q) continue;
             if constexpr (LONG_KC)
                 fl[i] = load_once16(Lb + kk0 * 2 + (voff_l[i] - back));
             else
                 fl[i] = load_once16(Lb + (kk0 + (half ? (8 * i) & 31 : 8 * i)) * ldl * 2 + voff_l[0]);
         }
     };
-    auto stash = [&](uint16_t *buf, const uint4 (&fs)[RT], const uint4 (&fl)[8]) {
+    auto stash = [&](uint16_t *buf, const uint4 (&fs)[RT], const uint4 (&fl)[8], uint32_t keep, auto quarter) {
+        constexpr int Q = decltype(quarter)::value;
         uint16_t *sS = buf, *sL = buf + S_ELEMS;
 #pragma unroll
-        for (int i = 0; i < RT; ++i) *reinterpret_cast<uint4 *>(sS + (r32 + 32 * i) * SK_PITCH + c8 * 8) = fs[i];
+        for (int i = 0; i < RT; ++i) {
+            if (Q >= 0 && (i & 3) != Q) continue;
+            *reinterpret_cast<uint4 *>(sS + (r32 + 32 * i) * SK_PITCH + c8 * 8) =
+                make_uint4(fs[i].x & keep, fs[i].y & keep, fs[i].z & keep, fs[i].w & keep);
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
+            if (Q >= 0 && (i >> 1) != Q) continue;
             if constexpr (LONG_KC)
                 *reinterpret_cast<uint4 *>(sL + (r32 + 32 * i) * SK_PITCH + c8 * 8) = fl[i];
             else
                 *reinterpret_cast<uint4 *>(sL + (k8 + 8 * i) * SK_TPITCH + 8 * c32) = fl[i];
         }
     };
+    typedef std::integral_constant<int, -1> all_t;
 
     v16f acc[RT][2];
 #pragma unroll
@@ -174,10 +189,16 @@ __global__ __launch_bounds__(256, 1) void k_oe_skinny(const uint16_t *__restrict
     // wave are (rows 0-15 | 16-31 of the 32-row tile) x (K-half h) as the matrix cores want them.
     const int tr_elem = ((lane & 15) >> 2) * SK_TPITCH + 64 * w + 16 * ((lane >> 4) & 1) + 4 * (lane & 3) + 8 * h * SK_TPITCH;
 
-    // The fragments of K-step ks + 1 are read from LDS while the matrix cores work on K-step ks; the scheduling
-    // barriers keep the compiler from reading a whole stage's fragments (128 registers) ahead.
-    auto multiply = [&](const uint16_t *buf) {
-        const uint16_t *sS = buf, *sL = buf + S_ELEMS;
+    // One stage: multiply from `cur`; meanwhile write the stage that has arrived in (fs, fl) into `oth` (every wave
+    // left that buffer before the last barrier) and refill (fs, fl) with stage `next`.  A wave issues in order and
+    // is alone on its SIMD, so whatever is issued in a burst keeps it from feeding the matrix core: the fragment
+    // reads of K-step ks + 1, a quarter of the LDS writes and a quarter of the loads are slotted one by one between
+    // the matrix-core instructions of K-step ks (scheduling groups), and a scheduling barrier after every K-step
+    // keeps the compiler from reading a whole stage's fragments (128 registers) ahead.
+    // (fs, fl) hold stage next - 2 on entry.
+    auto stage_body = [&](const uint16_t *cur, uint16_t *oth, uint4 (&fs)[RT], uint4 (&fl)[8], int next) {
+        const uint32_t keep = stage_keep(next - 2);
+        const uint16_t *sS = cur, *sL = cur + S_ELEMS;
         uint4 a[2][RT];
         v8bf b[2][2];
         auto fragments = [&](int ks, uint4 (&fa)[RT], v8bf (&fb)[2]) {
@@ -200,38 +221,51 @@ __global__ __launch_bounds__(256, 1) void k_oe_skinny(const uint16_t *__restrict
             for (int i = 0; i < RT; ++i)
                 fa[i] = *reinterpret_cast<const uint4 *>(sS + (32 * i + l32) * SK_PITCH + 16 * ks + 8 * h);
         };
-        fragments(0, a[0], b[0]);
-#pragma unroll
-        for (int ks = 0; ks < SK_KSTAGE / 16; ++ks) {
-            if (ks + 1 < SK_KSTAGE / 16) fragments(ks + 1, a[(ks + 1) & 1], b[(ks + 1) & 1]);
+        auto step = [&](auto ks_c) {
+            constexpr int ks = decltype(ks_c)::value;
+            constexpr int n_read = ks + 1 < SK_KSTAGE / 16 ? RT + (LONG_KC ? 2 : 4) : 0;
+            constexpr int n_move = 2 + (ks < RT ? 1 : 0) + (ks + 4 < RT ? 1 : 0); // LDS writes = loads of this quarter
+            if constexpr (ks + 1 < SK_KSTAGE / 16) fragments(ks + 1, a[(ks + 1) & 1], b[(ks + 1) & 1]);
+            stash(oth, fs, fl, keep, ks_c);
+            fetch(next, fs, fl, ks_c);
 #pragma unroll
             for (int i = 0; i < RT; ++i)
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
                     acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[ks & 1][i]), b[ks & 1][c],
                                                                         acc[i][c], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 2 * RT; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // one matrix-core instruction
+                if (j < n_read) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // one LDS read
+                if (j < n_move) {
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);             // one LDS write
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // one load
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+        fragments(0, a[0], b[0]);
+        step(std::integral_constant<int, 0>());
+        step(std::integral_constant<int, 1>());
+        step(std::integral_constant<int, 2>());
+        step(std::integral_constant<int, 3>());
     };
+    static_assert(SK_KSTAGE == 64, "four K-steps per stage, one quarter of the data movement in each");
 
     // Register set (stage - s0) & 1 carries a stage from memory to LDS buffer (stage - s0) & 1.  While a stage is
-    // multiplied, the next one is written into the other buffer (which every wave left before the last barrier)
-    // and the two after that are in flight.
+    // multiplied, the next one is written into the other buffer and the two after that are in flight.
     uint4 ps[2][RT], pl[2][8];
     uint16_t *buf0 = smem, *buf1 = smem + BUF_ELEMS;
-    fetch(s0, ps[0], pl[0]);
-    fetch(s0 + 1, ps[1], pl[1]);
-    stash(buf0, ps[0], pl[0]);
-    fetch(s0 + 2, ps[0], pl[0]);
+    fetch(s0, ps[0], pl[0], all_t());
+    fetch(s0 + 1, ps[1], pl[1], all_t());
+    stash(buf0, ps[0], pl[0], stage_keep(s0), all_t());
+    fetch(s0 + 2, ps[0], pl[0], all_t());
     __syncthreads();
     for (int stage = s0; stage < s1; stage += 2) { // no branch around a multiply: the accumulators stay where they are
-        stash(buf1, ps[1], pl[1]);
-        fetch(stage + 3, ps[1], pl[1]);
-        multiply(buf0);
+        stage_body(buf0, buf1, ps[1], pl[1], stage + 3);
         __syncthreads();
-        stash(buf0, ps[0], pl[0]);
-        fetch(stage + 4, ps[0], pl[0]);
-        multiply(buf1);
+        stage_body(buf1, buf0, ps[0], pl[0], stage + 4);
         __syncthreads();
     }
 
