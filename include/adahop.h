@@ -156,7 +156,9 @@ int adahop_gemm_mx_bf16out(int64_t M, int64_t N, int64_t K, const uint8_t *a_cod
  * The BF16 part uses the original bf16 values with fp32 accumulation and is added in fp32.
  * The workspace holds, at the offsets reported by adahop_gemm_workspace_layout(), the canonical
  * codes and scales of both operands, the extraction mask and the FOID scores, all left in place on
- * return so that a caller can inspect or reuse them.
+ * return so that a caller can inspect or reuse them -- except that with ADAHOP_IHT_OE_K the region of the
+ * scores may come back holding a 16-bit table of the selected channels' positions instead (the quantisers
+ * use it to copy those channels out).
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
     size_t a_codes, a_scales, b_codes, b_scales; /* byte offsets into the workspace */
