@@ -657,6 +657,9 @@ __global__ __launch_bounds__(256) void k_quant_kc16_gather(const uint16_t *__res
 // columns reversed: lane n then holds column 3 - n % 4 when m is odd, and lane n ^ 7 is its stride-64 partner in
 // the same column.  The two MX blocks of a lane lie entirely in its registers (no cross-lane maximum).
 //
+// (A variant with 128 columns per workgroup, 256-byte pieces of the operand's K-rows, runs at the same speed: the
+// kernel is bound by its vector instructions, about 15 per element, as much as by memory.)
+//
 // LDS layout: K-row kk at row index 4 (kk % 64) + kk / 64, 144 bytes per row (128 of data).  The 16 pieces of one
 // transposing read of a half wave (two groups: 16 bytes per row) then start 4 banks apart and cover the 64 banks
 // exactly once; the 16-byte writes of a 16-lane group go to two rows whose banks do not overlap either.
