@@ -823,14 +823,29 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
         uint8_t *crow = codes + o * (K >> 1) + ((k0 + 64 * m) >> 1);
         *reinterpret_cast<uint4 *>(crow) = make_uint4(c[0], c[1], c[2], c[3]);
         *reinterpret_cast<uint4 *>(crow + 16) = make_uint4(c[4], c[5], c[6], c[7]);
-        uint8_t *srow = scales + o * (K >> 5) + ((k0 + 64 * m) >> 5); // (byte stores: the array has no alignment rule)
-        srow[0] = (uint8_t)sc[0];
-        srow[1] = (uint8_t)sc[1];
-        if (sm.out && o < sm.rows) {
-            uint8_t *q = sm.out + ((k0 >> 8) * sm.rows + o) * 8 + 2 * m;
-            q[0] = (uint8_t)sc[0];
-            q[1] = (uint8_t)sc[1];
+    }
+    // The column's 8 scale bytes of this tile sit in the four lanes m = 0 .. 3 of the column, which are 4 apart in
+    // the row of 16 lanes: the lane m = 0 collects them (two DPP shifts) and stores them at once.  Byte stores, four
+    // per lane, were three quarters of the kernel's write requests.
+    // (Lanes with odd m hold the columns of their quad in reverse order: they take their neighbour's bytes first.)
+    const uint32_t own = (uint32_t)sc[0] | ((uint32_t)sc[1] << 8);
+    const uint32_t mirrored = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0x1B /* quad_perm:[3,2,1,0] */, 0xf, 0xf, true);
+    const uint32_t mine = (m & 1) ? mirrored : own;
+    const uint32_t pair = mine | ((uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0x104 /* row_shl:4 */, 0xf, 0xf, true) << 16);
+    const uint32_t upper = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pair, 0x108 /* row_shl:8 */, 0xf, 0xf, true);
+    if (active && m == 0) {
+        uint8_t *srow = scales + o * (K >> 5) + (k0 >> 5);
+        if ((reinterpret_cast<uintptr_t>(srow) & 7) == 0) {
+            *reinterpret_cast<uint2 *>(srow) = make_uint2(pair, upper);
+        } else { // the canonical array has no alignment rule
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                srow[i] = (uint8_t)(pair >> (8 * i));
+                srow[4 + i] = (uint8_t)(upper >> (8 * i));
+            }
         }
+        if (sm.out && o < sm.rows)
+            *reinterpret_cast<uint2 *>(sm.out + ((k0 >> 8) * sm.rows + o) * 8) = make_uint2(pair, upper);
     }
 }
 
