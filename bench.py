@@ -415,6 +415,14 @@ def main():
         extras["iht_quantize_k_strided"] = {"outer": qs.outer, "K": qs.K, "k_contig": qs.k_contig, "ms": qs_ms,
                                             "GBps": 2.53125 * qs.outer * qs.K / (qs_ms * 1e-3) / 1e9, "peak_GBps": 8000.0}
         del codes, scales, cs, ss
+        # the calibration-phase detector (App. A) on the same operand, both layouts: reads the operand once
+        det = {}
+        for name_, op_ in (("k_contig", qx), ("k_strided", qs)):
+            dws = torch.empty(max(int(ah.lib().adahop_detect_pattern_workspace_bytes(__import__("ctypes").byref(op_.c()))), 256),
+                              dtype=torch.uint8, device="cuda")
+            d_ms = time_ms(torch, lambda: ah.adahop_detect_pattern(op_, 2.0, dws), 10)
+            det[name_] = {"ms": d_ms, "GBps": 2.0 * op_.outer * op_.K / (d_ms * 1e-3) / 1e9}
+        extras["detect_pattern"] = {"outer": qx.outer, "K": qx.K, "peak_GBps": 8000.0, **det}
         # the BF16 row / column product alone (gather, skinny product, slice reduction): bound by reading the long
         # operand once; and FOID (scores + top-k) alone
         rowp = next((p for p in prepared if p.g.strategy in (inputs.IHT_OE_ROW, inputs.IHT_OE_COL) and p.g.k > 0), None)

@@ -15,8 +15,9 @@
 //   k_pattern_partial  one pass over the stored matrix S[R][C]: a workgroup takes 256 rows x 512
 //                      columns and writes, per row, its sum / sum of squares over the 512 columns,
 //                      and per column over the 256 rows (no atomics);
-//   k_pattern_finish   one workgroup adds the partials in a fixed order, forms both variance vectors
-//                      and their statistics, and writes the class and the four CV figures.
+//   k_pattern_fold     adds the partials of every row and every column in a fixed order (one thread each);
+//   k_pattern_finish   one workgroup forms both variance vectors and their statistics and writes the class and
+//                      the four CV figures.
 #include "common.h"
 
 namespace adahop {
@@ -43,31 +44,40 @@ __global__ __launch_bounds__(256) void k_pattern_partial(const uint16_t *__restr
     double cs[8], cq[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) cs[j] = cq[j] = 0.0;
-    for (int i = 0; i < PT_ROWS / 4; ++i) {
-        const int64_t r = r0 + w + 4 * i;
-        double rs = 0.0, rq = 0.0;
-        if (r < R && cok) {
-            float e[8];
-            if (c0 + 8 <= C) {
-                const uint4 u = load_once16(S + r * ld + c0);
-                e[0] = bf16_lo(u.x); e[1] = bf16_hi(u.x); e[2] = bf16_lo(u.y); e[3] = bf16_hi(u.y);
-                e[4] = bf16_lo(u.z); e[5] = bf16_hi(u.z); e[6] = bf16_lo(u.w); e[7] = bf16_hi(u.w);
-            } else {
+    const bool whole = c0 + 8 <= C;
+    for (int i0 = 0; i0 < PT_ROWS / 4; i0 += 8) { // eight rows of the wave at a time: their loads are in flight together
+        uint4 u[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) e[j] = c0 + j < C ? bf16_one(S[r * ld + c0 + j]) : 0.0f;
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const double x = (double)e[j], x2 = x * x;
-                rs += x;
-                rq += x2;
-                cs[j] += x;
-                cq[j] += x2;
-            }
+        for (int t = 0; t < 8; ++t) {
+            const int64_t r = r0 + w + 4 * (i0 + t);
+            u[t] = (r < R && whole) ? load_once16(S + r * ld + c0) : make_uint4(0, 0, 0, 0);
         }
-        rs = wave_sum(rs);
-        rq = wave_sum(rq);
-        if (lane == 0 && r < R) rowpart[(int64_t)blockIdx.x * R + r] = make_double2(rs, rq);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int64_t r = r0 + w + 4 * (i0 + t);
+            double rs = 0.0, rq = 0.0;
+            if (r < R && cok) {
+                float e[8];
+                if (whole) {
+                    e[0] = bf16_lo(u[t].x); e[1] = bf16_hi(u[t].x); e[2] = bf16_lo(u[t].y); e[3] = bf16_hi(u[t].y);
+                    e[4] = bf16_lo(u[t].z); e[5] = bf16_hi(u[t].z); e[6] = bf16_lo(u[t].w); e[7] = bf16_hi(u[t].w);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) e[j] = c0 + j < C ? bf16_one(S[r * ld + c0 + j]) : 0.0f;
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const double x = (double)e[j], x2 = x * x;
+                    rs += x;
+                    rq += x2;
+                    cs[j] += x;
+                    cq[j] += x2;
+                }
+            }
+            rs = wave_sum(rs);
+            rq = wave_sum(rq);
+            if (lane == 0 && r < R) rowpart[(int64_t)blockIdx.x * R + r] = make_double2(rs, rq);
+        }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) scol[w][lane * 8 + j] = make_double2(cs[j], cq[j]);
@@ -83,6 +93,26 @@ __global__ __launch_bounds__(256) void k_pattern_partial(const uint16_t *__restr
             colpart[(int64_t)blockIdx.y * C + cg] = a;
         }
     }
+}
+
+// part[i] <- sum over p of part[p * n + i], p ascending, for the rows (i < R, row_parts partials) and the columns.
+// One thread per index, over the whole chip: left to the one workgroup of k_pattern_finish this sum was most of
+// the detector's time (112 partials x 8192 columns x 16 bytes through one compute unit).
+__global__ __launch_bounds__(256) void k_pattern_fold(double2 *__restrict__ rowpart, int row_parts, double2 *__restrict__ colpart,
+                                                      int col_parts, int64_t R, int64_t C)
+{
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    double2 *part = g < R ? rowpart : colpart;
+    const int64_t n = g < R ? R : C, i = g < R ? g : g - R;
+    const int parts = g < R ? row_parts : col_parts;
+    if (i >= n) return;
+    double s = 0.0, q = 0.0;
+    for (int p = 0; p < parts; ++p) {
+        const double2 v = part[(int64_t)p * n + i];
+        s += v.x;
+        q += v.y;
+    }
+    part[i] = make_double2(s, q);
 }
 
 // Statistics of the variance vector of one axis: n entries, entry i = sum over `parts` partials of
@@ -188,8 +218,12 @@ int launch_detect_pattern(const adahop_operand_t &x, double tau, double eps, int
                        static_cast<const uint16_t *>(x.data), x.ld, R, C, rowpart, colpart);
     int rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
-    hipLaunchKernelGGL(k_pattern_finish, dim3(1), dim3(1024), 0, st, rowpart, (int)cb, colpart, (int)rb, R, C,
-                       x.k_contig ? 1 : 0, tau, eps, pattern_out, stats_out);
+    hipLaunchKernelGGL(k_pattern_fold, dim3((unsigned)ceil_div(R + C, 256)), dim3(256), 0, st, rowpart, (int)cb, colpart, (int)rb,
+                       R, C);
+    rc = check_launch();
+    if (rc != ADAHOP_OK) return rc;
+    hipLaunchKernelGGL(k_pattern_finish, dim3(1), dim3(1024), 0, st, rowpart, 1, colpart, 1, R, C, x.k_contig ? 1 : 0, tau, eps,
+                       pattern_out, stats_out);
     return check_launch();
 }
 
