@@ -216,7 +216,7 @@ __device__ __forceinline__ void wave_histogram_private(uint32_t *hist, bool vali
 
 struct topk_shared_t {
     uint32_t hist[TOPK_WAVES + 1][256]; // one per wave, and their sum
-    uint32_t prefix, remaining, count;
+    uint32_t prefix, remaining, count, whole_bin;
     uint32_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
     uint32_t cand[TOPK_CAND];
 };
@@ -224,8 +224,12 @@ struct topk_shared_t {
 // Radix select over NK keys per thread (valid[j] says which exist), digits of 8 bits from bit 24 down to bit
 // LAST_SHIFT: on return `prefix` holds the upper bits of the k-th largest key (k >= 1, at most the number of valid
 // keys) and `remaining` how many keys with exactly these upper bits are among the k largest.  All threads call it.
-template <int NK, int LAST_SHIFT>
-__device__ __forceinline__ void radix_select(topk_shared_t &sh, const uint32_t (&key)[NK], const bool (&valid)[NK], uint32_t k,
+// EARLY: stop at the first digit at which the k largest keys are exactly the keys of the found bin and of the bins
+// above it (well separated outliers: usually the first or second digit): the remaining digits cannot change the
+// selection then.  `prefix` then has zeros below that digit and `remaining` is UINT32_MAX, which says "every key
+// >= prefix is selected"; returns true.
+template <int NK, int LAST_SHIFT, bool EARLY = false>
+__device__ __forceinline__ bool radix_select(topk_shared_t &sh, const uint32_t (&key)[NK], const bool (&valid)[NK], uint32_t k,
                                              uint32_t &prefix, uint32_t &remaining)
 {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -280,13 +284,20 @@ __device__ __forceinline__ void radix_select(topk_shared_t &sh, const uint32_t (
             if (hit && lane == __ffsll((long long)hit) - 1) {
                 sh.prefix = prefix | ((uint32_t)found << shift);
                 sh.remaining = remaining - cum_at;
+                sh.whole_bin = total[found] == remaining - cum_at ? 1u : 0u;
             }
         }
         __syncthreads();
         prefix = sh.prefix;
         remaining = sh.remaining;
         pmask |= 255u << shift;
+        if (EARLY && shift > LAST_SHIFT && sh.whole_bin) { // (uniform: every thread reads the same word)
+            remaining = 0xffffffffu;
+            __syncthreads(); // the next use of the histograms and of sh.* must not overtake this read
+            return true;
+        }
     }
+    return false;
 }
 
 __global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restrict__ scores, int dim, int k,
@@ -366,11 +377,12 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restri
                 cv[q] = i < count;
                 ck[q] = cv[q] ? sh.cand[i] : 0u;
             }
-            radix_select<TOPK_CAND_PER_THREAD, 0>(sh, ck, cv, (uint32_t)k, T, remaining);
+            // (stopped early, the threshold may lie below T0, where keys that are no candidates begin)
+            if (radix_select<TOPK_CAND_PER_THREAD, 0, true>(sh, ck, cv, (uint32_t)k, T, remaining)) T = max(T, T0);
             selected = true;
         }
     }
-    if (!selected) radix_select<TOPK_REG_KEYS, 0>(sh, key, in, (uint32_t)k, T, remaining); // the general way
+    if (!selected) radix_select<TOPK_REG_KEYS, 0, true>(sh, key, in, (uint32_t)k, T, remaining); // the general way
 
     // 3. ordered compaction, as in k_topk
     uint32_t gt = 0, eq = 0;
