@@ -205,17 +205,23 @@ def test_topk_selection_paths_bit_exact(ah):
     """The exact top-k on score vectors chosen to take each way through the selection kernel: a short candidate list
     behind the threshold from the thread maxima; more candidates than the list holds (all scores equal, or equal in
     their upper 16 bits); k above the number of threads; fewer key-owning threads than k; k = dim; dims just above
-    and below the list size.  Scores come from rows that are constant except for two entries, so that their fp32
+    and below the list size; well separated outliers, with k at, below and above their number (the select stops
+    early, also with a threshold below that of the candidate list).  Scores come from rows that are constant except for two entries, so that their fp32
     variance scores can be steered: x = (a, -a, 0, ...) scores 2 a^2 exactly."""
     rng = np.random.default_rng(77)
     cases = []
     for dim, ks, kind in ((28672, (287, 574, 1, 1024, 1025, 3000, 28672), "random"), (28672, (287, 5000), "equal"),
                           (28672, (300,), "two-level"), (4097, (41, 4097), "random"), (4096, (41, 1500), "random"),
-                          (9000, (90, 1100), "few-big"), (32768, (328, 640), "random"), (1090, (1089, 1024, 70), "random")):
+                          (9000, (90, 1100), "few-big"), (32768, (328, 640), "random"), (1090, (1089, 1024, 70), "random"),
+                          (16384, (164, 100, 165, 200), "separated"), (3000, (30, 29, 31), "separated")):
         if kind == "random":
             a = np.abs(rng.standard_normal(dim)).astype(np.float32) + 0.5
         elif kind == "equal":
             a = np.full(dim, 1.5, dtype=np.float32)
+        elif kind == "separated":            # 1 % of the scores far above the rest and spread over several leading
+            a = rng.uniform(0.5, 1.5, dim).astype(np.float32)  # digits: the select stops at its first or second digit
+            big = rng.permutation(dim)[:ks[0]]
+            a[big] = rng.uniform(8.0, 64.0, ks[0]).astype(np.float32)
         elif kind == "two-level":            # upper 16 bits of every score equal; they differ further down
             a = (1.0 + rng.integers(0, 60, dim) * 2.0 ** -9).astype(np.float32)
         else:                                # a handful of large scores among many equal small ones
