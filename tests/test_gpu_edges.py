@@ -70,6 +70,21 @@ def test_smallest_shapes(ah, layouts):
             whole(ah, A, B, layouts[0], layouts[1], strategy, b, 0)
 
 
+@pytest.mark.parametrize("layouts", [(True, True), (True, False), (False, True), (False, False)])
+def test_smallest_shapes_with_extraction(ah, layouts):
+    """One extracted row / column / K-channel (and all but one of them) on operands far smaller than any tile of the
+    BF16 product kernels: a single workgroup whose loads past the last row repeat that row, a K of half a pipeline
+    stage, a long side of one row."""
+    rng = np.random.default_rng(4)
+    for M, N, K in ((1, 1, 32), (1, 9, 64), (7, 1, 32), (3, 5, 256), (9, 17, 96), (260, 3, 160)):
+        A = bf16(rng.standard_normal((M, K)) * np.where(rng.random((M, 1)) < 0.3, 50.0, 1.0))
+        B = bf16(rng.standard_normal((N, K)) * 0.02)
+        for strategy, dim in ((inputs.IHT_OE_ROW, M), (inputs.IHT_OE_COL, N), (inputs.IHT_OE_K, K)):
+            for k in sorted({1, max(dim - 1, 1)}):
+                say("smallest with extraction", (M, N, K), layouts, inputs.STRATEGY_NAMES[strategy], k)
+                whole(ah, A, B, layouts[0], layouts[1], strategy, 32, k)
+
+
 @pytest.mark.parametrize("layouts", [(True, True), (False, False)])
 def test_everything_extracted_is_the_bf16_product(ah, layouts):
     """k equal to the whole extracted dimension: the residual is all zero (codes 0, scales 0) and C is the BF16 product
