@@ -201,9 +201,12 @@ def workload_summary(ah, torch, inputs, name, k_pct=1.0):
             b = time_ms(torch, lambda: run_gemm(ah, p, ws, strategy=inputs.IHT, k=0), 5)
             per.append((100.0 * (a - b) / b, p.g.name))
         worst = {"pct": max(per)[0], "gemm": max(per)[1], "mean_pct": sum(x for x, _ in per) / len(per)}
+    stages = [stage_times(ah, torch, inputs, p, ws) for p in prepared] if name == "paper-table3" else None
     out = {"workload": desc, "gemms": len(prepared), "step_ms": t, "tflops": flops / t / 1e9,
            "pct_mxfp4_peak": 100.0 * flops / t / 1e9 / MXFP4_PEAK_TFLOPS, "step_ms_iht_only": t_iht,
            "tflops_iht_only": flops / t_iht / 1e9, "step_ms_bf16_hipblaslt": t_bf, "speedup_vs_bf16": t_bf / t}
+    if stages:
+        out["per_stage_ms"] = stages
     if worst:
         out["oe_overhead_pct_worst"] = worst
     elif oe:
@@ -469,6 +472,10 @@ def main():
                                   "ms": t, "ms_iht_only": t0, "oe_overhead_pct": 100.0 * (t - t0) / t0})
             extras["cfg4_k_sweep"] = sweep
             extras["per_stage_ms"] = [stage_times(ah, torch, inputs, p, ws) for p in prepared[:2]]
+        elif args.workload == "paper-table3":
+            # the stages of the paper's kernel latency table (right): FOID | IHT and quantise | fused product with the
+            # BF16 outlier part and its scatter
+            extras["per_stage_ms"] = [stage_times(ah, torch, inputs, p, ws) for p in prepared]
         out["extras"] = extras
         if args.workload == "cfg4" and not args.no_other_workloads:
             del prepared, cache, pool, ws, big, ac, asc, bc, bsc, gemm_ws
