@@ -563,10 +563,11 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
     const int64_t k0 = (int64_t)unit * 256, kk = k0 + plan.chunk * 8;
 
     uint4 r0 = make_uint4(0, 0, 0, 0), r1 = make_uint4(0, 0, 0, 0);
-    if (active && !(zero_outer && zero_outer[row])) {
+    if (active) { // the row's mask byte travels with the data (1 % of the rows are read for nothing) instead of ahead of it
         const uint16_t *src = x + row * ld + kk;
         r0 = load_once16(src);
         r1 = load_once16(src + 128);
+        if (zero_outer && zero_outer[row]) r0 = r1 = make_uint4(0, 0, 0, 0);
     }
     float w0[8] = {bf16_lo(r0.x), bf16_hi(r0.x), bf16_lo(r0.y), bf16_hi(r0.y),
                    bf16_lo(r0.z), bf16_hi(r0.z), bf16_lo(r0.w), bf16_hi(r0.w)};
