@@ -734,16 +734,22 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
                 if ((z >> (8 * c)) & 0xffu) cm[c >> 1] &= (c & 1) ? 0x0000ffffu : 0xffff0000u;
         }
         uint4 v[8];
+        uint32_t zk = 0; // bit it: the lane's K-row of pass it is masked out (looked at when the row goes to LDS, so
+                         // that neither these loads nor the data loads wait for one another)
+        if (zero_k) {
+#pragma unroll
+            for (int it = 0; it < 8; ++it) zk |= (zero_k[k0 + it * 32 + rw] ? 1u : 0u) << it;
+        }
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int64_t kk = k0 + it * 32 + rw;
             v[it] = ok ? load_once16(x + kk * ld + oc) : make_uint4(0, 0, 0, 0);
-            if (zero_k && zero_k[kk]) v[it] = make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int row = it * 32 + rw; // K-row within the tile; bit 6 = bit 1 of it
-            uint4 u = make_uint4(v[it].x & cm[0], v[it].y & cm[1], v[it].z & cm[2], v[it].w & cm[3]);
+            const uint32_t kz = ((zk >> it) & 1u) ? 0u : ~0u;
+            uint4 u = make_uint4(v[it].x & cm[0] & kz, v[it].y & cm[1] & kz, v[it].z & cm[2] & kz, v[it].w & cm[3] & kz);
             if (it & 2) u = make_uint4(rot16(u.y), rot16(u.x), rot16(u.w), rot16(u.z)); // groups of 4 columns reversed
             *reinterpret_cast<uint4 *>(tile + (4 * (row & 63) + (row >> 6)) * KT_PITCH + cg * 16) = u;
         }
