@@ -307,6 +307,47 @@ __global__ __launch_bounds__(256) void k_oe_reduce(const float *__restrict__ P, 
         C[l * ldc + o] = v;
 }
 
+// The same on 4 consecutive long-side indices per thread (Lo % 4 == 0; for ROWS also 16-byte / 8-byte aligned rows of
+// C): 16-byte reads of the partials, and for ROWS one 16-byte (fp32) or 8-byte (bf16) store.
+__device__ __forceinline__ uint16_t bf16_rne(float s)
+{
+    const uint32_t u = __float_as_uint(s);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+template <bool ROWS, typename OUT>
+__global__ __launch_bounds__(256) void k_oe_reduce4(const float *__restrict__ P, int nslice, int64_t rows_all, int64_t Lo,
+                                                    const int32_t *__restrict__ idx, int k, OUT *__restrict__ C, int64_t ldc)
+{
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x, per = Lo >> 2;
+    if (g >= (int64_t)k * per) return;
+    const int64_t t = g / per, l = (g - t * per) * 4;
+    float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int i = 0; i < nslice; ++i) {
+        const float4 v = *reinterpret_cast<const float4 *>(P + ((int64_t)i * rows_all + t) * Lo + l);
+        s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+    }
+    const int64_t o = idx[t];
+    if constexpr (ROWS) {
+        if constexpr (sizeof(OUT) == 4) {
+            *reinterpret_cast<float4 *>(C + o * ldc + l) = s;
+        } else {
+            const uint32_t lo = (uint32_t)bf16_rne(s.x) | ((uint32_t)bf16_rne(s.y) << 16);
+            const uint32_t hi = (uint32_t)bf16_rne(s.z) | ((uint32_t)bf16_rne(s.w) << 16);
+            *reinterpret_cast<uint2 *>(C + o * ldc + l) = make_uint2(lo, hi);
+        }
+    } else {
+        const float e[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (sizeof(OUT) == 4)
+                C[(l + j) * ldc + o] = e[j];
+            else
+                C[(l + j) * ldc + o] = bf16_rne(e[j]);
+        }
+    }
+}
+
 struct skinny_plan_t {
     int rt, groups, nslice, stages_per_slice;
     int64_t rows_all;
@@ -487,6 +528,17 @@ int launch_oe_rowcol(const adahop_operand_t &A, const adahop_operand_t &B, int k
     const unsigned rblocks = (unsigned)ceil_div((int64_t)k * Lo, 256);
     auto reduce = [&](auto *c) {
         typedef typename std::remove_pointer<decltype(c)>::type out_t;
+        // four long-side indices per thread where rows of the partials (and, for rows of C, of C) are 16-byte pieces
+        if (Lo % 4 == 0 && (!rows || (ldc % 4 == 0 && aligned(c, 4 * sizeof(out_t))))) {
+            const unsigned b4 = (unsigned)ceil_div((int64_t)k * (Lo >> 2), 256);
+            if (rows)
+                hipLaunchKernelGGL((k_oe_reduce4<true, out_t>), dim3(b4), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx, k, c,
+                                   ldc);
+            else
+                hipLaunchKernelGGL((k_oe_reduce4<false, out_t>), dim3(b4), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx, k,
+                                   c, ldc);
+            return;
+        }
         if (rows)
             hipLaunchKernelGGL((k_oe_reduce<true, out_t>), dim3(rblocks), dim3(256), 0, st, P, p.nslice, p.rows_all, Lo, idx,
                                k, c, ldc);
