@@ -14,10 +14,11 @@
  *   - All data pointers are DEVICE pointers owned by the caller; the library allocates nothing
  *     and never synchronises: work is queued on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and the call returns.  No data is kept between calls.  The only state is
- *     a per-device "configured" flag: the first call on a device that reaches a kernel with a
- *     large LDS footprint sets that kernel's function attribute and reads the device's
- *     compute-unit count (host-side HIP calls, no allocation, no synchronisation); make that
- *     first call outside a stream capture.
+ *     a per-device "configured" flag per kernel family: the first call on a device that reaches a
+ *     family with a large LDS footprint sets the function attributes of all its kernels and reads
+ *     the device's compute-unit count (host-side HIP calls, no allocation, no synchronisation).
+ *     adahop_prepare_device() does this for every family at once; call it (or make the first
+ *     calls) outside a stream capture.
  *   - Sizes: 1 <= outer <= 2^21 and 32 <= K <= 2^21 for every operand (M, N, K of a product
  *     alike), and outer * K < 2^35; anything larger is ADAHOP_E_INVALID_ARG.
  *   - Outputs are fully overwritten.  Inputs are not modified.
@@ -305,6 +306,13 @@ int adahop_last_hip_error(void);
 const char *adahop_status_string(int status);
 /* ABI version: bumped on any incompatible change. */
 int adahop_abi_version(void);
+
+/* One-time set-up of the current device for every kernel of the library (function attributes, compute-unit
+ * count, address of the built-in scratch of adahop_foid_topk_noalloc): host-side HIP calls only, nothing is
+ * queued or allocated.  Optional -- every entry point does the part it needs at its first call on a device --
+ * but a caller that captures streams into graphs calls it once per device beforehand, so that no later call has
+ * set-up left to do.  Returns ADAHOP_OK or ADAHOP_E_HIP. */
+int adahop_prepare_device(void);
 
 /* =============================================================================================
  * DIAGNOSTICS -- not part of the method and not needed by a user of the product path.

@@ -22,7 +22,7 @@ EXPORTS = ["adahop_quantize_mx", "adahop_iht_quantize", "adahop_foid_topk", "ada
            "adahop_oht_quantize", "adahop_oht_inverse", "adahop_iht_quantize_sr",
            "adahop_gemm_workspace_layout", "adahop_gemm_workspace_bytes", "adahop_gemm", "adahop_oe_gather_bytes",
            "adahop_oe_gemm_bf16", "adahop_detect_pattern_workspace_bytes", "adahop_detect_pattern",
-           "adahop_select_strategy", "adahop_vote_pattern", "adahop_probe_mfma_rate", "adahop_debug_force_gemm_kernel", "adahop_last_hip_error", "adahop_status_string",
+           "adahop_select_strategy", "adahop_vote_pattern", "adahop_probe_mfma_rate", "adahop_debug_force_gemm_kernel", "adahop_prepare_device", "adahop_last_hip_error", "adahop_status_string",
            "adahop_abi_version"]
 
 
@@ -325,6 +325,11 @@ def adahop_probe_mfma_rate(random_operands, workgroups, iters, sink, stream=None
                                         _stream(stream)),
            "adahop_probe_mfma_rate")
     return 2.0 * 65536 * 16 * iters * 4 * workgroups
+
+
+def adahop_prepare_device():
+    """One-time set-up of the current device for every kernel (call before capturing streams into graphs)."""
+    _check(lib().adahop_prepare_device(), "adahop_prepare_device")
 
 
 def adahop_debug_force_gemm_kernel(which):

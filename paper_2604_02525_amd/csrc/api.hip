@@ -60,6 +60,17 @@ int adahop_debug_force_gemm_kernel(int which)
     return ADAHOP_OK;
 }
 
+int adahop_prepare_device(void)
+{
+    int rc;
+    if ((rc = configure_gemm_mx(nullptr)) != ADAHOP_OK || (rc = configure_gemm_mx_dual(nullptr)) != ADAHOP_OK ||
+        (rc = configure_oe_rowcol()) != ADAHOP_OK || (rc = configure_oht()) != ADAHOP_OK ||
+        (rc = configure_quantizers()) != ADAHOP_OK)
+        return rc;
+    float *scores = nullptr;
+    return foid_static_scores(&scores); // the address of the built-in score scratch, looked up once per device
+}
+
 int adahop_last_hip_error(void) { return g_last_hip_error; }
 
 const char *adahop_status_string(int status)

@@ -27,6 +27,15 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 int validate_operand(const adahop_operand_t *x);
 bool valid_iht_block(int b);
 
+// One-time set-up per device and kernel family: function attributes (LDS sizes above the default) for every
+// instance of the family, and the compute-unit count for the persistent kernels.  Host-side calls only; the
+// launchers call them, adahop_prepare_device calls them all.
+int configure_gemm_mx(int *ncu_out);
+int configure_gemm_mx_dual(int *ncu_out);
+int configure_oe_rowcol();
+int configure_oht();
+int configure_quantizers();
+
 // Launchers (one per kernel family); each validates nothing and returns a status.
 // Stage-major copy of the scales for the tiled GEMM kernel (see gemm_mx_tiled_part): [K/256][rows][8].
 struct scales_sm_t {

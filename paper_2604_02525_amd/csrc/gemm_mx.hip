@@ -643,6 +643,34 @@ uint8_t *gemm_mx_scales_sm(void *workspace, int64_t M, int64_t K, int which)
     return which == 0 ? a_sm : a_sm + align_up((size_t)M * (K / 32), 256);
 }
 
+// Once per device: the compute-unit count, and for every instance of the tiled kernel the LDS size (more than a
+// launch may ask for by default).  Host-side calls, nothing queued.
+int configure_gemm_mx(int *ncu_out)
+{
+    static device_once_t once;
+    static std::atomic<int> cu_count[64];
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
+    if (rc != ADAHOP_OK) return rc;
+    int ncu = dev >= 0 && dev < 64 ? cu_count[dev].load(std::memory_order_relaxed) : 0;
+    if (once.need(dev) || ncu == 0) {
+        rc = check_hip(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+        if (rc != ADAHOP_OK) return rc;
+        const void *kernels[4] = {reinterpret_cast<const void *>(&k_gemm_mx_tile256<false, float>),
+                                  reinterpret_cast<const void *>(&k_gemm_mx_tile256<true, float>),
+                                  reinterpret_cast<const void *>(&k_gemm_mx_tile256<false, uint16_t>),
+                                  reinterpret_cast<const void *>(&k_gemm_mx_tile256<true, uint16_t>)};
+        for (const void *f : kernels) {
+            rc = check_hip(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
+            if (rc != ADAHOP_OK) return rc;
+        }
+        if (dev >= 0 && dev < 64) cu_count[dev].store(ncu, std::memory_order_relaxed);
+        once.mark(dev);
+    }
+    if (ncu_out) *ncu_out = ncu;
+    return ADAHOP_OK;
+}
+
 namespace {
 
 template <typename OUT>
@@ -664,26 +692,9 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     gemm_mx_tiled_part(M, N, K, kpad, a_scales, b_scales, C, ldc, sizeof(OUT) == 2, &Mi, &Ni);
     if (Mi == 0) return generic(M, N, a_codes, a_scales, b_codes, b_scales, C, Ag, Bg);
 
-    int dev = 0;
-    int rc0 = check_hip(hipGetDevice(&dev));
+    int ncu = 0;
+    const int rc0 = configure_gemm_mx(&ncu); // once per device: the compute-unit count and the kernels' LDS size
     if (rc0 != ADAHOP_OK) return rc0;
-    // Once per output type and device: the compute-unit count, and the kernels' LDS size (more than a launch may
-    // ask for by default).
-    static device_once_t once;
-    static std::atomic<int> cu_count[64];
-    int ncu = dev >= 0 && dev < 64 ? cu_count[dev].load(std::memory_order_relaxed) : 0;
-    if (once.need(dev) || ncu == 0) {
-        rc0 = check_hip(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
-        if (rc0 != ADAHOP_OK) return rc0;
-        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<false, OUT>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
-        if (rc != ADAHOP_OK) return rc;
-        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mx_tile256<true, OUT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS_BYTES));
-        if (rc != ADAHOP_OK) return rc;
-        if (dev >= 0 && dev < 64) cu_count[dev].store(ncu, std::memory_order_relaxed);
-        once.mark(dev);
-    }
     ncu = ncu / 8 * 8; // keep a workgroup's tiles on one XCD
     if (ncu < 8) ncu = 8;
     // scales of the tiled part, stage-major, in the caller's workspace (sm_ready bit 0 / 1: the quantiser of A / B

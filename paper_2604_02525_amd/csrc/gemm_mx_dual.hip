@@ -377,14 +377,14 @@ bool gemm_mx_dual_eligible(int64_t M, int64_t N, int64_t K)
 }
 
 // Launches the kernel on rows [0, Mi), columns [0, Ni) (multiples of 256 and 128); scales stage-major over those rows.
-int launch_gemm_mx_dual(int64_t Mi, int64_t Ni, int64_t K, const uint8_t *a_codes, const uint8_t *a_sm,
-                        const uint8_t *b_codes, const uint8_t *b_sm, float *C, int64_t ldc, hipStream_t st)
+// Once per device: the compute-unit count and the kernel's LDS size.  Host-side calls, nothing queued.
+int configure_gemm_mx_dual(int *ncu_out)
 {
+    static device_once_t once;
+    static std::atomic<int> cu_count[64];
     int dev = 0;
     int rc = check_hip(hipGetDevice(&dev));
     if (rc != ADAHOP_OK) return rc;
-    static device_once_t once;
-    static std::atomic<int> cu_count[64];
     int ncu = dev >= 0 && dev < 64 ? cu_count[dev].load(std::memory_order_relaxed) : 0;
     if (once.need(dev) || ncu == 0) {
         rc = check_hip(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
@@ -395,6 +395,16 @@ int launch_gemm_mx_dual(int64_t Mi, int64_t Ni, int64_t K, const uint8_t *a_code
         if (dev >= 0 && dev < 64) cu_count[dev].store(ncu, std::memory_order_relaxed);
         once.mark(dev);
     }
+    if (ncu_out) *ncu_out = ncu;
+    return ADAHOP_OK;
+}
+
+int launch_gemm_mx_dual(int64_t Mi, int64_t Ni, int64_t K, const uint8_t *a_codes, const uint8_t *a_sm,
+                        const uint8_t *b_codes, const uint8_t *b_sm, float *C, int64_t ldc, hipStream_t st)
+{
+    int ncu = 0;
+    int rc = configure_gemm_mx_dual(&ncu);
+    if (rc != ADAHOP_OK) return rc;
     ncu = ncu / 8 * 8;
     if (ncu < 8) ncu = 8;
     const int tiles_m = (int)(Mi / dual::TM), tiles_n = (int)(Ni / dual::TN);

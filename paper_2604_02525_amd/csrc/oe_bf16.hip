@@ -377,21 +377,21 @@ skinny_plan_t plan_skinny(int64_t Lo, int64_t K, int k)
     return p;
 }
 
+template <int RT, bool LONG_KC> constexpr size_t skinny_lds_bytes() { return 2 * (RT * 32 * SK_PITCH + SK_L_ELEMS) * sizeof(uint16_t); }
+
+template <int RT, bool LONG_KC> int allow_skinny_lds()
+{
+    return check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oe_skinny<RT, LONG_KC>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)skinny_lds_bytes<RT, LONG_KC>()));
+}
+
 template <int RT, bool LONG_KC>
 int launch_skinny_as(dim3 grid, hipStream_t st, const uint16_t *Sg, const uint16_t *L, int64_t ldl, int64_t Lo, int64_t K,
                      int sps, float *P, int64_t rows_all)
 {
-    constexpr size_t lds = 2 * (RT * 32 * SK_PITCH + SK_L_ELEMS) * sizeof(uint16_t);
-    static device_once_t once; // more LDS than a launch may ask for by default: allowed once per device
-    int dev = 0;
-    int rc = check_hip(hipGetDevice(&dev));
+    const int rc = configure_oe_rowcol(); // more LDS than a launch may ask for by default: allowed once per device
     if (rc != ADAHOP_OK) return rc;
-    if (once.need(dev)) {
-        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oe_skinny<RT, LONG_KC>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        if (rc != ADAHOP_OK) return rc;
-        once.mark(dev);
-    }
+    constexpr size_t lds = skinny_lds_bytes<RT, LONG_KC>();
     hipLaunchKernelGGL((k_oe_skinny<RT, LONG_KC>), grid, dim3(256), lds, st, Sg, L, ldl, Lo, K, sps, P, rows_all);
     return check_launch();
 }
@@ -486,6 +486,21 @@ int launch_gather_k(const adahop_operand_t &x, const int32_t *idx, int k, int kp
     hipLaunchKernelGGL(k_gather_k, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st,
                        static_cast<const uint16_t *>(x.data), x.ld, x.k_contig, x.outer, idx, k, kpad, out);
     return check_launch();
+}
+
+// Every instance of the row / column product kernel, once per device (host-side calls, nothing queued).
+int configure_oe_rowcol()
+{
+    static device_once_t once;
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
+    if (rc != ADAHOP_OK || !once.need(dev)) return rc;
+    if ((rc = allow_skinny_lds<2, true>()) != ADAHOP_OK || (rc = allow_skinny_lds<2, false>()) != ADAHOP_OK ||
+        (rc = allow_skinny_lds<4, true>()) != ADAHOP_OK || (rc = allow_skinny_lds<4, false>()) != ADAHOP_OK ||
+        (rc = allow_skinny_lds<6, true>()) != ADAHOP_OK || (rc = allow_skinny_lds<6, false>()) != ADAHOP_OK)
+        return rc;
+    once.mark(dev);
+    return ADAHOP_OK;
 }
 
 size_t oe_rowcol_workspace_bytes(int64_t M, int64_t N, int64_t K, int kind, int k)

@@ -208,42 +208,37 @@ __global__ __launch_bounds__(256) void k_oht_inverse(float *__restrict__ C, int6
                                     C + m0 * ldc + n0 + tid % OHT_TN, ldc);
 }
 
+template <int B> constexpr size_t oht_quant_lds() { return (size_t)B * OHT_KP * sizeof(float); }
+template <int B> constexpr size_t oht_inverse_lds() { return (size_t)B * OHT_NP * sizeof(float); }
+
+template <int B> int allow_oht_lds()
+{
+    int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_quant<B>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)oht_quant_lds<B>()));
+    if (rc != ADAHOP_OK) return rc;
+    rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)oht_inverse_lds<B>()));
+    if (rc != ADAHOP_OK) return rc;
+    return check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B, false>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)oht_inverse_lds<B>()));
+}
+
 template <int B> int launch_quant(const adahop_operand_t &x, uint8_t *codes, uint8_t *scales, hipStream_t st)
 {
-    const size_t lds = (size_t)B * OHT_KP * sizeof(float);
-    // more LDS than a launch may ask for by default (B = 128): set once per device
-    static device_once_t once;
-    int dev = 0;
-    int rc = check_hip(hipGetDevice(&dev));
+    const int rc = configure_oht(); // more LDS than a launch may ask for by default (B = 128): allowed once per device
     if (rc != ADAHOP_OK) return rc;
-    if (once.need(dev)) {
-        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_quant<B>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        if (rc != ADAHOP_OK) return rc;
-        once.mark(dev);
-    }
     const dim3 grid((unsigned)ceil_div(x.K, OHT_TK), (unsigned)(x.outer / B));
-    hipLaunchKernelGGL(k_oht_quant<B>, grid, dim3(256), lds, st, static_cast<const uint16_t *>(x.data), x.outer, x.K, x.ld,
-                       x.k_contig, codes, scales);
+    hipLaunchKernelGGL(k_oht_quant<B>, grid, dim3(256), oht_quant_lds<B>(), st, static_cast<const uint16_t *>(x.data), x.outer,
+                       x.K, x.ld, x.k_contig, codes, scales);
     return check_launch();
 }
 
 template <int B, bool VEC> int launch_inverse_as(float *C, int64_t M, int64_t N, int64_t ldc, hipStream_t st)
 {
-    const size_t lds = (size_t)B * OHT_NP * sizeof(float);
-    // more LDS than a launch may ask for by default (B = 128): set once per device
-    static device_once_t once;
-    int dev = 0;
-    int rc = check_hip(hipGetDevice(&dev));
+    const int rc = configure_oht();
     if (rc != ADAHOP_OK) return rc;
-    if (once.need(dev)) {
-        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B, VEC>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        if (rc != ADAHOP_OK) return rc;
-        once.mark(dev);
-    }
     const dim3 grid((unsigned)ceil_div(N, OHT_TN), (unsigned)(M / B));
-    hipLaunchKernelGGL((k_oht_inverse<B, VEC>), grid, dim3(256), lds, st, C, M, N, ldc);
+    hipLaunchKernelGGL((k_oht_inverse<B, VEC>), grid, dim3(256), oht_inverse_lds<B>(), st, C, M, N, ldc);
     return check_launch();
 }
 
@@ -254,6 +249,20 @@ template <int B> int launch_inverse(float *C, int64_t M, int64_t N, int64_t ldc,
 }
 
 } // namespace
+
+// Every OHT kernel instance, once per device (host-side calls, nothing queued).
+int configure_oht()
+{
+    static device_once_t once;
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
+    if (rc != ADAHOP_OK || !once.need(dev)) return rc;
+    if ((rc = allow_oht_lds<32>()) != ADAHOP_OK || (rc = allow_oht_lds<64>()) != ADAHOP_OK ||
+        (rc = allow_oht_lds<128>()) != ADAHOP_OK)
+        return rc;
+    once.mark(dev);
+    return ADAHOP_OK;
+}
 
 bool valid_oht_block(int b) { return b == 32 || b == 64 || b == 128; }
 

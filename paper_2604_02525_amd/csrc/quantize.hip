@@ -902,6 +902,21 @@ int launch_kc(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, u
     return check_launch();
 }
 
+template <int B> constexpr size_t ks_lds_bytes()
+{
+    return ks_cfg<B>::NCH > 1 ? (size_t)ks_cfg<B>::NW * 32 * 64 * sizeof(float2) : 0;
+}
+
+template <int B> int allow_ks_lds()
+{
+    if (ks_lds_bytes<B>() <= 48 * 1024) return ADAHOP_OK;
+    int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_quant_ks<B, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)ks_lds_bytes<B>()));
+    if (rc != ADAHOP_OK) return rc;
+    return check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_quant_ks<B, true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)ks_lds_bytes<B>()));
+}
+
 template <int B, bool SR>
 int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, uint8_t *codes, uint8_t *scales,
               sr_key_t key, scales_sm_t sm, hipStream_t st)
@@ -914,18 +929,10 @@ int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, u
     }
     constexpr int NW = ks_cfg<B>::NW;
     constexpr int NCH = ks_cfg<B>::NCH;
-    const size_t lds = NCH > 1 ? (size_t)NW * 32 * 64 * sizeof(float2) : 0;
-    if (lds > 48 * 1024) { // more LDS than a launch may ask for by default: set once per device
-        static device_once_t once;
-        int dev = 0;
-        int rc = check_hip(hipGetDevice(&dev));
+    const size_t lds = ks_lds_bytes<B>();
+    if (lds > 48 * 1024) { // more LDS than a launch may ask for by default: allowed once per device
+        const int rc = configure_quantizers();
         if (rc != ADAHOP_OK) return rc;
-        if (once.need(dev)) {
-            rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_quant_ks<B, SR>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            if (rc != ADAHOP_OK) return rc;
-            once.mark(dev);
-        }
     }
     dim3 grid((unsigned)ceil_div(x.outer, 128), (unsigned)ceil_div(x.K / 32, NW));
     hipLaunchKernelGGL((k_quant_ks<B, SR>), grid, dim3(NW * 64), lds, st, static_cast<const uint16_t *>(x.data),
@@ -954,6 +961,21 @@ int dispatch_block(const adahop_operand_t &x, int b, const uint8_t *zo, const ui
 }
 
 } // namespace
+
+// The instances of the general K-strided quantiser that need more LDS than the default, once per device (host-side
+// calls, nothing queued).
+int configure_quantizers()
+{
+    static device_once_t once;
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
+    if (rc != ADAHOP_OK || !once.need(dev)) return rc;
+    if ((rc = allow_ks_lds<0>()) != ADAHOP_OK || (rc = allow_ks_lds<32>()) != ADAHOP_OK || (rc = allow_ks_lds<64>()) != ADAHOP_OK ||
+        (rc = allow_ks_lds<128>()) != ADAHOP_OK || (rc = allow_ks_lds<256>()) != ADAHOP_OK)
+        return rc;
+    once.mark(dev);
+    return ADAHOP_OK;
+}
 
 // The kernels for K % 256 == 0 (K / 256 is a grid dimension of the K-strided one) are the ones that also write
 // the stage-major copy of the scales.

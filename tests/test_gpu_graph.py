@@ -29,6 +29,13 @@ def ah():
     return binding
 
 
+def test_prepare_device_is_idempotent(ah):
+    """The one-time set-up a capturing caller makes beforehand: succeeds, also when repeated or when entry points
+    have already done their own part."""
+    ah.adahop_prepare_device()
+    ah.adahop_prepare_device()
+
+
 @pytest.mark.parametrize("strategy,k", [(inputs.IHT, 0), (inputs.IHT_OE_K, 6), (inputs.IHT_OE_ROW, 5), (inputs.IHT_OE_COL, 4)])
 def test_whole_path_replays_from_a_graph(ah, strategy, k):
     M, N, K, b = 512, 384, 1024, 128
