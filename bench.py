@@ -41,6 +41,9 @@ def parse():
     p.add_argument("--dominant-kernel-only", action="store_true",
                    help="profiling aid: time only the FP4 GEMM of the largest product (the roofline object); the "
                         "whole-step figures of the JSON line are then absent")
+    p.add_argument("--quantizer-only", action="store_true",
+                   help="profiling aid: time only the IHT + MXFP4 quantiser on the largest product's B operand, read "
+                        "K-contiguous and K-strided, with the workload's transform block and with block 32")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run one plain 1 GiB device-to-device copy (reference reading for rocprofv3's "
                         "FETCH_SIZE / WRITE_SIZE counters)")
@@ -253,6 +256,27 @@ def main():
     def step():
         for p in prepared:
             run_gemm(ah, p, ws)
+
+    if args.quantizer_only:
+        big = max(prepared, key=lambda p: p.flops)
+        res = []
+        for op in (big.B, ah.Operand(big.B.tensor, not big.B.k_contig)):
+            codes = torch.empty((op.outer, op.K // 2), dtype=torch.uint8, device="cuda")
+            scales = torch.empty((op.outer, op.K // 32), dtype=torch.uint8, device="cuda")
+            for b in sorted({big.g.iht_block, 32}, reverse=True):
+                ms = time_ms(torch, lambda: ah.adahop_iht_quantize(op, b, None, None, codes, scales), max(5, args.steps), 2)
+                res.append({"outer": op.outer, "K": op.K, "k_contig": bool(op.k_contig), "iht_block": b, "ms": ms,
+                            "GBps": 2.53125 * op.outer * op.K / (ms * 1e-3) / 1e9})
+        out = {"metric": "IHT + MXFP4 quantiser, algorithmic GB/s (2.53125 B per element)", "unit": "GB/s", "peak_GBps": 8000.0,
+               "n_gpus": 1, "data": "synthetic", "config": {"workload": desc}, "runs": res}
+        if args.copy_calibration:
+            src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+            dst = torch.empty_like(src)
+            dst.copy_(src)
+            torch.cuda.synchronize()
+            out["copy_calibration_bytes"] = src.numel() * 4
+        print(json.dumps(out))
+        return 0
 
     if args.dominant_kernel_only:
         wall_ms = ms_per_step = value = None
