@@ -65,7 +65,7 @@ int adahop_prepare_device(void)
     int rc;
     if ((rc = configure_gemm_mx(nullptr)) != ADAHOP_OK || (rc = configure_gemm_mx_dual(nullptr)) != ADAHOP_OK ||
         (rc = configure_oe_rowcol()) != ADAHOP_OK || (rc = configure_oht()) != ADAHOP_OK ||
-        (rc = configure_quantizers()) != ADAHOP_OK)
+        (rc = configure_quantizers()) != ADAHOP_OK || (rc = configure_foid()) != ADAHOP_OK)
         return rc;
     float *scores = nullptr;
     return foid_static_scores(&scores); // the address of the built-in score scratch, looked up once per device

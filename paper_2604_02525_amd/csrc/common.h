@@ -35,6 +35,7 @@ int configure_gemm_mx_dual(int *ncu_out);
 int configure_oe_rowcol();
 int configure_oht();
 int configure_quantizers();
+int configure_foid();
 
 // Launchers (one per kernel family); each validates nothing and returns a status.
 // Stage-major copy of the scales for the tiled GEMM kernel (see gemm_mx_tiled_part): [K/256][rows][8].

@@ -3,7 +3,7 @@
 //
 // Scores are evaluated in a fixed fp32 order (sequential sum, mean = sum * (1/L), sequential fused
 // multiply-add of squared deviations) so the ranking is reproducible bit for bit; ties are broken
-// towards the lower index.  The selection is a 4-pass radix select over the score bits (scores are
+// towards the lower index.  The selection is a radix select over the score bits (scores are
 // non-negative, so their bit patterns order like the values) followed by an ordered compaction, all
 // inside one workgroup: the candidate count is at most a few tens of thousands and the whole step
 // is latency-bound.
@@ -184,26 +184,30 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const float *__restrict__
     }
 }
 
-// The same selection for dim <= TOPK_REG_KEYS * 1024 with every key held in registers: wave w owns the contiguous
-// index range [w*per, (w+1)*per) throughout and lane l its keys w*per + 64 j + l, loaded once.
+// The same selection for dim <= TOPK_LDS_KEYS with every key staged in LDS once: wave w owns the contiguous index
+// range [w*per, (w+1)*per) throughout.
 //
-// One workgroup is all the parallelism there is, so the cost is the number of instructions per key.  A radix pass over
-// all keys costs about 25 of them per key, and four are needed.  Instead:
-//   1. every thread takes the maximum of its keys; the k-th largest of these 1024 maxima, cut down to its upper 16
-//      bits (two radix passes over ONE value per thread), is a threshold T0 that at least k keys reach -- so the k
-//      largest keys, and every key tied with the k-th, are among the keys >= T0 -- and that few others reach
-//      (about 1.2 k of them for scores without structure);
-//   2. the keys >= T0 are collected in LDS (one pass over the registers: a compare per key) and the radix select
-//      runs over this short list (at most TOPK_CAND_PER_THREAD per thread);
-//   3. the ordered compaction walks all keys once, as in k_topk.
-// If k > 1024, or more than TOPK_CAND keys reach T0, the select runs over all register keys as before.
-constexpr int TOPK_REG_KEYS = 32;
-constexpr int TOPK_CAND_PER_THREAD = 4, TOPK_CAND = TOPK_CAND_PER_THREAD * TOPK_THREADS;
+// One workgroup is all the parallelism there is, and it runs every instruction of the kernel once or a few times
+// only: what such a kernel costs is, first, the instruction lines it has to fetch (the cache is cold at every launch;
+// a version of this kernel with the keys in registers and every loop unrolled spent most of its 12-18 us there) and,
+// second, the number of passes over all keys.  So every pass is a rolled loop over keys in LDS, the select and the
+// compaction exist once each (they run over a list described by a few numbers), and the passes over all keys are light:
+//   1. every thread takes the maximum of the keys it loads; the k-th largest of these 1024 maxima, cut down to its
+//      upper 16 bits (two radix passes over ONE value per thread), is a threshold T0 that at least k keys reach -- so
+//      the k largest keys, and every key tied with the k-th, are among the keys >= T0 -- and that few others reach
+//      (about 1.2 k of them for scores without structure).  With fewer than k threads that own a key the threshold
+//      comes out as 0 and step 2 finds too many candidates, which is handled there;
+//   2. the keys >= T0 are counted per wave and then copied, with their indices, to a list in index order (a compare
+//      per key in each of the two passes);
+//   3. radix select and ordered compaction run over this list (at most two entries per thread).
+// If k > 1024, or more than TOPK_CAND keys reach T0, or there are no more keys than four per thread, the list is
+// the keys themselves.
+constexpr int TOPK_LDS_KEYS = 32768;
+constexpr int TOPK_CAND = 2048, TOPK_DIRECT = 4 * TOPK_THREADS;
 
-// hist[bin] += 1 for every lane with valid set, hist being private to the wave: one combined add for the bin
-// of the first valid lane (the scores of ordinary rows share their high bytes, so that bin usually takes most of
-// the wave), plain per-lane adds for the rest (conflicts only among the lanes of this wave).
-__device__ __forceinline__ void wave_histogram_private(uint32_t *hist, bool valid, uint32_t bin)
+// hist[bin] += 1 for every lane with valid set: one combined add for the bin of the first valid lane (the scores of
+// ordinary rows share their high bytes, so that bin usually takes most of the wave), plain per-lane adds for the rest.
+__device__ __forceinline__ void wave_histogram_once(uint32_t *hist, bool valid, uint32_t bin)
 {
     const uint64_t todo = __ballot(valid);
     if (todo == 0) return;
@@ -214,205 +218,257 @@ __device__ __forceinline__ void wave_histogram_private(uint32_t *hist, bool vali
     if (valid && bin != b) atomicAdd(&hist[bin], 1u);
 }
 
-struct topk_shared_t {
-    uint32_t hist[TOPK_WAVES + 1][256]; // one per wave, and their sum
-    uint32_t prefix, remaining, count, whole_bin;
-    uint32_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
-    uint32_t cand[TOPK_CAND];
-};
-
-// Radix select over NK keys per thread (valid[j] says which exist), digits of 8 bits from bit 24 down to bit
-// LAST_SHIFT: on return `prefix` holds the upper bits of the k-th largest key (k >= 1, at most the number of valid
-// keys) and `remaining` how many keys with exactly these upper bits are among the k largest.  All threads call it.
-// EARLY: stop at the first digit at which the k largest keys are exactly the keys of the found bin and of the bins
-// above it (well separated outliers: usually the first or second digit): the remaining digits cannot change the
-// selection then.  `prefix` then has zeros below that digit and `remaining` is UINT32_MAX, which says "every key
-// >= prefix is selected"; returns true.
-template <int NK, int LAST_SHIFT, bool EARLY = false>
-__device__ __forceinline__ bool radix_select(topk_shared_t &sh, const uint32_t (&key)[NK], const bool (&valid)[NK], uint32_t k,
-                                             uint32_t &prefix, uint32_t &remaining)
+// Inclusive sum over the lanes of a wave (all 64 active): four shifts within the rows of 16 lanes, then the row totals
+// handed on to the following rows.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
 {
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    uint32_t pmask = 0;
-    prefix = 0;
-    remaining = k;
-    uint32_t *total = sh.hist[TOPK_WAVES];
-    for (int shift = 24; shift >= LAST_SHIFT; shift -= 8) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) sh.hist[w][lane + 64 * q] = 0;
-        // (each wave clears and fills its own histogram: no barrier needed in between)
-#pragma unroll
-        for (int j = 0; j < NK; ++j) {
-            const bool in = valid[j] && (key[j] & pmask) == prefix;
-            if (__ballot(in)) wave_histogram_private(sh.hist[w], in, (key[j] >> shift) & 255u);
-        }
-        __syncthreads();
-        if (tid < 256) {
-            uint32_t sum = 0;
-#pragma unroll
-            for (int v = 0; v < TOPK_WAVES; ++v) sum += sh.hist[v][tid];
-            total[tid] = sum;
-        }
-        __syncthreads();
-        // The digit of the k-th largest key: the highest bin b with (keys in bins above b) + total[b] >= remaining.
-        // Wave 0 scans the 256 bins in parallel: lane l owns bins 255 - 4l .. 252 - 4l.
-        if (w == 0) {
-            uint32_t c[4], mine = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                c[j] = total[255 - 4 * lane - j];
-                mine += c[j];
-            }
-            uint32_t incl = mine; // inclusive scan over lanes = over descending bins
-#pragma unroll
-            for (int d = 1; d < 64; d *= 2) {
-                const uint32_t up = __shfl_up(incl, d);
-                if (lane >= d) incl += up;
-            }
-            uint32_t cum = incl - mine; // keys in bins above this lane's
-            int found = -1;
-            uint32_t cum_at = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (found < 0 && cum + c[j] >= remaining) {
-                    found = 255 - 4 * lane - j;
-                    cum_at = cum;
-                }
-                cum += c[j];
-            }
-            const uint64_t hit = __ballot(found >= 0);
-            if (hit && lane == __ffsll((long long)hit) - 1) {
-                sh.prefix = prefix | ((uint32_t)found << shift);
-                sh.remaining = remaining - cum_at;
-                sh.whole_bin = total[found] == remaining - cum_at ? 1u : 0u;
-            }
-        }
-        __syncthreads();
-        prefix = sh.prefix;
-        remaining = sh.remaining;
-        pmask |= 255u << shift;
-        if (EARLY && shift > LAST_SHIFT && sh.whole_bin) { // (uniform: every thread reads the same word)
-            remaining = 0xffffffffu;
-            __syncthreads(); // the next use of the histograms and of sh.* must not overtake this read
-            return true;
-        }
-    }
-    return false;
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false); // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false); // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false); // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false); // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false); // lane 15 of rows 0, 2 to rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false); // lane 31 to rows 2, 3
+    return v;
 }
 
-__global__ __launch_bounds__(TOPK_THREADS) void k_topk_reg(const float *__restrict__ scores, int dim, int k,
+struct topk_shared_t { // behind the keys
+    uint32_t hist[2][256];              // used in turn by the radix passes, each cleared again after its pass
+    uint32_t cand[TOPK_CAND];           // first the 1024 thread maxima, then the keys >= T0 in index order
+    uint16_t cand_i[TOPK_CAND];         // and their indices (< TOPK_LDS_KEYS)
+    uint32_t prefix, remaining, whole_bin, unused;
+    uint32_t wave_a[TOPK_WAVES], wave_b[TOPK_WAVES];
+};
+static_assert(TOPK_LDS_KEYS <= 65536, "candidate indices are kept in 16 bits");
+
+constexpr int topk_per_wave(int n) { return ((n + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64; }
+constexpr size_t topk_lds_bytes(int dim) { return (size_t)topk_per_wave(dim) * TOPK_WAVES * 4 + sizeof(topk_shared_t); }
+static_assert(topk_lds_bytes(TOPK_LDS_KEYS) <= 160 * 1024, "keys, histograms and candidates share one compute unit's LDS");
+
+__global__ __launch_bounds__(TOPK_THREADS) void k_topk_lds(const float *__restrict__ scores, int dim, int k,
                                                            int32_t *__restrict__ idx, uint8_t *__restrict__ mask)
 {
-    __shared__ topk_shared_t sh;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    extern __shared__ __align__(16) uint32_t skeys[]; // per * TOPK_WAVES keys, then topk_shared_t
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6); // (a scalar: loop bounds derived from it are uniform)
     const uint32_t *keys = reinterpret_cast<const uint32_t *>(scores);
-    const int per = ((dim + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64; // <= 64 * TOPK_REG_KEYS
+    const int per = topk_per_wave(dim); // <= TOPK_LDS_KEYS / TOPK_WAVES
     const int lo = w * per, hi = min(dim, lo + per);
+    const int nslice = hi > lo ? (hi - lo + 63) / 64 : 0; // 64-key slices of this wave that hold keys
+    topk_shared_t &sh = *reinterpret_cast<topk_shared_t *>(skeys + per * TOPK_WAVES);
 
     if (k <= 0) {
         for (int i = tid; i < dim; i += TOPK_THREADS) mask[i] = 0;
         return;
     }
-    uint32_t key[TOPK_REG_KEYS];
-    bool in[TOPK_REG_KEYS];
+
+    // 0. the wave's keys into LDS (a wave reads back only what it wrote itself: no barrier), the thread's maximum,
+    // and the mask cleared (the selected entries are set at the end, many barriers later)
     uint32_t tmax = 0;
-    bool any = false;
+    if (((reinterpret_cast<uintptr_t>(keys) & 15) | (reinterpret_cast<uintptr_t>(mask) & 3)) == 0) {
+        // 16 bytes per lane, all loads of the wave in flight together (per <= 2048 = 8 x 256)
+        uint4 u[8];
 #pragma unroll
-    for (int j = 0; j < TOPK_REG_KEYS; ++j) {
-        const int i = lo + 64 * j + lane;
-        in[j] = i < hi; // false for every lane once 64 j >= per
-        key[j] = in[j] ? keys[i] : 0u;
-        tmax = max(tmax, key[j]);
-        any |= in[j];
-    }
-    if (tid == 0) sh.count = 0;
-
-    // 1. threshold from the thread maxima (dim <= TOPK_CAND: every key is a candidate anyway)
-    uint32_t T0 = 0;
-    bool short_list = dim <= TOPK_CAND;
-    if (!short_list && k <= TOPK_THREADS) {
-        const uint32_t m[1] = {tmax};
-        const bool mv[1] = {any};
-        // threads that own at least one key (a wave's range may hold fewer than 64): with fewer than k of them there
-        // is no k-th largest maximum and no threshold
-        uint32_t have = 0;
-        for (int v = 0; v < TOPK_WAVES; ++v) {
-            const int n = min(dim, (v + 1) * per) - v * per;
-            have += (uint32_t)max(0, min(n, 64));
-        }
-        if ((uint32_t)k <= have) {
-            uint32_t p, r;
-            radix_select<1, 16>(sh, m, mv, (uint32_t)k, p, r);
-            T0 = p; // upper 16 bits of the k-th largest maximum, lower bits 0
-            short_list = true;
-        }
-    }
-    __syncthreads(); // sh.count = 0 is visible; the histograms are free again
-
-    uint32_t T = 0, remaining = (uint32_t)k;
-    bool selected = false;
-    if (short_list) {
-        // 2. collect the keys >= T0, in any order
-#pragma unroll
-        for (int j = 0; j < TOPK_REG_KEYS; ++j) {
-            const bool c = in[j] && key[j] >= T0;
-            const uint64_t m = __ballot(c);
-            if (m) {
-                uint32_t base = 0;
-                const int leader = __ffsll((long long)m) - 1;
-                if (lane == leader) base = atomicAdd(&sh.count, (uint32_t)__popcll(m));
-                base = __builtin_amdgcn_readlane(base, leader);
-                const uint32_t pos = base + (uint32_t)__popcll(m & (((uint64_t)1 << lane) - 1));
-                if (c && pos < (uint32_t)TOPK_CAND) sh.cand[pos] = key[j];
+        for (int q = 0; q < 8; ++q) {
+            const int o = 256 * q + 4 * lane, i = lo + o; // (per is a multiple of 64, not of 256)
+            u[q] = make_uint4(0u, 0u, 0u, 0u);
+            if (o < per) {
+                if (i + 3 < hi) {
+                    u[q] = *reinterpret_cast<const uint4 *>(keys + i);
+                    *reinterpret_cast<uint32_t *>(mask + i) = 0u;
+                } else { // (one lane of one wave at most)
+                    if (i < hi) u[q].x = keys[i], mask[i] = 0;
+                    if (i + 1 < hi) u[q].y = keys[i + 1], mask[i + 1] = 0;
+                    if (i + 2 < hi) u[q].z = keys[i + 2], mask[i + 2] = 0;
+                }
             }
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int o = 256 * q + 4 * lane;
+            if (o < per) {
+                *reinterpret_cast<uint4 *>(skeys + lo + o) = u[q];
+                tmax = max(max(tmax, u[q].x), max(max(u[q].y, u[q].z), u[q].w));
+            }
+        }
+    } else {
+#pragma unroll 4
+        for (int i = lo + lane; i < hi; i += 64) {
+            const uint32_t key = keys[i];
+            mask[i] = 0;
+            skeys[i] = key;
+            tmax = max(tmax, key);
+        }
+    }
+
+    // The list that the final select and the compaction run over: entries [c_lo, c_hi) of src are this wave's part
+    // (in index order over the waves; c_n slices of 64), entry p standing for index p (the keys themselves) or
+    // cand_i[p] (candidates).  Entries up to the end of the last slice may be read (and are ignored).
+    const uint32_t *src = skeys;
+    int c_lo = lo, c_hi = hi, c_n = nslice;
+    bool direct = true;
+
+    // 1./2. radix select, once over the thread maxima (gives T0) and once over the list: digits of 8 bits from bit 24
+    // down to bit last_shift.  After a use `prefix` holds the upper bits of the k-th largest key and `remaining` how
+    // many keys with exactly these upper bits are among the k largest.  Over the list it stops at the first digit at
+    // which the k largest keys are exactly the keys of the found bin and of the bins above it (well separated
+    // outliers: usually the first or second digit): the remaining digits cannot change the selection then; `prefix`
+    // then has zeros below that digit and `remaining` is UINT32_MAX, which says "every key >= prefix is selected".
+    bool maxima = dim > TOPK_DIRECT && k <= TOPK_THREADS;
+    if (maxima) sh.cand[tid] = tmax;
+    if (tid < 512) sh.hist[0][tid] = 0; // (both histograms)
+    __syncthreads();
+    int pass = 0;
+    uint32_t T = 0, T0 = 0, remaining = (uint32_t)k;
+    const uint64_t below = ((uint64_t)1 << lane) - 1;
+    for (;;) {
+        const uint32_t *from = maxima ? sh.cand : src;
+        const int first = maxima ? tid : c_lo + lane;
+        const int end = maxima ? 64 * (w + 1) : c_hi; // (the maxima: one per thread, the wave's own 64)
+        const int n = maxima ? 1 : c_n;
+        const int last_shift = maxima ? 16 : 0;
+        uint32_t prefix = 0, pmask = 0;
+        remaining = (uint32_t)k;
+        for (int shift = 24; shift >= last_shift; shift -= 8) {
+            uint32_t *hist = sh.hist[pass & 1]; // (all zeros: cleared two passes ago, or before the first)
+            ++pass;
+            for (int j = 0; j < n; j += 2) { // (two reads in flight; what lies past the list is ignored)
+                const int i0 = first + 64 * j, i1 = i0 + 64;
+                const uint32_t key0 = from[i0], key1 = from[i1];
+                const bool in0 = i0 < end && (key0 & pmask) == prefix, in1 = i1 < end && (key1 & pmask) == prefix;
+                if (__ballot(in0)) wave_histogram_once(hist, in0, (key0 >> shift) & 255u);
+                if (__ballot(in1)) wave_histogram_once(hist, in1, (key1 >> shift) & 255u);
+            }
+            __syncthreads();
+            // The digit of the k-th largest key: the highest bin b with (keys in bins above b) + count[b] >= remaining.
+            // Wave 0 scans the 256 bins in parallel: lane l owns bins 255 - 4l .. 252 - 4l.
+            if (w == 0) {
+                const uint4 h = *reinterpret_cast<const uint4 *>(&hist[252 - 4 * lane]);
+                const uint32_t c[4] = {h.w, h.z, h.y, h.x};
+                const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+                uint32_t cum = wave_inclusive_sum(mine) - mine; // keys in bins above this lane's (lanes = descending bins)
+                int found = -1;
+                uint32_t cum_at = 0, c_at = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (found < 0 && cum + c[j] >= remaining) {
+                        found = 255 - 4 * lane - j;
+                        cum_at = cum;
+                        c_at = c[j];
+                    }
+                    cum += c[j];
+                }
+                const uint64_t hit = __ballot(found >= 0);
+                if (hit && lane == __ffsll((long long)hit) - 1) {
+                    sh.prefix = prefix | ((uint32_t)found << shift);
+                    sh.remaining = remaining - cum_at;
+                    sh.whole_bin = c_at == remaining - cum_at ? 1u : 0u;
+                }
+            }
+            __syncthreads();
+            if (tid < 256) hist[tid] = 0; // for the pass after the next (barriers in between)
+            prefix = sh.prefix;
+            remaining = sh.remaining;
+            pmask |= 255u << shift;
+            const bool stop = !maxima && shift > last_shift && sh.whole_bin; // (uniform: every thread reads the same word)
+            if (stop || shift == last_shift) __syncthreads(); // what comes next must not overtake these reads
+            if (stop) {
+                remaining = 0xffffffffu;
+                break;
+            }
+        }
+        if (!maxima) {
+            // (stopped early over the candidates, the threshold may lie below T0, where keys that are no candidates begin)
+            T = max(prefix, T0);
+            break;
+        }
+        maxima = false;
+        T0 = prefix; // upper 16 bits of the k-th largest maximum, lower bits 0
+        // the keys >= T0: how many in this wave's part, in the parts before it, and in all
+        // (four reads in flight; what lies past the wave's part is ignored)
+        uint32_t mine = 0;
+        for (int j = 0; j < nslice; j += 4) {
+            uint32_t key[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) key[q] = skeys[lo + 64 * (j + q) + lane];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                mine += (uint32_t)__popcll(__ballot(lo + 64 * (j + q) + lane < hi && key[q] >= T0));
+        }
+        if (lane == 0) sh.wave_a[w] = mine;
+        __syncthreads();
+        uint32_t pos = 0, count = 0;
+        for (int v = 0; v < TOPK_WAVES; ++v) {
+            const uint32_t c = sh.wave_a[v];
+            pos += v < w ? c : 0u;
+            count += c;
+        }
+        pos = __builtin_amdgcn_readfirstlane(pos);
+        count = __builtin_amdgcn_readfirstlane(count);
+        if (count <= (uint32_t)TOPK_CAND) {
+            // copied in index order, with their indices
+            for (int j = 0; j < nslice; j += 4) {
+                uint32_t key[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) key[q] = skeys[lo + 64 * (j + q) + lane];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int i = lo + 64 * (j + q) + lane;
+                    const bool c = i < hi && key[q] >= T0;
+                    const uint64_t m = __ballot(c);
+                    if (m) { // (most slices hold no candidate)
+                        if (c) {
+                            const uint32_t p = pos + (uint32_t)__popcll(m & below);
+                            sh.cand[p] = key[q];
+                            sh.cand_i[p] = (uint16_t)i;
+                        }
+                        pos += (uint32_t)__popcll(m);
+                    }
+                }
+            }
+            const int per_c = topk_per_wave((int)count);
+            src = sh.cand;
+            direct = false;
+            c_lo = w * per_c;
+            c_hi = min((int)count, c_lo + per_c);
+            c_n = c_hi > c_lo ? (c_hi - c_lo + 63) / 64 : 0;
         }
         __syncthreads();
-        const uint32_t count = sh.count;
-        if (count <= (uint32_t)TOPK_CAND) {
-            uint32_t ck[TOPK_CAND_PER_THREAD];
-            bool cv[TOPK_CAND_PER_THREAD];
-#pragma unroll
-            for (int q = 0; q < TOPK_CAND_PER_THREAD; ++q) {
-                const uint32_t i = (uint32_t)tid + (uint32_t)q * TOPK_THREADS;
-                cv[q] = i < count;
-                ck[q] = cv[q] ? sh.cand[i] : 0u;
-            }
-            // (stopped early, the threshold may lie below T0, where keys that are no candidates begin)
-            if (radix_select<TOPK_CAND_PER_THREAD, 0, true>(sh, ck, cv, (uint32_t)k, T, remaining)) T = max(T, T0);
-            selected = true;
-        }
     }
-    if (!selected) radix_select<TOPK_REG_KEYS, 0, true>(sh, key, in, (uint32_t)k, T, remaining); // the general way
 
-    // 3. ordered compaction, as in k_topk
+    // 3. ordered compaction over the list
     uint32_t gt = 0, eq = 0;
-#pragma unroll
-    for (int j = 0; j < TOPK_REG_KEYS; ++j) {
-        gt += (uint32_t)__popcll(__ballot(in[j] && key[j] > T));
-        eq += (uint32_t)__popcll(__ballot(in[j] && key[j] == T));
+#pragma unroll 2
+    for (int j = 0; j < c_n; ++j) {
+        const int i = c_lo + 64 * j + lane;
+        const uint32_t key = src[i];
+        gt += (uint32_t)__popcll(__ballot(i < c_hi && key > T));
+        eq += (uint32_t)__popcll(__ballot(i < c_hi && key == T));
     }
     if (lane == 0) {
-        sh.wave_gt[w] = gt;
-        sh.wave_eq[w] = eq;
+        sh.wave_a[w] = gt;
+        sh.wave_b[w] = eq;
     }
     __syncthreads();
     uint32_t gt_before = 0, eq_before = 0;
     for (int v = 0; v < w; ++v) {
-        gt_before += sh.wave_gt[v];
-        eq_before += sh.wave_eq[v];
+        gt_before += sh.wave_a[v];
+        eq_before += sh.wave_b[v];
     }
-    const uint64_t below = ((uint64_t)1 << lane) - 1;
-#pragma unroll
-    for (int j = 0; j < TOPK_REG_KEYS; ++j) {
-        const int i = lo + 64 * j + lane;
-        const bool is_gt = in[j] && key[j] > T, is_eq = in[j] && key[j] == T;
+#pragma unroll 2
+    for (int j = 0; j < c_n; ++j) {
+        const int i = c_lo + 64 * j + lane;
+        const bool in = i < c_hi;
+        const uint32_t key = src[i];
+        const bool is_gt = in && key > T, is_eq = in && key == T;
         const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
-        if ((m_gt | m_eq) == 0 && !__ballot(in[j])) continue; // past the end of the wave's range
         const uint32_t my_gt = gt_before + (uint32_t)__popcll(m_gt & below);
         const uint32_t my_eq = eq_before + (uint32_t)__popcll(m_eq & below);
-        const bool sel = is_gt || (is_eq && my_eq < remaining);
-        if (sel) idx[my_gt + min(my_eq, remaining)] = i;
-        if (in[j]) mask[i] = sel ? 1 : 0;
+        // selected entries before this one: every greater key, and the equal keys that were taken
+        if (is_gt || (is_eq && my_eq < remaining)) {
+            const int index = direct ? i : (int)sh.cand_i[i];
+            idx[my_gt + min(my_eq, remaining)] = index;
+            mask[index] = 1;
+        }
         gt_before += (uint32_t)__popcll(m_gt);
         eq_before += (uint32_t)__popcll(m_eq);
     }
@@ -432,6 +488,20 @@ __global__ __launch_bounds__(256) void k_mark(const int32_t *__restrict__ idx, i
 
 } // namespace
 
+// The one-workgroup selection keeps up to TOPK_LDS_KEYS keys in LDS: allowed once per device (host-side call).
+int configure_foid()
+{
+    static device_once_t once;
+    int dev = 0;
+    int rc = check_hip(hipGetDevice(&dev));
+    if (rc != ADAHOP_OK || !once.need(dev)) return rc;
+    rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(k_topk_lds), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)topk_lds_bytes(TOPK_LDS_KEYS)));
+    if (rc != ADAHOP_OK) return rc;
+    once.mark(dev);
+    return ADAHOP_OK;
+}
+
 int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, uint8_t *mask, float *scores,
                      hipStream_t st)
 {
@@ -444,10 +514,14 @@ int launch_foid_topk(const adahop_operand_t &x, int axis, int k, int32_t *idx, u
                        static_cast<const uint16_t *>(x.data), x.ld, x.k_contig, axis, dim, L, inv_L, scores);
     int rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
-    if (dim <= (int64_t)TOPK_REG_KEYS * TOPK_THREADS)
-        hipLaunchKernelGGL(k_topk_reg, dim3(1), dim3(TOPK_THREADS), 0, st, scores, (int)dim, k, idx, mask);
-    else
+    if (dim <= (int64_t)TOPK_LDS_KEYS) {
+        rc = configure_foid(); // more LDS than a launch may ask for by default: allowed once per device
+        if (rc != ADAHOP_OK) return rc;
+        hipLaunchKernelGGL(k_topk_lds, dim3(1), dim3(TOPK_THREADS), topk_lds_bytes((int)dim), st, scores, (int)dim, k, idx,
+                           mask);
+    } else {
         hipLaunchKernelGGL(k_topk, dim3(1), dim3(TOPK_THREADS), 0, st, scores, (int)dim, k, idx, mask);
+    }
     return check_launch();
 }
 

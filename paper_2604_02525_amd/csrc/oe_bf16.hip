@@ -429,26 +429,48 @@ __global__ __launch_bounds__(256) void k_gather_k(const uint16_t *__restrict__ x
 
 // The same for a K-strided operand (x stored [K, outer]): 64 channels x 64 rows per workgroup through
 // LDS, so that both the reads (along the rows of one channel) and the writes (along the channels of
-// one row) are whole 128-byte segments.
+// one row) are whole 128-byte segments, 16 bytes per lane.
 __global__ __launch_bounds__(256) void k_gather_k_strided(const uint16_t *__restrict__ x, int64_t ld, int64_t outer,
                                                           const int32_t *__restrict__ idx, int k, int kpad,
                                                           uint16_t *__restrict__ out)
 {
-    __shared__ uint16_t tile[64][66];
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    constexpr int PITCH = 72; // elements: 144-byte rows, 16-byte aligned
+    __shared__ __align__(16) uint16_t tile[64 * PITCH];
+    const int row = threadIdx.x >> 3, seg = threadIdx.x & 7;
     const int64_t o0 = (int64_t)blockIdx.x * 64;
     const int t0 = blockIdx.y * 64;
-#pragma unroll 4
-    for (int r = 0; r < 16; ++r) {
-        const int t = t0 + ty * 16 + r;
-        const int64_t o = o0 + tx;
-        tile[ty * 16 + r][tx] = (t < k && o < outer) ? load_once2(x + (int64_t)idx[t] * ld + o) : (uint16_t)0;
+    uint4 v[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int t = t0 + p * 32 + row;
+        const int64_t o = o0 + seg * 8;
+        v[p] = make_uint4(0u, 0u, 0u, 0u);
+        if (t < k) {
+            const uint16_t *src = x + (int64_t)idx[t] * ld + o;
+            if (o + 7 < outer) {
+                v[p] = load_once16(src);
+            } else { // (the last, ragged segment of a channel)
+                uint16_t e[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) e[q] = o + q < outer ? load_once2(src + q) : (uint16_t)0;
+                v[p] = make_uint4(e[0] | (uint32_t)e[1] << 16, e[2] | (uint32_t)e[3] << 16, e[4] | (uint32_t)e[5] << 16,
+                                  e[6] | (uint32_t)e[7] << 16);
+            }
+        }
     }
+#pragma unroll
+    for (int p = 0; p < 2; ++p) *reinterpret_cast<uint4 *>(&tile[(p * 32 + row) * PITCH + seg * 8]) = v[p];
     __syncthreads();
-#pragma unroll 4
-    for (int r = 0; r < 16; ++r) {
-        const int64_t o = o0 + ty * 16 + r;
-        if (o < outer) out[o * kpad + t0 + tx] = tile[tx][ty * 16 + r];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int ol = p * 32 + row; // row of the output: one outer index, 8 channels per lane
+        uint16_t e[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) e[q] = tile[(seg * 8 + q) * PITCH + ol];
+        if (o0 + ol < outer)
+            *reinterpret_cast<uint4 *>(out + (o0 + ol) * kpad + t0 + seg * 8) =
+                make_uint4(e[0] | (uint32_t)e[1] << 16, e[2] | (uint32_t)e[3] << 16, e[4] | (uint32_t)e[5] << 16,
+                           e[6] | (uint32_t)e[7] << 16);
     }
 }
 

@@ -213,7 +213,8 @@ def test_topk_selection_paths_bit_exact(ah):
     for dim, ks, kind in ((28672, (287, 574, 1, 1024, 1025, 3000, 28672), "random"), (28672, (287, 5000), "equal"),
                           (28672, (300,), "two-level"), (4097, (41, 4097), "random"), (4096, (41, 1500), "random"),
                           (9000, (90, 1100), "few-big"), (32768, (328, 640), "random"), (1090, (1089, 1024, 70), "random"),
-                          (16384, (164, 100, 165, 200), "separated"), (3000, (30, 29, 31), "separated")):
+                          (16384, (164, 100, 165, 200), "separated"), (3000, (30, 29, 31), "separated"),
+                          (4100, (1000, 820, 41), "random"), (8191, (81, 1024), "random"), (32767, (327,), "separated")):
         if kind == "random":
             a = np.abs(rng.standard_normal(dim)).astype(np.float32) + 0.5
         elif kind == "equal":
@@ -242,6 +243,33 @@ def test_topk_selection_paths_bit_exact(ah):
             ridx, rmask = orc.topk(ref_scores, k)
             assert np.array_equal(host(idx), ridx)
             assert np.array_equal(host(mask), rmask)
+
+
+def test_topk_score_scratch_at_odd_addresses(ah):
+    """Score scratch that is only 4-byte aligned, which is all the interface asks for (the selection kernel then
+    loads and clears element by element), on sizes with a ragged last wave."""
+    import ctypes as C
+    rng = np.random.default_rng(78)
+    for dim, k in ((5000, 50), (28671, 287), (130, 7)):
+        bits = rand_bits(rng, (dim, 64))
+        bits[rng.permutation(dim)[:k // 2], :] = rand_bits(rng, (k // 2, 64), 30.0)
+        op = ah.Operand.from_bits(bits, True)
+        ref_scores = orc.foid_scores(bits, True, 0)
+        ridx, rmask = orc.topk(ref_scores, k)
+        for s_off, m_off in ((1, 0), (3, 8), (2, 0)):
+            say("top-k, scratch at odd addresses", dict(dim=dim, k=k, scores_offset=4 * s_off, mask_offset=m_off))
+            scores = torch.zeros(dim + 8, dtype=torch.float32, device="cuda")
+            mask = torch.full((dim + 16,), 7, dtype=torch.uint8, device="cuda")
+            idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+            rc = ah.lib().adahop_foid_topk(C.byref(op.c()), 0, k, idx.data_ptr(), mask.data_ptr() + m_off,
+                                           scores.data_ptr() + 4 * s_off, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert rc == 0
+            assert np.array_equal(host(scores)[s_off:s_off + dim].view(np.uint32), ref_scores.view(np.uint32))
+            assert np.array_equal(host(idx), ridx)
+            m = host(mask)
+            assert np.array_equal(m[m_off:m_off + dim], rmask)
+            assert (m[:m_off] == 7).all() and (m[m_off + dim:] == 7).all()      # nothing written around the mask
 
 
 # ----------------------------------------------------------------------------- MXFP4 product
