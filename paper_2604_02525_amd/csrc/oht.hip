@@ -169,32 +169,17 @@ __global__ __launch_bounds__(256) void k_oht_quant(const uint16_t *__restrict__ 
 }
 
 // Workgroup = B rows x OHT_TN columns of C (OHT_TN / B blocks side by side), transformed along both axes in LDS.
-// grid (ceil(N / OHT_TN), M / B).  M % B == 0, N % B == 0.
-// VEC: C is 16-byte aligned with ldc % 4 == 0, rows are read as float4 (N % B == 0 makes every float4 whole).
-// (A persistent variant that keeps the next tile on its way in registers while the butterflies run was measured:
-// 1.08 against 1.12 ms for block 128 and 0.78 against 0.68 ms for block 32 on 16384 x 28672 -- the registers it
-// needs cost the occupancy that hides the same latency here.)
-template <int B, bool VEC>
+// grid (ceil(N / OHT_TN), M / B).  M % B == 0, N % B == 0.  Any alignment of C and any ldc: the kernel for rows that
+// are not 16-byte aligned; aligned rows take k_oht_inverse_reg below.
+template <int B>
 __global__ __launch_bounds__(256) void k_oht_inverse(float *__restrict__ C, int64_t M, int64_t N, int64_t ldc)
 {
     extern __shared__ float tile[]; // [B][OHT_NP]
     const int tid = threadIdx.x;
     const int64_t n0 = (int64_t)blockIdx.x * OHT_TN, m0 = (int64_t)blockIdx.y * B;
-    if constexpr (VEC) {
-#pragma unroll 4
-        for (int idx = tid; idx < B * (OHT_TN / 4); idx += 256) {
-            const int r = idx / (OHT_TN / 4), c4 = idx % (OHT_TN / 4);
-            if (n0 + 4 * c4 < N) {
-                const float4 q = *reinterpret_cast<const float4 *>(C + (m0 + r) * ldc + n0 + 4 * c4);
-                float *t = tile + r * OHT_NP + 4 * c4;
-                t[0] = q.x, t[1] = q.y, t[2] = q.z, t[3] = q.w;
-            }
-        }
-    } else {
-        for (int idx = tid; idx < B * OHT_TN; idx += 256) {
-            const int r = idx / OHT_TN, c = idx % OHT_TN;
-            if (n0 + c < N) tile[r * OHT_NP + c] = C[(m0 + r) * ldc + n0 + c];
-        }
+    for (int idx = tid; idx < B * OHT_TN; idx += 256) {
+        const int r = idx / OHT_TN, c = idx % OHT_TN;
+        if (n0 + c < N) tile[r * OHT_NP + c] = C[(m0 + r) * ldc + n0 + c];
     }
     __syncthreads();
     {   // H^T from the right: two threads per (row, B-wide column block); there are B * (OHT_TN / B) such pairs
@@ -208,6 +193,118 @@ __global__ __launch_bounds__(256) void k_oht_inverse(float *__restrict__ C, int6
                                     C + m0 * ldc + n0 + tid % OHT_TN, ldc);
 }
 
+// The value of lane (own lane ^ M) for M = 1, 2, 4, 8 (inside a row of 16 lanes: DPP) and 16 (between neighbouring
+// rows: the row swap of this chip), combined with the own value into the butterfly of stride M over lanes:
+// x + y on the lane with bit M clear, x - y (x the lower lane's value) on the lane with bit M set.  `sign` is +1 on
+// the lower lane and -1 on the upper one: sign * own + partner is that sum or difference with a single rounding.
+template <int M> __device__ __forceinline__ float lane_butterfly(float own, float sign)
+{
+    const int x = (int)__float_as_uint(own);
+    if constexpr (M == 16) {
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        // .x: the even row's value in both rows of a pair, .y: the odd row's
+        const u32x2 r = __builtin_amdgcn_permlane16_swap((unsigned)x, (unsigned)x, false, false);
+        return __builtin_fmaf(sign, __uint_as_float(r.y), __uint_as_float(r.x));
+    } else {
+        int p;
+        if constexpr (M == 1) p = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, true);      // quad_perm [1,0,3,2]
+        else if constexpr (M == 2) p = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, true); // quad_perm [2,3,0,1]
+        else if constexpr (M == 4) {
+            p = __builtin_amdgcn_update_dpp(0, x, 0x104, 0xf, 0x5, false); // lanes 0-3, 8-11 of a row: from lane + 4
+            p = __builtin_amdgcn_update_dpp(p, x, 0x114, 0xf, 0xa, false); // lanes 4-7, 12-15: from lane - 4
+        } else {
+            p = __builtin_amdgcn_update_dpp(0, x, 0x108, 0xf, 0x3, false); // lanes 0-7: from lane + 8
+            p = __builtin_amdgcn_update_dpp(p, x, 0x118, 0xf, 0xc, false); // lanes 8-15: from lane - 8
+        }
+        return __builtin_fmaf(sign, own, __uint_as_float((uint32_t)p));
+    }
+}
+
+template <int M, int B> __device__ __forceinline__ void lane_step(float4 &v, int lane)
+{
+    if constexpr (4 * M < B) { // the stride 4 M (in floats) lies inside a block of B
+        const float sign = (lane & M) ? -1.0f : 1.0f;
+        v.x = lane_butterfly<M>(v.x, sign);
+        v.y = lane_butterfly<M>(v.y, sign);
+        v.z = lane_butterfly<M>(v.z, sign);
+        v.w = lane_butterfly<M>(v.w, sign);
+    }
+}
+
+// The same rotation with the butterflies in registers (C 16-byte aligned, ldc % 4 == 0).  A lane holds four
+// consecutive columns of B / 8 rows (row = 8 it + 2 wave + lane / 32): the right-hand transform of a row's block of B
+// columns runs inside the float4 (strides 1, 2) and over the B / 4 neighbouring lanes (strides 4 .. B / 2).  The tile
+// then goes through LDS once, and comes back with a lane holding B / 2 rows of one column (column = 32 wave +
+// lane % 32, rows from (B / 2) (lane / 32)): strides 1 .. B / 4 of the left-hand transform are in registers, the last
+// one is between the two halves of the wave.  Every value sees the strides in ascending order with x + y to the lower
+// and x - y to the upper index and one multiply by 1/sqrt(B) per transform: the result is that of k_oht_inverse,
+// bit for bit.  On 16384 x 28672 with block 128 it takes 0.73 ms (5.1 TB/s read + written) against 1.13 ms with both
+// transforms through LDS (five barriers and 512 KB of LDS traffic per tile instead of one and 128 KB); a persistent
+// variant of the LDS kernel that kept the next tile on its way in registers had brought 4 % for block 128 and lost
+// 15 % for block 32.
+template <int B>
+__global__ __launch_bounds__(256) void k_oht_inverse_reg(float *__restrict__ C, int64_t M, int64_t N, int64_t ldc)
+{
+    extern __shared__ float tile[]; // [B][OHT_NP]
+    constexpr int ROWS = B / 8, CH = B / 2;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, half = lane >> 5, c4 = lane & 31;
+    const int64_t n0 = (int64_t)blockIdx.x * OHT_TN, m0 = (int64_t)blockIdx.y * B;
+    const float c = oht_norm<B>();
+    {
+        const bool live = n0 + 4 * c4 < N; // N % B == 0: a block of B columns is inside or outside as a whole
+        const float *src = C + (m0 + 2 * w + half) * ldc + n0 + 4 * c4;
+        float4 v[ROWS];
+#pragma unroll
+        for (int it = 0; it < ROWS; ++it)
+            v[it] = live ? *reinterpret_cast<const float4 *>(src + (int64_t)(8 * it) * ldc) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int it = 0; it < ROWS; ++it) {
+            float4 q = v[it];
+            const float a0 = q.x + q.y, a1 = q.x - q.y, a2 = q.z + q.w, a3 = q.z - q.w;
+            q = make_float4(a0 + a2, a1 + a3, a0 - a2, a1 - a3);
+            lane_step<1, B>(q, lane);
+            lane_step<2, B>(q, lane);
+            lane_step<4, B>(q, lane);
+            lane_step<8, B>(q, lane);
+            lane_step<16, B>(q, lane);
+            float *t = tile + (8 * it + 2 * w + half) * OHT_NP + 4 * c4;
+            t[0] = __builtin_fmaf(q.x, c, 0.0f); // "+ 0": an exact zero becomes +0
+            t[1] = __builtin_fmaf(q.y, c, 0.0f);
+            t[2] = __builtin_fmaf(q.z, c, 0.0f);
+            t[3] = __builtin_fmaf(q.w, c, 0.0f);
+        }
+    }
+    __syncthreads();
+    {
+        const int col = 32 * w + c4;
+        const bool live = n0 + col < N;
+        float u[CH];
+        const float *t = tile + (CH * half) * OHT_NP + col;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) u[i] = t[i * OHT_NP];
+#pragma unroll
+        for (int h = 1; h < CH; h *= 2)
+#pragma unroll
+            for (int i = 0; i < CH; i += 2 * h)
+#pragma unroll
+                for (int j = i; j < i + h; ++j) {
+                    const float a = u[j], b = u[j + h];
+                    u[j] = a + b;
+                    u[j + h] = a - b;
+                }
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        const float sign = half ? -1.0f : 1.0f;
+        float *dst = C + (m0 + CH * half) * ldc + n0 + col;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            // .x: the lower half's value in both halves of the wave, .y: the upper half's
+            const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(u[i]), __float_as_uint(u[i]), false, false);
+            const float y = __builtin_fmaf(sign, __uint_as_float(r.y), __uint_as_float(r.x));
+            if (live) dst[(int64_t)i * ldc] = __builtin_fmaf(y, c, 0.0f);
+        }
+    }
+}
+
 template <int B> constexpr size_t oht_quant_lds() { return (size_t)B * OHT_KP * sizeof(float); }
 template <int B> constexpr size_t oht_inverse_lds() { return (size_t)B * OHT_NP * sizeof(float); }
 
@@ -216,10 +313,10 @@ template <int B> int allow_oht_lds()
     int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_quant<B>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)oht_quant_lds<B>()));
     if (rc != ADAHOP_OK) return rc;
-    rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B, true>),
+    rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse_reg<B>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)oht_inverse_lds<B>()));
     if (rc != ADAHOP_OK) return rc;
-    return check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B, false>),
+    return check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_oht_inverse<B>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)oht_inverse_lds<B>()));
 }
 
@@ -233,19 +330,16 @@ template <int B> int launch_quant(const adahop_operand_t &x, uint8_t *codes, uin
     return check_launch();
 }
 
-template <int B, bool VEC> int launch_inverse_as(float *C, int64_t M, int64_t N, int64_t ldc, hipStream_t st)
+template <int B> int launch_inverse(float *C, int64_t M, int64_t N, int64_t ldc, hipStream_t st)
 {
     const int rc = configure_oht();
     if (rc != ADAHOP_OK) return rc;
     const dim3 grid((unsigned)ceil_div(N, OHT_TN), (unsigned)(M / B));
-    hipLaunchKernelGGL((k_oht_inverse<B, VEC>), grid, dim3(256), oht_inverse_lds<B>(), st, C, M, N, ldc);
+    if (aligned(C, 16) && ldc % 4 == 0)
+        hipLaunchKernelGGL(k_oht_inverse_reg<B>, grid, dim3(256), oht_inverse_lds<B>(), st, C, M, N, ldc);
+    else
+        hipLaunchKernelGGL(k_oht_inverse<B>, grid, dim3(256), oht_inverse_lds<B>(), st, C, M, N, ldc);
     return check_launch();
-}
-
-template <int B> int launch_inverse(float *C, int64_t M, int64_t N, int64_t ldc, hipStream_t st)
-{
-    return aligned(C, 16) && ldc % 4 == 0 ? launch_inverse_as<B, true>(C, M, N, ldc, st)
-                                          : launch_inverse_as<B, false>(C, M, N, ldc, st);
 }
 
 } // namespace

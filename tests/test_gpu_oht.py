@@ -75,6 +75,25 @@ def test_oht_inverse_matches_double_rotations(ah, b, M, N, pad):
     assert bool((buf[:, N:] == 3.0).all())
 
 
+@pytest.mark.parametrize("b,M,N", [(32, 64, 160), (64, 128, 448), (128, 384, 640)])
+def test_oht_inverse_same_bits_in_both_kernels(ah, b, M, N):
+    """The rotation with butterflies in registers (16-byte aligned rows) and the one through LDS (any ldc) apply the
+    same butterfly network: identical bits, including exact zeros (a block of equal values transforms to one
+    nonzero and B - 1 zeros)."""
+    rng = np.random.default_rng(b * 7 + N)
+    Cq = (rng.standard_normal((M, N)) * np.exp(rng.uniform(-3, 3, (M, 1)))).astype(np.float32)
+    Cq[:b, :b] = -1.25                      # exact cancellations
+    Cq[b // 2, b:2 * b] = 0.0
+    say("oht_inverse, both kernels", b, M, N)
+    fast = torch.from_numpy(Cq).cuda()
+    slow = torch.full((M, N + 1), 9.0, dtype=torch.float32, device="cuda")
+    slow[:, :N] = torch.from_numpy(Cq).cuda()
+    ah.adahop_oht_inverse(fast, b)
+    ah.adahop_oht_inverse(slow[:, :N], b)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(fast).view(np.uint32), host(slow[:, :N]).view(np.uint32))
+
+
 @pytest.mark.parametrize("b,M,N,K,layouts", [(128, 256, 384, 512, (True, True)), (64, 320, 192, 160, (True, False)),
                                              (32, 512, 512, 1024, (False, False)), (128, 768, 512, 1024, (True, False))])
 def test_oht_whole_strategy(ah, b, M, N, K, layouts):
