@@ -333,7 +333,8 @@ def adahop_prepare_device():
 
 
 def adahop_debug_force_gemm_kernel(which):
-    """Measurement aid: 0 = kernel chosen by shape, 1 = 256 x 256 tiles, 2 = 256 x 128 tiles with two accumulator sets."""
+    """Measurement aid: 0 = kernel chosen by shape, 1 = 256 x 256 tiles, 2 = 256 x 128 tiles with two accumulator sets,
+    3 / 4 = kernel by shape with the XCD-contiguous / the band-major tile walk forced."""
     _check(lib().adahop_debug_force_gemm_kernel(int(which)), "adahop_debug_force_gemm_kernel")
 
 

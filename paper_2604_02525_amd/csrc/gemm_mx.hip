@@ -471,7 +471,7 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
                                                          OUT *__restrict__ C, int64_t ldc,
                                                          const uint16_t *__restrict__ Ag,
                                                          const uint16_t *__restrict__ Bg, int kpad, int tiles_m,
-                                                         int tiles_n, int group_m)
+                                                         int tiles_n, int group_m, int band_major)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
@@ -485,7 +485,19 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
     // is the XCD of every tile of a workgroup: give each XCD a contiguous run of the tile sequence, and
     // order that sequence in bands of group_m tile rows so that concurrently running tiles share A and B
     // panels.
+    //
+    // band_major (host side: a grid of 256, tiles_m % 8 == 0, tiles_n % 32 == 0): the 256 tiles that run at a time
+    // are 8 tile rows x 32 tile columns instead -- XCD x takes columns 4x .. 4x+3 of them -- and the walk sweeps the
+    // column groups of a band of 8 rows before it moves to the next band.  For an A too large to stay in the
+    // Infinity Cache: a band of A is then fetched from HBM once and B is what is swept again and again, where the
+    // XCD-contiguous order sweeps all of A once per round.
     auto tile_origin = [&](int v, int64_t &m0, int64_t &n0) {
+        if (band_major) {
+            const int x = v & 7, s = (v >> 3) & 31, round = v >> 8, groups = tiles_n >> 5;
+            m0 = (int64_t)((round / groups) * 8 + (s & 7)) * TM;
+            n0 = (int64_t)((round % groups) * 32 + 4 * x + (s >> 3)) * TN;
+            return;
+        }
         int tix = v;
         if (ntiles % 8 == 0) tix = (v & 7) * (ntiles >> 3) + (v >> 3);
         const int band = group_m * tiles_n;
@@ -602,8 +614,13 @@ size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
 // nothing.  At least three pipeline stages are needed (64 gathered channels or 256 K-elements each, two of
 // them FP4 stages); the bf16 epilogue stores 16 bytes per lane.
 static std::atomic<int> g_kernel_choice{0};
+static std::atomic<int> g_force_walk{-1}; // -1: the order of the tile walk chosen by shape; 0 / 1: forced
 
-void gemm_mx_force_kernel(int which) { g_kernel_choice.store(which); }
+void gemm_mx_force_kernel(int which)
+{
+    g_kernel_choice.store(which <= 2 ? which : 0);
+    g_force_walk.store(which == 3 ? 0 : which == 4 ? 1 : -1);
+}
 
 // Which tiled kernel takes a product (fp32 C, no gathered K-channels; otherwise always the 256 x 256 kernel).  The
 // 256 x 128 kernel with two accumulator sets hides the C stores behind the next tile but moves 1.5 times the operand
@@ -714,6 +731,17 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     // one workgroup per compute unit walks the tiles (each workgroup fills a compute unit's LDS and registers)
     const int ntiles = tiles_m * tiles_n;
     const dim3 grid((unsigned)(ntiles < ncu ? ntiles : ncu));
+    // The order of the walk.  In XCD-contiguous runs the eight XCDs work on up to 64 different tile rows at a time and
+    // come back to them once per round of tiles: when those rows of the packed A do not stay in the 256 MB Infinity
+    // Cache meanwhile (and the packed B would), bands of A swept over all of B fetch A from HBM once instead --
+    // 16384 x 8192 x 28672 (235 MB of A in use at a time): 1.66 against 1.79 ms; where the rows in use do stay
+    // (28672 x 8192 x 16384: 134 MB) the XCD-contiguous order is 4 % faster, the XCDs not all asking for the same
+    // panels at the same time.
+    constexpr int64_t STAYS = 192ll << 20;
+    const int64_t a_in_use = (int64_t)(tiles_m < 64 ? tiles_m : 64) * TM * (K / 2);
+    const int forced = g_force_walk.load();
+    const int band_major = forced >= 0 ? forced : (a_in_use > STAYS && Ni * (K / 2) <= STAYS) ? 1 : 0;
+    const int walk = band_major && grid.x == 256 && tiles_m % 8 == 0 && tiles_n % 32 == 0 ? 1 : 0;
     if constexpr (sizeof(OUT) == 4) {
         if (takes_dual_kernel(M, N, K, kpad, 0)) {
             rc = launch_gemm_mx_dual(Mi, Ni, K, a_codes, a_sm, b_codes, b_sm, reinterpret_cast<float *>(C), ldc, st);
@@ -722,10 +750,10 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     }
     if (kpad > 0)
         hipLaunchKernelGGL((k_gemm_mx_tile256<true, OUT>), grid, dim3(256), KERNEL_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
-                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
+                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m, walk);
     else
         hipLaunchKernelGGL((k_gemm_mx_tile256<false, OUT>), grid, dim3(256), KERNEL_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
-                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m);
+                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m, walk);
     rc = check_launch();
 edges:
     if (rc != ADAHOP_OK) return rc;

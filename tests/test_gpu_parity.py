@@ -420,6 +420,38 @@ def test_more_tiles_than_compute_units(ah, strategy, k, M, N):
     run_whole(ah, g, rows=rows.astype(np.int32), cols=cols.astype(np.int32))
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 8192, 768), (2048, 16384, 1024), (4096, 16384, 768)])
+def test_both_orders_of_the_tile_walk_give_the_same_bits(ah, M, N, K):
+    """The persistent 256 x 256 kernel walks its tiles in XCD-contiguous runs or in bands of A swept over B (taken by
+    itself only for operands larger than the Infinity Cache): forced either way on 512 and 1024 tiles (two and four
+    rounds of the 256 workgroups; two bands; two column groups), every tile must be computed exactly once, with the
+    same bits, and agree with the oracle on a sample that touches every tile."""
+    rng = np.random.default_rng(M + N + K)
+    a_codes = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    b_codes = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    a_scales = rng.integers(117, 137, size=(M, K // 32), dtype=np.uint8)
+    b_scales = rng.integers(100, 120, size=(N, K // 32), dtype=np.uint8)
+    dev = [torch.from_numpy(t).cuda() for t in (a_codes, a_scales, b_codes, b_scales)]
+    say("tile walk orders", (M, N, K))
+    out = {}
+    try:
+        for which in (3, 4):
+            ah.adahop_debug_force_gemm_kernel(which)
+            C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+            ah.adahop_gemm_mx(*dev, Cout=C)
+            torch.cuda.synchronize()
+            out[which] = host(C)
+    finally:
+        ah.adahop_debug_force_gemm_kernel(0)
+    assert np.array_equal(out[3].view(np.uint32), out[4].view(np.uint32))
+    rows = np.arange(0, M, 256) + rng.integers(0, 256, M // 256)
+    cols = np.arange(0, N, 256) + rng.integers(0, 256, N // 256)
+    ref = orc.mx_gemm(a_codes[rows], a_scales[rows], b_codes[cols], b_scales[cols])
+    err = rel_fro(out[4][np.ix_(rows, cols)], ref)
+    say("  rel_fro", err)
+    assert err < 1e-5
+
+
 @pytest.mark.parametrize("a_kc,b_kc", [(True, True), (True, False), (False, True)])
 @pytest.mark.parametrize("K,k", [(4096, 41), (8192, 5), (8192, 200)])
 def test_oe_k_channels_copied_by_the_quantiser(ah, a_kc, b_kc, K, k):
