@@ -330,10 +330,12 @@ int adahop_probe_mfma_rate(int random_operands, int idle_sleeps, int workgroups,
 
 /* Measurement aid: which tiled kernel the MXFP4 product uses from now on (process-wide).  0 = chosen by shape (the
  * default), 1 = always the 256 x 256 tile kernel, 2 = the 256 x 128 tile kernel with two accumulator sets wherever it
- * can run (fp32 C, K % 256 == 0, K >= 2048, no K-channel extraction).  3 / 4 = kernel chosen by shape, and the
- * 256 x 256 kernel walks its tiles in XCD-contiguous runs always (3) or in bands of A swept over B wherever that
- * order can run (4; by default it is taken when the packed A exceeds what stays in the Infinity Cache).  Results are
- * the same up to fp32 summation order (3, 4: the same bits).  Returns ADAHOP_E_INVALID_ARG for any other value. */
+ * can run (fp32 C, K % 256 == 0, K >= 2048, no K-channel extraction).  3 .. 6 = kernel chosen by shape, and the
+ * 256 x 256 kernel walks its tiles in a forced order: 3 = bands of A in XCD-contiguous runs, 4 = bands of A swept
+ * over B, 5 / 6 = the same two with the roles of A and B exchanged (a sweep that the shape does not allow falls back
+ * to the contiguous runs).  By default the bands run along the operand with more tiles, swept where more of it would
+ * be in use at a time than stays in the Infinity Cache.  Results are the same up to fp32 summation order (3 .. 6: the
+ * same bits).  Returns ADAHOP_E_INVALID_ARG for any other value. */
 int adahop_debug_force_gemm_kernel(int which);
 
 #ifdef __cplusplus

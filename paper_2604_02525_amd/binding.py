@@ -334,7 +334,7 @@ def adahop_prepare_device():
 
 def adahop_debug_force_gemm_kernel(which):
     """Measurement aid: 0 = kernel chosen by shape, 1 = 256 x 256 tiles, 2 = 256 x 128 tiles with two accumulator sets,
-    3 / 4 = kernel by shape with the XCD-contiguous / the band-major tile walk forced."""
+    3 .. 6 = kernel by shape with the order of the tile walk forced (bands of A: contiguous runs / swept over B; 5, 6: of B)."""
     _check(lib().adahop_debug_force_gemm_kernel(int(which)), "adahop_debug_force_gemm_kernel")
 
 

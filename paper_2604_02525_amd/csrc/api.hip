@@ -55,7 +55,7 @@ int adahop_abi_version(void) { return 1; }
 
 int adahop_debug_force_gemm_kernel(int which)
 {
-    if (which < 0 || which > 4) return ADAHOP_E_INVALID_ARG;
+    if (which < 0 || which > 6) return ADAHOP_E_INVALID_ARG;
     gemm_mx_force_kernel(which);
     return ADAHOP_OK;
 }

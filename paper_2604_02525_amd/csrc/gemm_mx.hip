@@ -471,7 +471,7 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
                                                          OUT *__restrict__ C, int64_t ldc,
                                                          const uint16_t *__restrict__ Ag,
                                                          const uint16_t *__restrict__ Bg, int kpad, int tiles_m,
-                                                         int tiles_n, int group_m, int band_major)
+                                                         int tiles_n, int group_m, int order)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
@@ -482,29 +482,35 @@ __global__ __launch_bounds__(256) void k_gemm_mx_tile256(int64_t K, const uint8_
 
     // Position v of the walk -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each
     // with its own L2) and the grid is a multiple of 8 whenever it is smaller than the tile count, so v % 8
-    // is the XCD of every tile of a workgroup: give each XCD a contiguous run of the tile sequence, and
-    // order that sequence in bands of group_m tile rows so that concurrently running tiles share A and B
-    // panels.
-    //
-    // band_major (host side: a grid of 256, tiles_m % 8 == 0, tiles_n % 32 == 0): the 256 tiles that run at a time
-    // are 8 tile rows x 32 tile columns instead -- XCD x takes columns 4x .. 4x+3 of them -- and the walk sweeps the
-    // column groups of a band of 8 rows before it moves to the next band.  For an A too large to stay in the
-    // Infinity Cache: a band of A is then fetched from HBM once and B is what is swept again and again, where the
-    // XCD-contiguous order sweeps all of A once per round.
+    // is the XCD of every tile of a workgroup.  The operand with more tiles is the "major" one (order bit 1: B,
+    // else A); the other is what the XCDs share.
+    //   order bit 0 clear: every XCD gets a contiguous run of the tile sequence, ordered in bands of group_m major
+    //     tiles (rows of tiles for A), so that the 32 tiles an XCD runs at a time share 8 + 4 panels, and an XCD keeps
+    //     its bands of the major operand to itself.
+    //   order bit 0 set (host side: a grid of 256, major tiles % 8 == 0, minor tiles % 32 == 0): the 256 tiles that run
+    //     at a time are 8 major x 32 minor tiles -- XCD x takes minor tiles 4x .. 4x+3 of them -- and the walk sweeps the
+    //     groups of 32 minor tiles before it moves to the next band of 8.  For a major operand of which the XCD-contiguous
+    //     order would keep more in use than stays in the Infinity Cache: a band of it is fetched from HBM once.
     auto tile_origin = [&](int v, int64_t &m0, int64_t &n0) {
-        if (band_major) {
-            const int x = v & 7, s = (v >> 3) & 31, round = v >> 8, groups = tiles_n >> 5;
-            m0 = (int64_t)((round / groups) * 8 + (s & 7)) * TM;
-            n0 = (int64_t)((round % groups) * 32 + 4 * x + (s >> 3)) * TN;
-            return;
+        const bool b_major = (order & 2) != 0;
+        const int t_major = b_major ? tiles_n : tiles_m, t_minor = b_major ? tiles_m : tiles_n;
+        int major, minor;
+        if (order & 1) {
+            const int x = v & 7, s = (v >> 3) & 31, round = v >> 8, groups = t_minor >> 5;
+            major = (round / groups) * 8 + (s & 7);
+            minor = (round % groups) * 32 + 4 * x + (s >> 3);
+        } else {
+            int tix = v;
+            if (ntiles % 8 == 0) tix = (v & 7) * (ntiles >> 3) + (v >> 3);
+            const int gm = min(group_m, t_major);
+            const int band = gm * t_minor;
+            const int first = (tix / band) * gm;
+            const int gsz = min(gm, t_major - first);
+            major = first + (tix % band) % gsz;
+            minor = (tix % band) / gsz;
         }
-        int tix = v;
-        if (ntiles % 8 == 0) tix = (v & 7) * (ntiles >> 3) + (v >> 3);
-        const int band = group_m * tiles_n;
-        const int first_m = (tix / band) * group_m;
-        const int gsz = min(group_m, tiles_m - first_m);
-        m0 = (int64_t)(first_m + (tix % band) % gsz) * TM;
-        n0 = (int64_t)((tix % band) / gsz) * TN;
+        m0 = (int64_t)(b_major ? minor : major) * TM;
+        n0 = (int64_t)(b_major ? major : minor) * TN;
     };
 
     tile_state_t t;
@@ -614,12 +620,12 @@ size_t gemm_mx_workspace_bytes(int64_t M, int64_t N, int64_t K)
 // nothing.  At least three pipeline stages are needed (64 gathered channels or 256 K-elements each, two of
 // them FP4 stages); the bf16 epilogue stores 16 bytes per lane.
 static std::atomic<int> g_kernel_choice{0};
-static std::atomic<int> g_force_walk{-1}; // -1: the order of the tile walk chosen by shape; 0 / 1: forced
+static std::atomic<int> g_force_walk{-1}; // -1: the order of the tile walk chosen by shape; 0 .. 3: forced
 
 void gemm_mx_force_kernel(int which)
 {
     g_kernel_choice.store(which <= 2 ? which : 0);
-    g_force_walk.store(which == 3 ? 0 : which == 4 ? 1 : -1);
+    g_force_walk.store(which >= 3 ? which - 3 : -1);
 }
 
 // Which tiled kernel takes a product (fp32 C, no gathered K-channels; otherwise always the 256 x 256 kernel).  The
@@ -727,21 +733,33 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     int rc = check_launch();
     if (rc != ADAHOP_OK) return rc;
     const int tiles_m = (int)(Mi / TM), tiles_n = (int)(Ni / TN);
-    const int group_m = tiles_m < 8 ? tiles_m : 8;
+    const int group_m = 8;
     // one workgroup per compute unit walks the tiles (each workgroup fills a compute unit's LDS and registers)
     const int ntiles = tiles_m * tiles_n;
     const dim3 grid((unsigned)(ntiles < ncu ? ntiles : ncu));
-    // The order of the walk.  In XCD-contiguous runs the eight XCDs work on up to 64 different tile rows at a time and
-    // come back to them once per round of tiles: when those rows of the packed A do not stay in the 256 MB Infinity
-    // Cache meanwhile (and the packed B would), bands of A swept over all of B fetch A from HBM once instead --
-    // 16384 x 8192 x 28672 (235 MB of A in use at a time): 1.66 against 1.79 ms; where the rows in use do stay
-    // (28672 x 8192 x 16384: 134 MB) the XCD-contiguous order is 4 % faster, the XCDs not all asking for the same
-    // panels at the same time.
+    // The order of the walk (see the kernel), as measured on MI355X with the same flops each:
+    //  - bands along the operand with more tiles, in XCD-contiguous runs.  The XCDs keep their bands of it to
+    //    themselves and share the other one, which is smaller and stays in the 256 MB Infinity Cache:
+    //    8192 x 28672 x 16384 takes 1.60 ms in bands of B against 1.74 ms in bands of A (each panel of the 235 MB B is
+    //    then asked for by four XCDs at once, before the cache has it), and 28672 x 8192 x 16384 1.60 against 1.70 ms
+    //    the other way round; 8192 x 16384 x 28672: 1.64 (bands of B) against 1.72 ms;
+    //  - in such runs the eight XCDs work on up to 64 bands' worth of major tiles at a time and come back to them
+    //    once per round: when that much of a packed A does not stay in the cache (and B would), bands of A swept over
+    //    all of B fetch A from HBM once instead -- 16384 x 8192 x 28672 (235 MB of A in use at a time): 1.65 against
+    //    1.69 .. 1.79 ms by machine.  (The mirrored sweep, bands of B over A, exists and gives the same bits but is
+    //    not chosen: on the mirrored shape the contiguous runs are faster, 1.64 against 1.72 ms.)
     constexpr int64_t STAYS = 192ll << 20;
+    const bool b_major = tiles_n > tiles_m;
     const int64_t a_in_use = (int64_t)(tiles_m < 64 ? tiles_m : 64) * TM * (K / 2);
+    const bool sweep_a = !b_major && a_in_use > STAYS && Ni * (K / 2) <= STAYS && grid.x == 256 && tiles_m % 8 == 0 &&
+                         tiles_n % 32 == 0;
+    int order = b_major ? 2 : sweep_a ? 1 : 0;
     const int forced = g_force_walk.load();
-    const int band_major = forced >= 0 ? forced : (a_in_use > STAYS && Ni * (K / 2) <= STAYS) ? 1 : 0;
-    const int walk = band_major && grid.x == 256 && tiles_m % 8 == 0 && tiles_n % 32 == 0 ? 1 : 0;
+    if (forced >= 0) {
+        const bool fb = (forced & 2) != 0;
+        const bool ok = !(forced & 1) || (grid.x == 256 && (fb ? tiles_n : tiles_m) % 8 == 0 && (fb ? tiles_m : tiles_n) % 32 == 0);
+        order = ok ? forced : (forced & 2);
+    }
     if constexpr (sizeof(OUT) == 4) {
         if (takes_dual_kernel(M, N, K, kpad, 0)) {
             rc = launch_gemm_mx_dual(Mi, Ni, K, a_codes, a_sm, b_codes, b_sm, reinterpret_cast<float *>(C), ldc, st);
@@ -750,10 +768,10 @@ int launch_gemm_mx_t(int64_t M, int64_t N, int64_t K, const uint8_t *a_codes, co
     }
     if (kpad > 0)
         hipLaunchKernelGGL((k_gemm_mx_tile256<true, OUT>), grid, dim3(256), KERNEL_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
-                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m, walk);
+                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m, order);
     else
         hipLaunchKernelGGL((k_gemm_mx_tile256<false, OUT>), grid, dim3(256), KERNEL_LDS_BYTES, st, K, a_codes, a_sm, b_codes,
-                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m, walk);
+                           b_sm, Mi, Ni, C, ldc, Ag, Bg, kpad, tiles_m, tiles_n, group_m, order);
     rc = check_launch();
 edges:
     if (rc != ADAHOP_OK) return rc;

@@ -420,12 +420,14 @@ def test_more_tiles_than_compute_units(ah, strategy, k, M, N):
     run_whole(ah, g, rows=rows.astype(np.int32), cols=cols.astype(np.int32))
 
 
-@pytest.mark.parametrize("M,N,K", [(4096, 8192, 768), (2048, 16384, 1024), (4096, 16384, 768)])
-def test_both_orders_of_the_tile_walk_give_the_same_bits(ah, M, N, K):
-    """The persistent 256 x 256 kernel walks its tiles in XCD-contiguous runs or in bands of A swept over B (taken by
-    itself only for operands larger than the Infinity Cache): forced either way on 512 and 1024 tiles (two and four
-    rounds of the 256 workgroups; two bands; two column groups), every tile must be computed exactly once, with the
-    same bits, and agree with the oracle on a sample that touches every tile."""
+@pytest.mark.parametrize("M,N,K", [(4096, 8192, 768), (2048, 16384, 1024), (16384, 4096, 768), (8192, 8192, 768),
+                                   (2304, 8192, 768)])
+def test_every_order_of_the_tile_walk_gives_the_same_bits(ah, M, N, K):
+    """The persistent 256 x 256 kernel walks its tiles in bands of A or of B, in XCD-contiguous runs or swept over the
+    other operand (chosen by shape: the sweep only for operands larger than the Infinity Cache).  Forced each way on
+    512 and 1024 tiles (two and four rounds of the 256 workgroups; two bands; two groups of 32 minor tiles; a shape
+    whose sweep along B cannot run and falls back), every tile must be computed exactly once, with the same bits, and
+    agree with the oracle on a sample that touches every tile."""
     rng = np.random.default_rng(M + N + K)
     a_codes = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
     b_codes = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
@@ -435,7 +437,7 @@ def test_both_orders_of_the_tile_walk_give_the_same_bits(ah, M, N, K):
     say("tile walk orders", (M, N, K))
     out = {}
     try:
-        for which in (3, 4):
+        for which in (0, 3, 4, 5, 6):
             ah.adahop_debug_force_gemm_kernel(which)
             C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
             ah.adahop_gemm_mx(*dev, Cout=C)
@@ -443,7 +445,8 @@ def test_both_orders_of_the_tile_walk_give_the_same_bits(ah, M, N, K):
             out[which] = host(C)
     finally:
         ah.adahop_debug_force_gemm_kernel(0)
-    assert np.array_equal(out[3].view(np.uint32), out[4].view(np.uint32))
+    for which in (0, 4, 5, 6):
+        assert np.array_equal(out[3].view(np.uint32), out[which].view(np.uint32)), which
     rows = np.arange(0, M, 256) + rng.integers(0, 256, M // 256)
     cols = np.arange(0, N, 256) + rng.integers(0, 256, N // 256)
     ref = orc.mx_gemm(a_codes[rows], a_scales[rows], b_codes[cols], b_scales[cols])
