@@ -22,7 +22,7 @@ BF16_PEAK_TFLOPS = 2516.0
 # HBM bytes per launch of the FP4 GEMM kernel, by (M, N, K): rocprofv3 FETCH_SIZE + WRITE_SIZE (KiB per
 # dispatch), each scaled by what the same counter reads for a plain 1 GiB copy (--copy-calibration);
 # the runs and the scaling are in profiles/gemm_mx_16384x28672x8192_counters.txt.
-GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 4.97e9, (8192, 8192, 2048): 3.57e8}
+GEMM_HBM_TRAFFIC_BYTES = {(16384, 28672, 8192): 4.99e9, (8192, 8192, 2048): 3.57e8}
 GEMM_HBM_TRAFFIC_SOURCE = {(16384, 28672, 8192): "profiles/gemm_mx_16384x28672x8192_counters.txt",
                            (8192, 8192, 2048): "profiles/gemm_mx_dual_8192x8192x2048_counters.txt"}
 
