@@ -666,6 +666,7 @@ __global__ __launch_bounds__(256) void k_quant_kc16_gather(const uint16_t *__res
 // exactly once; the 16-byte writes of a 16-lane group go to two rows whose banks do not overlap either.
 // ------------------------------------------------------------------------------------------------
 constexpr int KS_COLS = 64, KT_PITCH = 144;
+constexpr unsigned KS_GROUP = 32, KS_GROUP_FROM = 256; // column tiles that walk the K-blocks together; from how many on
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 
@@ -704,11 +705,32 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
                                                     int64_t ld, const uint8_t *__restrict__ zero_outer,
                                                     const uint8_t *__restrict__ zero_k,
                                                     uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
-                                                    sr_key_t key, scales_sm_t sm)
+                                                    sr_key_t key, scales_sm_t sm, unsigned group)
 {
     __shared__ __attribute__((aligned(16))) uint8_t tile[256 * KT_PITCH];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int64_t o0 = (int64_t)blockIdx.x * KS_COLS, k0 = (int64_t)blockIdx.y * 256;
+    // Workgroups start in the order of their linear index, x fastest.  Taken as it is, that order runs all column
+    // tiles of one K-block before the next K-block: the workgroups in flight together then write 128-byte pieces of
+    // thousands of different output rows.  Instead the index walks KS_GROUP neighbouring column tiles through all
+    // K-blocks before it moves to the next group: the reads still come in pieces of KS_GROUP x 128 bytes of a K-row, and
+    // an output row is written in one go.  Measured (block 256): operands with rows of 28672 elements (448 column
+    // tiles: about 1000 workgroups in flight span two K-blocks) 292 -> 237 us ([16384][28672]) and 133 -> 122 us
+    // ([8192][28672]); with rows of 8192 and 16384 elements (in flight: 8 and 4 K-blocks) the plain order is 2 .. 5 %
+    // faster and is kept (group == 0).
+    unsigned bx = blockIdx.x, by = blockIdx.y;
+    if (group) {
+        const uint64_t nx = gridDim.x, ny = gridDim.y, L = by * nx + bx, full = nx / group * group;
+        if (L < full * ny) {
+            const uint64_t r = L % (group * ny);
+            bx = (unsigned)(L / (group * ny) * group + r % group);
+            by = (unsigned)(r / group);
+        } else { // the last, narrower group
+            const uint64_t r = L - full * ny, wdt = nx - full;
+            bx = (unsigned)(full + r % wdt);
+            by = (unsigned)(r / wdt);
+        }
+    }
+    const int64_t o0 = (int64_t)bx * KS_COLS, k0 = (int64_t)by * 256;
 
     // ---- global -> LDS: a pass is 32 K-rows x 64 columns; lane: 8 columns (cg) of one of the wave's 8 rows.  A group
     // of 16 lanes takes two rows two apart (their banks do not overlap: consecutive K-rows are 16 banks apart).
@@ -923,8 +945,9 @@ int launch_ks(const adahop_operand_t &x, const uint8_t *zo, const uint8_t *zk, u
 {
     if (iht_quantize_writes_scales_sm(x)) {
         dim3 grid((unsigned)ceil_div(x.outer, KS_COLS), (unsigned)(x.K / 256));
+        const unsigned group = grid.x > KS_GROUP_FROM ? KS_GROUP : 0u;
         hipLaunchKernelGGL((k_quant_ks16<B, SR>), grid, dim3(256), 0, st, static_cast<const uint16_t *>(x.data), x.outer,
-                           x.K, x.ld, zo, zk, codes, scales, key, sm);
+                           x.K, x.ld, zo, zk, codes, scales, key, sm, group);
         return check_launch();
     }
     constexpr int NW = ks_cfg<B>::NW;

@@ -134,6 +134,29 @@ def test_iht_quantize_bit_exact(ah, b, k_contig):
         assert np.array_equal(host(codes), rc)
 
 
+@pytest.mark.parametrize("b", [256, 32])
+def test_iht_quantize_k_strided_long_rows_bit_exact(ah, b):
+    """K-strided operand with more than 256 tiles of 64 columns (the quantiser then starts its workgroups in groups of
+    32 column tiles that walk the K-blocks together): a whole number of groups plus a narrower last one plus a ragged
+    last tile, three K-blocks, with both masks."""
+    outer, K = (8 * 32 + 21) * 64 + 40, 768
+    rng = np.random.default_rng(300 + b)
+    logical = rand_bits(rng, (outer, K))
+    logical[:, 700] = rand_bits(rng, (outer,), 60.0)
+    arr, width = stored(logical, False)
+    x = ah.Operand(torch.from_numpy(arr.view(np.int16)).cuda()[:, :width], False)
+    zo = (rng.random(outer) < 0.05).astype(np.uint8)
+    zk = (rng.random(K) < 0.05).astype(np.uint8)
+    say("iht_quantize, K-strided, long rows", dict(b=b, outer=outer, K=K))
+    for masks in (False, True):
+        codes, scales = ah.adahop_iht_quantize(x, b, torch.from_numpy(zo).cuda() if masks else None,
+                                               torch.from_numpy(zk).cuda() if masks else None)
+        torch.cuda.synchronize()
+        rc, rs = orc.iht_quantize(arr[:, :width], False, b, zo if masks else None, zk if masks else None)
+        assert np.array_equal(host(scales), rs)
+        assert np.array_equal(host(codes), rc)
+
+
 def test_quantize_mx_every_bf16_pattern_bit_exact(ah):
     """Every finite bf16 value, placed so that it lands in each E2M1 binade (and in the saturating
     range) relative to the block scale set by an anchor element."""
