@@ -666,7 +666,7 @@ __global__ __launch_bounds__(256) void k_quant_kc16_gather(const uint16_t *__res
 // exactly once; the 16-byte writes of a 16-lane group go to two rows whose banks do not overlap either.
 // ------------------------------------------------------------------------------------------------
 constexpr int KS_COLS = 64, KT_PITCH = 144;
-constexpr unsigned KS_GROUP = 32, KS_GROUP_FROM = 256; // column tiles that walk the K-blocks together; from how many on
+constexpr unsigned KS_GROUP = 32, KS_GROUP_FROM = 200; // column tiles that walk the K-blocks together; from how many on
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 
@@ -713,10 +713,11 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
     // tiles of one K-block before the next K-block: the workgroups in flight together then write 128-byte pieces of
     // thousands of different output rows.  Instead the index walks KS_GROUP neighbouring column tiles through all
     // K-blocks before it moves to the next group: the reads still come in pieces of KS_GROUP x 128 bytes of a K-row, and
-    // an output row is written in one go.  Measured (block 256): operands with rows of 28672 elements (448 column
-    // tiles: about 1000 workgroups in flight span two K-blocks) 292 -> 237 us ([16384][28672]) and 133 -> 122 us
-    // ([8192][28672]); with rows of 8192 and 16384 elements (in flight: 8 and 4 K-blocks) the plain order is 2 .. 5 %
-    // faster and is kept (group == 0).
+    // an output row is written in one go.  Measured: operands with rows of 28672 elements (448 column tiles: the
+    // about 1000 workgroups in flight span two K-blocks, 300 bytes of an output row) 292 -> 237 us ([16384][28672])
+    // and 133 -> 122 us ([8192][28672]); 384, 320 and 224 column tiles 11 .. 13 % faster; 256 column tiles 7 % faster
+    // or 5 % slower by K; with 192 column tiles and fewer the plain order is as fast or up to 10 % faster and is kept
+    // (group == 0).
     unsigned bx = blockIdx.x, by = blockIdx.y;
     if (group) {
         const uint64_t nx = gridDim.x, ny = gridDim.y, L = by * nx + bx, full = nx / group * group;
