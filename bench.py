@@ -495,7 +495,7 @@ def main():
                     sweep.append({"name": p.g.name, "strategy": inputs.STRATEGY_NAMES[p.g.strategy], "k_pct": pc, "k": k,
                                   "ms": t, "ms_iht_only": t0, "oe_overhead_pct": 100.0 * (t - t0) / t0})
             extras["cfg4_k_sweep"] = sweep
-            extras["per_stage_ms"] = [stage_times(ah, torch, inputs, p, ws) for p in prepared[:2]]
+            extras["per_stage_ms"] = [stage_times(ah, torch, inputs, p, ws) for p in prepared]
         elif args.workload == "paper-table3":
             # the stages of the paper's kernel latency table (right): FOID | IHT and quantise | fused product with the
             # BF16 outlier part and its scatter

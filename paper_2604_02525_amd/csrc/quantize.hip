@@ -496,24 +496,32 @@ __device__ __forceinline__ void apply_k_mask(float (&w)[8], uint64_t zm)
         if ((zm >> (8 * i)) & 0xffu) w[i] = 0.0f;
 }
 
-// Of 8 consecutive K-elements (raw bf16 in r), the extracted ones go to their positions of the row's copy;
-// pos holds position + 1 per element as 16 bits, 0 for an element that stays.
-__device__ __forceinline__ void scatter_extracted(uint4 r, uint4 pos, uint16_t *dst)
+// Of 8 consecutive K-elements (raw bf16 in r), all go to slot[pos1] of the row's copy, pos1 being position + 1 for an
+// extracted element and 0 for one that stays: slot 0 takes what is not extracted and is never read, so that no
+// store needs a condition of its own (eight predicated stores cost three times the instructions).
+constexpr int KC_GATHER_SLOT0 = 7; // index of slot 0 in the LDS array: the copy proper starts 16-byte aligned behind it
+
+__device__ __forceinline__ void scatter_extracted(uint4 r, uint4 pos, uint16_t *slot)
 {
     const uint32_t e[4] = {r.x, r.y, r.z, r.w}, q[4] = {pos.x, pos.y, pos.z, pos.w};
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t p1 = (q[i >> 1] >> (16 * (i & 1))) & 0xffffu;
-        if (p1) dst[p1 - 1] = (uint16_t)(e[i >> 1] >> (16 * (i & 1)));
+    for (int j = 0; j < 4; ++j) {
+        slot[q[j] & 0xffffu] = (uint16_t)e[j];
+        slot[q[j] >> 16] = (uint16_t)(e[j] >> 16);
     }
 }
 
-__device__ __forceinline__ void zero_extracted(float (&w)[8], uint4 pos)
+// The raw bf16 pairs with the extracted elements (pos1 != 0) cleared to +0: per 16-bit half, min(pos1, 1) - 1 is
+// 0xffff for an element that stays and 0 for an extracted one.
+__device__ __forceinline__ uint4 clear_extracted(uint4 r, uint4 pos)
 {
-    const uint32_t q[4] = {pos.x, pos.y, pos.z, pos.w};
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        if ((q[i >> 1] >> (16 * (i & 1))) & 0xffffu) w[i] = 0.0f;
+    const uint32_t ones = 0x00010001u;
+    auto keep = [&](uint32_t q) { // (the compiler's own code for this is a compare and a select per half)
+        uint32_t t;
+        asm("v_pk_min_u16 %0, %1, %2\n\tv_pk_sub_u16 %0, %0, %2" : "=&v"(t) : "v"(q), "v"(ones));
+        return t;
+    };
+    return make_uint4(r.x & keep(pos.x), r.y & keep(pos.y), r.z & keep(pos.z), r.w & keep(pos.w));
 }
 
 // k0: start of the lane group's 256 K-elements (a multiple of 256).  sm: optional second copy of the scales in
@@ -589,10 +597,14 @@ __global__ __launch_bounds__(256) void k_quant_kc16(const uint16_t *__restrict__
 // takes a whole row, 4096 K-elements per pass.  In place of the byte mask it reads a 16-bit table, position in the
 // index list + 1 for an extracted channel and 0 for the others, with the operand (one more coalesced load, no
 // dependent look-ups); the extracted elements it meets go to those positions of a copy of the row's extracted part
-// in LDS, which leaves for memory at the end in whole 16-byte pieces.
+// in LDS, which leaves for memory at the end in whole 16-byte pieces; they are cleared in the raw bf16 pairs with three
+// packed 16-bit instructions per pair.
 // (Two variants were measured on 16384 x 28672 at 1 % and made the quantiser half again as slow, more than the
 // separate gather kernel costs: 2-byte stores straight into the copy, and a look-up of the position in a 32-bit
-// table under the branch that an extracted element takes -- a chain of dependent loads in nearly every wave.)
+// table under the branch that an extracted element takes -- a chain of dependent loads in nearly every wave.
+// What the kernel costs over the plain one, 10 .. 20 %, is not its instructions: with a fifth fewer of them, and
+// with the next pass's loads issued ahead, it took the same time; without the table loads 4 .. 37 us of the 14 .. 50
+// go away, most on the 57 KB table of K = 28672, which every workgroup reads whole.)
 constexpr int KC_GATHER_MAX_KPAD = 4096;
 
 template <int B, bool SR>
@@ -600,7 +612,8 @@ __global__ __launch_bounds__(256) void k_quant_kc16_gather(const uint16_t *__res
                                                            uint8_t *__restrict__ codes, uint8_t *__restrict__ scales,
                                                            sr_key_t key, scales_sm_t sm, k_gather_t gk)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t part[KC_GATHER_MAX_KPAD];
+    __shared__ __attribute__((aligned(16))) uint16_t lds[8 + KC_GATHER_MAX_KPAD];
+    uint16_t *slot = lds + KC_GATHER_SLOT0, *part = lds + 8; // part[t] = slot[t + 1]
     const uint32_t upr = (uint32_t)(K >> 8);
     const int64_t row = blockIdx.x;
     const lane_plan_t plan = make_plan<B>(threadIdx.x & 63);
@@ -617,18 +630,14 @@ __global__ __launch_bounds__(256) void k_quant_kc16_gather(const uint16_t *__res
             p0 = *reinterpret_cast<const uint4 *>(gk.pos1 + kk);
             p1 = *reinterpret_cast<const uint4 *>(gk.pos1 + kk + 128);
         }
+        if (p0.x | p0.y | p0.z | p0.w) scatter_extracted(r0, p0, slot);
+        if (p1.x | p1.y | p1.z | p1.w) scatter_extracted(r1, p1, slot);
+        r0 = clear_extracted(r0, p0);
+        r1 = clear_extracted(r1, p1);
         float w0[8] = {bf16_lo(r0.x), bf16_hi(r0.x), bf16_lo(r0.y), bf16_hi(r0.y),
                        bf16_lo(r0.z), bf16_hi(r0.z), bf16_lo(r0.w), bf16_hi(r0.w)};
         float w1[8] = {bf16_lo(r1.x), bf16_hi(r1.x), bf16_lo(r1.y), bf16_hi(r1.y),
                        bf16_lo(r1.z), bf16_hi(r1.z), bf16_lo(r1.w), bf16_hi(r1.w)};
-        if (p0.x | p0.y | p0.z | p0.w) {
-            zero_extracted(w0, p0);
-            scatter_extracted(r0, p0, part);
-        }
-        if (p1.x | p1.y | p1.z | p1.w) {
-            zero_extracted(w1, p1);
-            scatter_extracted(r1, p1, part);
-        }
         uint32_t c0, c1;
         int s0, s1;
         transform_quantize16<B, SR>(w0, w1, plan, c0, c1, s0, s1, key, row, kk, kk + 128);
