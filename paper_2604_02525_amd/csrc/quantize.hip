@@ -717,6 +717,7 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
                                                     sr_key_t key, scales_sm_t sm, unsigned group)
 {
     __shared__ __attribute__((aligned(16))) uint8_t tile[256 * KT_PITCH];
+    __shared__ uint8_t kmask[256];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     // Workgroups start in the order of their linear index, x fastest.  Taken as it is, that order runs all column
     // tiles of one K-block before the next K-block: the workgroups in flight together then write 128-byte pieces of
@@ -766,16 +767,21 @@ __global__ __launch_bounds__(256) void k_quant_ks16(const uint16_t *__restrict__
                 if ((z >> (8 * c)) & 0xffu) cm[c >> 1] &= (c & 1) ? 0x0000ffffu : 0xffff0000u;
         }
         uint4 v[8];
-        uint32_t zk = 0; // bit it: the lane's K-row of pass it is masked out (looked at when the row goes to LDS, so
-                         // that neither these loads nor the data loads wait for one another)
-        if (zero_k) {
-#pragma unroll
-            for (int it = 0; it < 8; ++it) zk |= (zero_k[k0 + it * 32 + rw] ? 1u : 0u) << it;
-        }
+        // K-mask: one byte of the tile's 256 per thread, loaded ahead of the data and handed round through LDS (eight
+        // byte loads per lane, one for each of its K-rows, made the masked call 15 % slower than the plain one)
+        uint8_t my_kz = 0;
+        if (zero_k) my_kz = zero_k[k0 + tid];
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int64_t kk = k0 + it * 32 + rw;
             v[it] = ok ? load_once16(x + kk * ld + oc) : make_uint4(0, 0, 0, 0);
+        }
+        uint32_t zk = 0; // bit it: the lane's K-row of pass it is masked out
+        if (zero_k) {    // (uniform: a kernel argument)
+            kmask[tid] = my_kz;
+            __syncthreads();
+#pragma unroll
+            for (int it = 0; it < 8; ++it) zk |= (kmask[it * 32 + rw] ? 1u : 0u) << it;
         }
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
